@@ -1,0 +1,210 @@
+/*
+ * pacer.h -- C ABI of the MI355X (gfx950) hot path of Pacer adaptive speculative decoding
+ * (Zhang et al., "Pacer: Blockwise Pre-verification for Speculative Decoding with Adaptive
+ * Length").  One decoding step of the paper's Alg. 1 is four calls:
+ *
+ *     pacer_draft_step        x b      Eq. 3 / Eq. 6   one draft-model token
+ *     pacer_preverify_block            Eq. 7 + the halting test of Alg. 1's inner loop
+ *       ... repeated while the block passes ...
+ *     pacer_verify                     Eq. 4           one target pass over the drafts
+ *     pacer_accept_rollback            Eq. 5 + the verification part of Alg. 1
+ *
+ * Conventions
+ *   - Every pointer named dev_* is DEVICE memory, everything else is HOST memory.
+ *   - The library allocates no device memory.  Weights, KV caches, the workspace and every
+ *     output buffer are owned by the caller and only BORROWED for the life of the context;
+ *     the caller frees them after pacer_destroy.
+ *   - All work is enqueued on the HIP stream given to pacer_create.  Hot calls do not
+ *     synchronise with the host, except where a call says so.
+ *   - Every call returns a status: 0 = PACER_OK, negative = error (arguments are validated
+ *     on the host before anything is enqueued, so a failed call has no effect on device state).
+ *     pacer_last_error gives a static, human readable string for the context's last failure.
+ *   - A context is bound to one device and one stream and is not thread safe.
+ *   - Token ids are int32.  Sequences are numbered 0..max_batch-1.
+ *
+ * Model: Llama-style decoder (pre-norm RMSNorm, rotate-half RoPE at absolute positions,
+ * causal multi-head attention, SwiGLU).  The pre-verification layer M_B is one such layer of
+ * the draft model's width over its own KV cache, a final RMSNorm and a 2-class head; its input
+ * row j is  hidden_j + PosEmb[draft position]  (Sec. 3.2).  Prefix rows use PosEmb row 0.
+ */
+#ifndef PACER_H
+#define PACER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PACER_OK 0
+#define PACER_EINVAL (-1)     /* bad argument: null pointer, bad shape, bad sequence id, bad mode */
+#define PACER_ESTATE (-2)     /* call out of order, tensor / cache / workspace not bound          */
+#define PACER_EOVERFLOW (-3)  /* KV capacity (max_seq) or gamma_max would be exceeded             */
+#define PACER_EHIP (-4)       /* the HIP runtime reported an error                                */
+
+#define PACER_F32 0
+#define PACER_BF16 1
+
+#define PACER_TARGET 0
+#define PACER_DRAFT 1
+#define PACER_PREVERIFY 2
+
+#define PACER_GREEDY 0
+#define PACER_SAMPLE 1
+
+#define PACER_MAX_BATCH 16
+
+/* tensor ids for pacer_bind; "layer" is ignored for the per-model tensors */
+#define PACER_T_EMBED 0       /* [vocab][d]        model dtype, row major (TARGET, DRAFT)        */
+#define PACER_T_FINAL_NORM 1  /* [d]               f32                                           */
+#define PACER_T_HEAD 2        /* [vocab][d]        matrix (TARGET, DRAFT)                        */
+#define PACER_T_ATTN_NORM 3   /* [d]               f32, per layer                                */
+#define PACER_T_WQKV 4        /* [3d][d]           matrix, rows = Wq then Wk then Wv, per layer  */
+#define PACER_T_WO 5          /* [d][d]            matrix, per layer                             */
+#define PACER_T_FFN_NORM 6    /* [d]               f32, per layer                                */
+#define PACER_T_WGU 7         /* [2*d_ffn][d]      matrix, rows = W_gate then W_up, per layer    */
+#define PACER_T_WD 8          /* [d][d_ffn]        matrix, per layer                             */
+#define PACER_T_POSEMB 9      /* [gamma_max+1][d]  f32, PREVERIFY only; row 0 must be zero       */
+#define PACER_T_CLS 10        /* [2][d]            f32, PREVERIFY only: logits of reject/accept  */
+#define PACER_T_COUNT 11
+/*
+ * "matrix" tensors are [out][in] (y = W x).  For a PACER_F32 model they are plain row-major
+ * f32.  For a PACER_BF16 model they must be in the tiled layout written by pacer_pack_weight
+ * (same byte count as the row-major bf16 matrix); out must be a multiple of 16 and in a
+ * multiple of 32.
+ */
+
+typedef struct pacer_ctx pacer_ctx;
+
+typedef struct {
+  int32_t n_layers, d_model, n_heads, head_dim /* 64 or 128 */, d_ffn, vocab, max_seq;
+  float rope_theta, rms_eps;
+  int32_t dtype; /* PACER_F32 or PACER_BF16: type of matrices, embedding and KV cache */
+} pacer_model_cfg;
+
+/* Inputs of Alg. 1: block size b, initial threshold t, growth factor rho; gamma_max caps the
+ * window (the paper's inner loop has no cap) and must be a multiple of block. */
+typedef struct {
+  int32_t block, gamma_max;
+  float t0, rho;
+} pacer_pv_cfg;
+
+/* ---- set-up (not hot) ---------------------------------------------------------------- */
+
+/* Creates a context.  Touches no GPU.  The pre-verification layer has the draft's d_model,
+ * n_heads, head_dim, d_ffn, dtype and max_seq.  hip_stream: a hipStream_t (may be 0). */
+int32_t pacer_create(pacer_ctx** out, const pacer_model_cfg* target, const pacer_model_cfg* draft,
+                     const pacer_pv_cfg* pv, int32_t max_batch, void* hip_stream);
+void pacer_destroy(pacer_ctx* ctx);
+const char* pacer_last_error(const pacer_ctx* ctx);
+
+/* Re-tiles a row-major bf16 matrix [n_out][n_in] (dev_src) into the layout the bf16 kernels
+ * stream (dev_dst, same size, must not alias).  Enqueued on hip_stream. */
+int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int32_t n_in,
+                          void* hip_stream);
+
+/* Borrow one weight tensor.  nbytes must equal the tensor's size for the model's shape. */
+int32_t pacer_bind(pacer_ctx* ctx, int32_t which, int32_t tensor_id, int32_t layer,
+                   const void* dev_ptr, uint64_t nbytes);
+
+/* KV cache of one model for all max_batch sequences:
+ * [max_batch][n_layers][2 (K,V)][max_seq][d_model] in the model dtype.  Contents need not be
+ * initialised.  pacer_kv_bytes returns the exact size pacer_bind_kv expects. */
+uint64_t pacer_kv_bytes(const pacer_ctx* ctx, int32_t which);
+int32_t pacer_bind_kv(pacer_ctx* ctx, int32_t which, void* dev_ptr, uint64_t nbytes);
+
+/* Scratch memory for activations, draft logits, committed tokens, attention partials.
+ * Must be 256-byte aligned and at least pacer_workspace_bytes large.  Binding it is the call
+ * that first touches the GPU (it also allocates a few hundred bytes of pinned host memory
+ * through which pacer_accept_rollback reports its results). */
+uint64_t pacer_workspace_bytes(const pacer_ctx* ctx);
+int32_t pacer_bind_workspace(pacer_ctx* ctx, void* dev_ptr, uint64_t nbytes);
+
+/* Prompt ingestion (support; Alg. 1 takes the prefix as given).  Resets sequence `seq` to the
+ * committed tokens dev_tokens[0..n-1], n >= 1, and fills the three caches for positions
+ * 0..n-2 (M_B with prefix rows). */
+int32_t pacer_prefill(pacer_ctx* ctx, int32_t seq, const int32_t* dev_tokens, int32_t n);
+
+/* Debug / teacher forcing: replace the committed tokens of `seq` from position `from` on with
+ * host_tokens[0..n-1] and set the committed length to from+n.  Valid only if all three caches
+ * already hold correct rows for positions < from+n-1 (e.g. directly after a step whose first
+ * from+n-1 positions agree).  Synchronises. */
+int32_t pacer_force_commit(pacer_ctx* ctx, int32_t seq, int32_t from, const int32_t* host_tokens,
+                           int32_t n);
+
+/* ---- the hot path -------------------------------------------------------------------- */
+
+/* Start of one outer iteration of Alg. 1 for `seq`: threshold <- t0, draft position <- 1,
+ * no drafts.  Waits for the sequence's previous pacer_accept_rollback, if its result has not
+ * been collected yet (pacer_get_state collects it as well). */
+int32_t pacer_begin_step(pacer_ctx* ctx, int32_t seq);
+
+/* Eq. 3 / Eq. 6: one draft-model forward per listed sequence on its newest token (the last
+ * committed token, or the previous draft), appending to the draft KV cache.  Keeps the logits
+ * q_i (f32 [vocab]) and the hidden state h_i (final-norm output, f32 [d]) in the workspace and
+ * picks y_i = argmax (PACER_GREEDY; lowest id wins ties) or y_i ~ softmax (PACER_SAMPLE,
+ * Gumbel-max on Philox-4x32-10 keyed by rng_seed; rng_ctr = index of the decoding step).
+ * PACER_EOVERFLOW if the sequence already holds gamma_max drafts. */
+int32_t pacer_draft_step(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, int32_t mode,
+                         uint64_t rng_seed, uint64_t rng_ctr);
+
+/* Eq. 7 and the halting test: runs M_B on the last `block` hidden states (+ their draft
+ * position embeddings) of each listed sequence, appends to M_B's KV cache, writes
+ * dev_alpha[n_seqs][block] (estimated acceptance rates), dev_stop[n_seqs] = (mean alpha <= t)
+ * evaluated in f32, then multiplies the sequence's threshold by rho.  dev_alpha / dev_stop may
+ * be read after synchronising the stream.  PACER_ESTATE unless exactly `block` new drafts
+ * exist since the last call. */
+int32_t pacer_preverify_block(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs,
+                              float* dev_alpha, int32_t* dev_stop);
+
+/* Eq. 4: one target pass over [last committed token, y_1..y_gamma] of each listed sequence
+ * against its KV cache (appending those rows).  gamma = number of drafts since
+ * pacer_begin_step, or gamma_override[s] if gamma_override != NULL and >= 0 (host array; must
+ * not exceed the number of drafts made).  Writes f32 logits to
+ * dev_logits[n_seqs][gamma_max+1][vocab] (rows beyond gamma+1 are left untouched). */
+int32_t pacer_verify(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs,
+                     const int32_t* gamma_override, float* dev_logits);
+
+/* Eq. 5 and the rest of Alg. 1: with effective target logits  l_T + beta[s] * l_D  (beta:
+ * host array [n_seqs]; 0 gives the paper's plain rule), PACER_GREEDY accepts the leading drafts
+ * equal to the effective argmax and emits the argmax at the first mismatch (or of the bonus
+ * row); PACER_SAMPLE accepts y_i while r_i <= p_i[y_i]/q_i[y_i], then samples from
+ * norm(max(0, p - q)) at the first rejection or from p_{gamma+1}.  Runs the draft forward on
+ * y_gamma that the all-accepted case needs (it also yields the draft logits of the bonus row)
+ * and extends M_B's cache over positions that no pacer_preverify_block covered.  Appends
+ * y_1..y_n and the new token to the committed tokens; all three caches then logically hold
+ * committed_length-1 positions (rollback = shorter length, nothing is erased).
+ * dev_logits: the buffer pacer_verify wrote.  dev_n_accepted[n_seqs], dev_next_token[n_seqs]
+ * receive n and the new token; the same values reach the host through pacer_get_state. */
+int32_t pacer_accept_rollback(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, int32_t mode,
+                              const float* beta, uint64_t rng_seed, uint64_t rng_ctr,
+                              const float* dev_logits, int32_t* dev_n_accepted,
+                              int32_t* dev_next_token);
+
+/* Synchronises the stream, folds a pending accept result into the host-side state and
+ * reports: gamma (drafts of the current/last step), len (committed tokens), t (current
+ * threshold), n_accepted / next_token of the last finished step (-1 if none).  Any output
+ * pointer may be NULL. */
+int32_t pacer_get_state(pacer_ctx* ctx, int32_t seq, int32_t* gamma, int32_t* len, float* t,
+                        int32_t* n_accepted, int32_t* next_token);
+
+/* ---- test taps (not hot) ------------------------------------------------------------- */
+#define PACER_PEEK_DRAFT_LOGITS 0 /* f32 [gamma_max+1][vocab]  row j = logits of draft forward j */
+#define PACER_PEEK_DRAFT_HIDDEN 1 /* f32 [gamma_max+1][d_draft]                                   */
+#define PACER_PEEK_DRAFT_TOKENS 2 /* i32 [gamma_max+1]                                            */
+#define PACER_PEEK_TOKENS 3       /* i32 [max_seq] committed tokens                               */
+/* Device pointer (inside the workspace) of a per-sequence buffer; valid while bound. */
+int32_t pacer_peek(pacer_ctx* ctx, int32_t seq, int32_t what, void** dev_ptr, uint64_t* nbytes);
+
+/* Kernel timing for benchmarks: while enabled, every launch of the weight-streaming GEMM is
+ * bracketed by HIP events on the context's stream.  pacer_profile_read synchronises and returns
+ * the number of launches, their summed duration and the summed weight bytes they streamed, then
+ * clears the counters. */
+int32_t pacer_profile_enable(pacer_ctx* ctx, int32_t on);
+int32_t pacer_profile_read(pacer_ctx* ctx, int64_t* n_launches, double* total_ms,
+                           double* weight_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PACER_H */

@@ -1,0 +1,759 @@
+// Device kernels of the Pacer hot path for gfx950 (CDNA4, wave64).
+//
+// Data layout conventions used by every kernel in this file
+//   activations ........ f32 [rows][width], row major
+//   packed activations . f16 operand tiles for the MFMA GEMM: tile (kt, mt) holds rows
+//                        mt*16..+15 and features kt*32..+31; inside a tile lane l = 16*g + j
+//                        owns row j and the 8 features 8*g..8*g+7 (16 bytes), so one wave
+//                        loads a tile with a single fully coalesced 1 KiB read.
+//   packed weights ..... bf16, same tiling: tile (nt, kt) holds outputs nt*16..+15 and inputs
+//                        kt*32..+31, tiles ordered [nt][kt], so a wave that walks along K for
+//                        one output tile reads one contiguous stream.
+//   KV cache ........... [seq][layer][K|V][position][d_model]
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define PK_MAXB 16
+#define ATT_MAXR 32   // rows of one sequence in one attention launch
+#define ATT_TILE 64   // keys per LDS tile
+
+// Rows of a launch: sequence si (slot in the call's list) owns rows row_off[si]..row_off[si+1]-1
+// at consecutive absolute positions starting at pos0[si]; len[si] = committed tokens.
+struct SeqRows {
+  int n_seqs;
+  int seq[PK_MAXB];
+  int row_off[PK_MAXB + 1];
+  int pos0[PK_MAXB];
+  int len[PK_MAXB];
+};
+
+__device__ __forceinline__ int find_seq(const SeqRows& sr, int r) {
+  int s = 0;
+  while (s + 1 < sr.n_seqs && sr.row_off[s + 1] <= r) ++s;
+  return s;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);   // round to nearest even
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float ld_f32(const T* p);
+template <> __device__ __forceinline__ float ld_f32<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ld_f32<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ __forceinline__ void st_f32(T* p, float v);
+template <> __device__ __forceinline__ void st_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Block-wide sum in a fixed order (deterministic).  red: LDS scratch of >= 16 floats.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  v = wave_sum(v);
+  __syncthreads();
+  if (lane == 0) red[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+__device__ __forceinline__ float block_max(float v, float* red) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  v = wave_max(v);
+  __syncthreads();
+  if (lane == 0) red[w] = v;
+  __syncthreads();
+  float t = red[0];
+  for (int i = 1; i < nw; ++i) t = fmaxf(t, red[i]);
+  return t;
+}
+// Block-wide argmax; the lowest index wins among equal values.  Result valid in all threads.
+__device__ __forceinline__ void block_argmax(float& v, int& idx, float* redv, int* redi) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(v, o, 64);
+    int oi = __shfl_xor(idx, o, 64);
+    if (ov > v || (ov == v && oi < idx)) { v = ov; idx = oi; }
+  }
+  __syncthreads();
+  if (lane == 0) { redv[w] = v; redi[w] = idx; }
+  __syncthreads();
+  v = redv[0]; idx = redi[0];
+  for (int i = 1; i < nw; ++i)
+    if (redv[i] > v || (redv[i] == v && redi[i] < idx)) { v = redv[i]; idx = redi[i]; }
+}
+
+// ------------------------------------------------------------------ Philox-4x32-10
+// Salmon et al., "Parallel random numbers: as easy as 1, 2, 3" (SC'11).
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+    c = make_uint4(hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0);
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c;
+}
+// uniform in (0,1), exactly representable in f32: ((bits >> 9) + 0.5) * 2^-23
+__device__ __forceinline__ float u01(uint32_t bits) { return ((float)(bits >> 9) + 0.5f) * 1.1920928955078125e-07f; }
+__device__ __forceinline__ float gumbel(float u) { return -logf(-logf(u)); }
+#define PURPOSE_DRAFT 0u
+#define PURPOSE_ACCEPT 1u
+#define PURPOSE_NEXT 2u
+// four uniforms for vocabulary ids 4*blk..4*blk+3
+__device__ __forceinline__ uint4 vocab_bits(uint64_t seed, int seq, uint32_t step, uint32_t row, uint32_t purpose, uint32_t blk) {
+  return philox4x32_10(make_uint4(blk, row, step, purpose | ((uint32_t)seq << 8)), (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+// ------------------------------------------------------------------ weight re-tiling
+__global__ void pack_weight_kernel(uint4* __restrict__ dst, const uint16_t* __restrict__ src, int N, int K) {
+  const int KT = K >> 5;
+  const size_t total = (size_t)(N >> 4) * KT * 64;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(i & 63);
+    const size_t tile = i >> 6;
+    const int kt = (int)(tile % KT);
+    const int nt = (int)(tile / KT);
+    const uint16_t* p = src + (size_t)(nt * 16 + (lane & 15)) * K + kt * 32 + (lane >> 4) * 8;
+    dst[i] = *reinterpret_cast<const uint4*>(p);
+  }
+}
+
+// ------------------------------------------------------------------ embedding gather
+// token of (sequence, position): committed token below len, else the draft made at that position
+template <typename T>
+__global__ void embed_rows_kernel(const T* __restrict__ E, const int* __restrict__ tokens, const int* __restrict__ draft_tok,
+                                  SeqRows sr, int max_seq, int G1, int d, float* __restrict__ x, int ldx) {
+  const int r = blockIdx.x;
+  const int si = find_seq(sr, r);
+  const int s = sr.seq[si];
+  const int p = sr.pos0[si] + (r - sr.row_off[si]);
+  const int tok = p < sr.len[si] ? tokens[(size_t)s * max_seq + p] : draft_tok[s * G1 + (p - sr.len[si])];
+  const T* e = E + (size_t)tok * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) x[(size_t)r * ldx + k] = ld_f32<T>(e + k);
+}
+
+// input rows of the pre-verification layer: hidden + PosEmb[e] (e = 0 for prefix rows)
+struct MbRows { int src_row0[PK_MAXB]; int e0[PK_MAXB]; };
+__global__ void mb_input_kernel(const float* __restrict__ src, int lds, const float* __restrict__ posemb, SeqRows sr, MbRows mr,
+                                int d, float* __restrict__ x, int ldx) {
+  const int r = blockIdx.x;
+  const int si = find_seq(sr, r);
+  const int rr = r - sr.row_off[si];
+  const float* h = src + (size_t)(mr.src_row0[si] + rr) * lds;
+  const float* e = posemb + (size_t)(mr.e0[si] < 0 ? 0 : mr.e0[si] + rr) * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) x[(size_t)r * ldx + k] = h[k] + e[k];
+}
+
+// ------------------------------------------------------------------ packing helpers
+// store 8 consecutive features k0..k0+7 of row m into the packed f16 operand
+__device__ __forceinline__ void store_packed8(_Float16* __restrict__ xp, int MT_total, int m, int k0, const float* v) {
+  const int kt = k0 >> 5, g = (k0 & 31) >> 3;
+  const int mt = m >> 4, j = m & 15;
+  half8 h;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) h[i] = (_Float16)v[i];
+  *reinterpret_cast<half8*>(xp + ((size_t)(kt * MT_total + mt) * 64 + (g * 16 + j)) * 8) = h;
+}
+
+// RMSNorm of R rows; writes the normalised rows as f32 (xn), optionally scattered copies for the
+// draft's hidden-state ring (hid_out row = seq*G1 + draft index), optionally the packed f16 operand
+// (then the grid covers MT_total*16 rows and rows >= R are zero filled).
+__global__ void rmsnorm_pack_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, float eps, int R, int d,
+                                    float* __restrict__ xn, int ldxn, _Float16* __restrict__ xp, int MT_total,
+                                    float* __restrict__ hid_out, int G1, SeqRows sr) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  const int ng = d >> 3;
+  if (r >= R) {
+    const float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int kg = threadIdx.x; kg < ng; kg += blockDim.x) store_packed8(xp, MT_total, r, kg * 8, z);
+    return;
+  }
+  const float* xr = x + (size_t)r * ldx;
+  float ss = 0.f;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) { const float v = xr[k]; ss += v * v; }
+  ss = block_sum(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  float* ho = nullptr;
+  if (hid_out) {
+    const int si = find_seq(sr, r);
+    const int j = sr.pos0[si] + (r - sr.row_off[si]) - (sr.len[si] - 1);
+    ho = hid_out + (size_t)(sr.seq[si] * G1 + j) * d;
+  }
+  for (int kg = threadIdx.x; kg < ng; kg += blockDim.x) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = xr[kg * 8 + i] * inv * g[kg * 8 + i];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) xn[(size_t)r * ldxn + kg * 8 + i] = v[i];
+    if (ho) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ho[kg * 8 + i] = v[i];
+    }
+    if (xp) store_packed8(xp, MT_total, r, kg * 8, v);
+  }
+}
+
+// f32 rows -> packed f16 operand (grid: MT_total*16 rows; rows >= R zero filled)
+__global__ void pack_act_kernel(const float* __restrict__ src, int lds, int R, int K, _Float16* __restrict__ xp, int MT_total) {
+  const int r = blockIdx.x;
+  const int ng = K >> 3;
+  for (int kg = threadIdx.x; kg < ng; kg += blockDim.x) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = r < R ? src[(size_t)r * lds + kg * 8 + i] : 0.f;
+    store_packed8(xp, MT_total, r, kg * 8, v);
+  }
+}
+
+// SwiGLU: act = silu(gate) * up for gu = [gate | up] rows; f32 out + optional packed operand
+__global__ void swiglu_pack_kernel(const float* __restrict__ gu, int ldg, int R, int F, float* __restrict__ act, int lda,
+                                   _Float16* __restrict__ xp, int MT_total) {
+  const int r = blockIdx.y;
+  const int kg = blockIdx.x * blockDim.x + threadIdx.x;
+  if (kg >= (F >> 3)) return;
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (r < R) {
+      const float gt = gu[(size_t)r * ldg + kg * 8 + i], up = gu[(size_t)r * ldg + F + kg * 8 + i];
+      v[i] = gt / (1.0f + expf(-gt)) * up;
+    } else {
+      v[i] = 0.f;
+    }
+  }
+  if (r < R) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) act[(size_t)r * lda + kg * 8 + i] = v[i];
+  }
+  if (xp) store_packed8(xp, MT_total, r, kg * 8, v);
+}
+
+// ------------------------------------------------------------------ output row mapping of a GEMM
+#define ROWMAP_ID 0      // out row = r
+#define ROWMAP_RING 1    // out row = seq*G1 + draft index      (draft logits ring)
+#define ROWMAP_LIST 2    // out row = slot*G1 + row within seq  (verify logits)
+__device__ __forceinline__ int map_row(const SeqRows& sr, int mode, int G1, int r) {
+  if (mode == ROWMAP_ID) return r;
+  const int si = find_seq(sr, r);
+  const int rr = r - sr.row_off[si];
+  if (mode == ROWMAP_LIST) return si * G1 + rr;
+  return sr.seq[si] * G1 + (sr.pos0[si] + rr - (sr.len[si] - 1));
+}
+
+// ------------------------------------------------------------------ weight-streaming small-M GEMM
+// out[m][n] (+)= sum_k X[m][k] * W[n][k]  for m < R <= 16*MT, bf16 packed W, f16 packed X, f32 accumulate
+// on v_mfma_f32_16x16x32_f16.  One block = NT adjacent output tiles; its WAVES waves split K into
+// contiguous ranges, each wave streaming its part of the weight tiles straight from HBM into
+// registers (bf16 -> f16 is exact for normal-range weights), partial sums meet in LDS in a fixed order.
+__device__ __forceinline__ half8 bf16x8_to_f16x8(u32x4 w) {
+  half8 h;
+  const uint32_t u[4] = {w[0], w[1], w[2], w[3]};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xffff0000u);
+    h[2 * i] = (_Float16)lo;
+    h[2 * i + 1] = (_Float16)hi;
+  }
+  return h;
+}
+
+template <int MT, int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xp,
+                                                              float* __restrict__ out, int ldo, int R, int KT, int mt0,
+                                                              int MT_total, int accumulate, SeqRows sr, int rowmap, int G1) {
+  constexpr int U = 4;
+  __shared__ f32x4 red[WAVES][NT * MT][64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nt0 = blockIdx.x * NT;
+  const int per = (KT + WAVES - 1) / WAVES;
+  const int kb = wave * per;
+  const int ke = min(KT, kb + per);
+  f32x4 acc[NT][MT];
+#pragma unroll
+  for (int a = 0; a < NT; ++a)
+#pragma unroll
+    for (int b = 0; b < MT; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const u32x4* wp[NT];
+#pragma unroll
+  for (int a = 0; a < NT; ++a) wp[a] = Wp + (size_t)(nt0 + a) * KT * 64 + lane;
+  const u32x4* xp = Xp + (size_t)mt0 * 64 + lane;
+
+  u32x4 A0[U][NT], A1[U][NT], B0[U][MT], B1[U][MT];
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][MT], int k0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kt = k0 + u;
+      if (kt < ke) {
+#pragma unroll
+        for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + (size_t)kt * 64);
+#pragma unroll
+        for (int b = 0; b < MT; ++b) B[u][b] = xp[((size_t)kt * MT_total + b) * 64];
+      } else {
+#pragma unroll
+        for (int a = 0; a < NT; ++a) A[u][a] = zero;
+#pragma unroll
+        for (int b = 0; b < MT; ++b) B[u][b] = zero;
+      }
+    }
+  };
+  auto compute = [&](u32x4(&A)[U][NT], u32x4(&B)[U][MT]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      half8 bh[MT];
+#pragma unroll
+      for (int b = 0; b < MT; ++b) bh[b] = __builtin_bit_cast(half8, B[u][b]);
+#pragma unroll
+      for (int a = 0; a < NT; ++a) {
+        const half8 ah = bf16x8_to_f16x8(A[u][a]);
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[b], acc[a][b], 0, 0, 0);
+      }
+    }
+  };
+  load(A0, B0, kb);
+  for (int k0 = kb; k0 < ke; k0 += 2 * U) {
+    load(A1, B1, k0 + U);
+    compute(A0, B0);
+    load(A0, B0, k0 + 2 * U);
+    compute(A1, B1);
+  }
+#pragma unroll
+  for (int a = 0; a < NT; ++a)
+#pragma unroll
+    for (int b = 0; b < MT; ++b) red[wave][a * MT + b][lane] = acc[a][b];
+  __syncthreads();
+  // D tile: lane l holds column j = l%16 (the activation row) and rows 4*(l/16)..+3 (outputs)
+  for (int t = threadIdx.x; t < NT * MT * 64; t += WAVES * 64) {
+    const int l = t & 63, ab = t >> 6;
+    const int a = ab / MT, b = ab % MT;
+    f32x4 s = red[0][ab][l];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) s += red[w][ab][l];
+    const int m = (mt0 + b) * 16 + (l & 15);
+    if (m < R) {
+      const int n = (nt0 + a) * 16 + (l >> 4) * 4;
+      float* o = out + (size_t)map_row(sr, rowmap, G1, m) * ldo + n;
+      if (accumulate) {
+        const f32x4 old = *reinterpret_cast<const f32x4*>(o);
+        s += old;
+      }
+      *reinterpret_cast<f32x4*>(o) = s;
+    }
+  }
+}
+
+// Plain f32 GEMM for f32 models and tiny heads: one wave per output feature, rows in groups of 8.
+__global__ void gemm_f32_kernel(const float* __restrict__ W, const float* __restrict__ X, int ldx, float* __restrict__ out, int ldo,
+                                int R, int N, int K, int accumulate, SeqRows sr, int rowmap, int G1) {
+  const int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (n >= N) return;
+  const float* w = W + (size_t)n * K;
+  for (int r0 = 0; r0 < R; r0 += 8) {
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int k = lane; k < K; k += 64) {
+      const float wv = w[k];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (r0 + i < R) acc[i] += wv * X[(size_t)(r0 + i) * ldx + k];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float s = wave_sum(acc[i]);
+      if (lane == 0 && r0 + i < R) {
+        float* o = out + (size_t)map_row(sr, rowmap, G1, r0 + i) * ldo + n;
+        *o = accumulate ? *o + s : s;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ RoPE
+// cos/sin table [R][hd/2][2] for this launch's absolute positions, evaluated in double
+__global__ void rope_table_kernel(SeqRows sr, int hd, float theta, float* __restrict__ tab) {
+  const int r = blockIdx.x, j = threadIdx.x;
+  const int half = hd >> 1;
+  if (j >= half) return;
+  const int si = find_seq(sr, r);
+  const double pos = (double)(sr.pos0[si] + (r - sr.row_off[si]));
+  const double inv = pow((double)theta, -2.0 * (double)j / (double)hd);
+  double sn, cs;
+  sincos(pos * inv, &sn, &cs);
+  tab[((size_t)r * half + j) * 2] = (float)cs;
+  tab[((size_t)r * half + j) * 2 + 1] = (float)sn;
+}
+
+// rotate q in place, rotate k and copy v into the KV cache (rotate-half pairing j, j+hd/2)
+template <typename KVT>
+__global__ void rope_append_kernel(float* __restrict__ qkv, int ld, const float* __restrict__ tab, SeqRows sr, int d, int hd,
+                                   KVT* __restrict__ kv, int layer, int n_layers, int max_seq, int kv_only) {
+  const int r = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+  const int half = hd >> 1;
+  if (j >= half) return;
+  const int si = find_seq(sr, r);
+  const int pos = sr.pos0[si] + (r - sr.row_off[si]);
+  const float cs = tab[((size_t)r * half + j) * 2], sn = tab[((size_t)r * half + j) * 2 + 1];
+  float* row = qkv + (size_t)r * ld;
+  const int c0 = h * hd + j, c1 = c0 + half;
+  if (!kv_only) {
+    const float a = row[c0], b = row[c1];
+    row[c0] = a * cs - b * sn;
+    row[c1] = b * cs + a * sn;
+  }
+  KVT* K = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2) * (size_t)max_seq * d + (size_t)pos * d;
+  KVT* V = K + (size_t)max_seq * d;
+  const float a = row[d + c0], b = row[d + c1];
+  st_f32<KVT>(K + c0, a * cs - b * sn);
+  st_f32<KVT>(K + c1, b * cs + a * sn);
+  st_f32<KVT>(V + c0, row[2 * d + c0]);
+  st_f32<KVT>(V + c1, row[2 * d + c1]);
+}
+
+// ------------------------------------------------------------------ attention over the KV cache
+// One block = (chunk of key tiles, head, sequence).  All rows of the sequence (<= 32) share every
+// K/V tile, which is staged once in LDS.  Row r attends to keys 0..pos_r.  Online softmax over the
+// tiles of the chunk; the chunk's (max, sum, weighted values) go to `part` for attn_combine.
+template <typename KVT> struct KvWords;
+template <> struct KvWords<float> { static constexpr int per_word = 1; };
+template <> struct KvWords<uint16_t> { static constexpr int per_word = 2; };
+template <typename KVT> __device__ __forceinline__ float kv_dim(const uint32_t* row, int dim);
+template <> __device__ __forceinline__ float kv_dim<float>(const uint32_t* row, int dim) { return __uint_as_float(row[dim]); }
+template <> __device__ __forceinline__ float kv_dim<uint16_t>(const uint32_t* row, int dim) {
+  const uint32_t w = row[dim >> 1];
+  return __uint_as_float((dim & 1) ? (w & 0xffff0000u) : (w << 16));
+}
+
+template <typename KVT, int HD>
+__global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restrict__ q, int ldq, const KVT* __restrict__ kv, int layer,
+                                                           int n_layers, int max_seq, int d, SeqRows sr, int tiles_per_chunk,
+                                                           int n_chunks, int H, float* __restrict__ part) {
+  constexpr int WORDS = HD / KvWords<KVT>::per_word;   // 32-bit words per key row of one head
+  constexpr int STR = WORDS + 1;                        // odd stride: conflict-free column access
+  constexpr int DPL = HD / 64;                          // output dims per lane
+  __shared__ float Qs[ATT_MAXR][HD];
+  __shared__ uint32_t Kt[ATT_TILE * STR];
+  __shared__ uint32_t Vt[ATT_TILE * STR];
+  __shared__ float S[ATT_MAXR][ATT_TILE];
+  __shared__ float sm[ATT_MAXR], sl[ATT_MAXR], sc[ATT_MAXR];
+
+  const int chunk = blockIdx.x, h = blockIdx.y, si = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int r0 = sr.row_off[si], Rs = sr.row_off[si + 1] - r0;
+  const int pos0 = sr.pos0[si];
+  const int n_keys = pos0 + Rs;                          // keys visible to the last row
+  const int n_tiles = (n_keys + ATT_TILE - 1) / ATT_TILE;
+  const int t_begin = chunk * tiles_per_chunk, t_end = min(n_tiles, t_begin + tiles_per_chunk);
+  const float scale = 1.0f / sqrtf((float)HD);
+  const KVT* Kb = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2) * (size_t)max_seq * d + h * HD;
+  const KVT* Vb = Kb + (size_t)max_seq * d;
+
+  for (int i = tid; i < Rs * HD; i += 256) Qs[i / HD][i % HD] = q[(size_t)(r0 + i / HD) * ldq + h * HD + (i % HD)] * scale;
+  if (tid < ATT_MAXR) { sm[tid] = -INFINITY; sl[tid] = 0.f; sc[tid] = 1.f; }
+  float acc[ATT_MAXR / 4][DPL];
+#pragma unroll
+  for (int i = 0; i < ATT_MAXR / 4; ++i)
+#pragma unroll
+    for (int e = 0; e < DPL; ++e) acc[i][e] = 0.f;
+  __syncthreads();
+
+  for (int t = t_begin; t < t_end; ++t) {
+    const int key0 = t * ATT_TILE;
+    // stage K and V tiles: 16-byte global reads, 4-byte LDS writes
+    constexpr int V4 = WORDS / 4;                       // uint4 per key
+    for (int i = tid; i < ATT_TILE * V4; i += 256) {
+      const int key = i / V4, c = i % V4;
+      uint4 kq = make_uint4(0, 0, 0, 0), vq = kq;
+      if (key0 + key < n_keys) {
+        kq = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(Kb + (size_t)(key0 + key) * d) + c * 4);
+        vq = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(Vb + (size_t)(key0 + key) * d) + c * 4);
+      }
+      uint32_t* kd = Kt + key * STR + c * 4;
+      uint32_t* vd = Vt + key * STR + c * 4;
+      kd[0] = kq.x; kd[1] = kq.y; kd[2] = kq.z; kd[3] = kq.w;
+      vd[0] = vq.x; vd[1] = vq.y; vd[2] = vq.z; vd[3] = vq.w;
+    }
+    __syncthreads();
+    // scores: thread = (key, row group)
+    {
+      float s[ATT_MAXR / 4];
+#pragma unroll
+      for (int i = 0; i < ATT_MAXR / 4; ++i) s[i] = 0.f;
+      const uint32_t* krow = Kt + lane * STR;
+      for (int w = 0; w < WORDS; ++w) {
+        const uint32_t kw = krow[w];
+        if (KvWords<KVT>::per_word == 2) {
+          const float k0 = __uint_as_float(kw << 16), k1 = __uint_as_float(kw & 0xffff0000u);
+#pragma unroll
+          for (int i = 0; i < ATT_MAXR / 4; ++i) {
+            const int r = wv + 4 * i;
+            if (r < Rs) s[i] += Qs[r][2 * w] * k0 + Qs[r][2 * w + 1] * k1;
+          }
+        } else {
+          const float k0 = __uint_as_float(kw);
+#pragma unroll
+          for (int i = 0; i < ATT_MAXR / 4; ++i) {
+            const int r = wv + 4 * i;
+            if (r < Rs) s[i] += Qs[r][w] * k0;
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < ATT_MAXR / 4; ++i) {
+        const int r = wv + 4 * i;
+        if (r < Rs) S[r][lane] = (key0 + lane <= pos0 + r) ? s[i] : -INFINITY;
+      }
+    }
+    __syncthreads();
+    // online softmax: wave wv owns rows wv, wv+4, ...; lane = key
+    for (int r = wv; r < Rs; r += 4) {
+      const float sv = S[r][lane];
+      const float mo = sm[r];
+      const float mn = fmaxf(mo, wave_max(sv));
+      const float p = (mn == -INFINITY) ? 0.f : expf(sv - mn);
+      const float ps = wave_sum(p);
+      S[r][lane] = p;
+      if (lane == 0) {
+        const float corr = (mo == -INFINITY) ? 1.f : expf(mo - mn);
+        sc[r] = corr;
+        sl[r] = sl[r] * corr + ps;
+        sm[r] = mn;
+      }
+    }
+    __syncthreads();
+    // weighted values: thread = (dims lane*DPL.., row group)
+#pragma unroll
+    for (int i = 0; i < ATT_MAXR / 4; ++i) {
+      const int r = wv + 4 * i;
+      if (r < Rs) {
+        const float c = sc[r];
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) acc[i][e] *= c;
+      }
+    }
+    for (int key = 0; key < ATT_TILE; ++key) {
+      float vv[DPL];
+#pragma unroll
+      for (int e = 0; e < DPL; ++e) vv[e] = kv_dim<KVT>(Vt + key * STR, lane * DPL + e);
+#pragma unroll
+      for (int i = 0; i < ATT_MAXR / 4; ++i) {
+        const int r = wv + 4 * i;
+        if (r < Rs) {
+          const float p = S[r][key];
+#pragma unroll
+          for (int e = 0; e < DPL; ++e) acc[i][e] += p * vv[e];
+        }
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < ATT_MAXR / 4; ++i) {
+    const int r = wv + 4 * i;
+    if (r < Rs) {
+      float* o = part + (((size_t)(r0 + r) * H + h) * n_chunks + chunk) * (HD + 2);
+#pragma unroll
+      for (int e = 0; e < DPL; ++e) o[lane * DPL + e] = acc[i][e];
+      if (lane == 0) { o[HD] = sm[r]; o[HD + 1] = sl[r]; }
+    }
+  }
+}
+
+// merge the chunks' partial softmaxes: grid (rows, heads), block HD threads
+__global__ void attn_combine_kernel(const float* __restrict__ part, int n_chunks, int H, int HD, float* __restrict__ out, int ldo) {
+  const int r = blockIdx.x, h = blockIdx.y, dim = threadIdx.x;
+  const float* p = part + ((size_t)r * H + h) * n_chunks * (HD + 2);
+  float M = -INFINITY;
+  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, p[(size_t)c * (HD + 2) + HD]);
+  float L = 0.f, a = 0.f;
+  for (int c = 0; c < n_chunks; ++c) {
+    const float m = p[(size_t)c * (HD + 2) + HD];
+    if (m == -INFINITY) continue;
+    const float w = expf(m - M);
+    L += p[(size_t)c * (HD + 2) + HD + 1] * w;
+    a += p[(size_t)c * (HD + 2) + dim] * w;
+  }
+  out[(size_t)r * ldo + h * HD + dim] = a / L;
+}
+
+// ------------------------------------------------------------------ token choice of the draft model
+// one block per listed sequence: y = argmax(logits) or Gumbel-max sample; row j of the ring
+struct PickArgs { int n_seqs; int seq[PK_MAXB]; int j[PK_MAXB]; };
+__global__ __launch_bounds__(1024) void pick_token_kernel(const float* __restrict__ ring, int* __restrict__ draft_tok, PickArgs pa,
+                                                          int G1, int V, int mode, uint64_t seed, uint32_t step) {
+  __shared__ float redv[16];
+  __shared__ int redi[16];
+  const int si = blockIdx.x, s = pa.seq[si], j = pa.j[si];
+  const float* lg = ring + (size_t)(s * G1 + j) * V;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int blk = threadIdx.x; blk * 4 < V; blk += blockDim.x) {
+    float g4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (mode) {
+      const uint4 b = vocab_bits(seed, s, step, (uint32_t)(j + 1), PURPOSE_DRAFT, (uint32_t)blk);
+      g4[0] = gumbel(u01(b.x)); g4[1] = gumbel(u01(b.y)); g4[2] = gumbel(u01(b.z)); g4[3] = gumbel(u01(b.w));
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int v = blk * 4 + e;
+      if (v < V) {
+        const float val = lg[v] + g4[e];
+        if (val > best) { best = val; bi = v; }
+      }
+    }
+  }
+  block_argmax(best, bi, redv, redi);
+  if (threadIdx.x == 0) draft_tok[s * G1 + j] = bi;
+}
+
+// ------------------------------------------------------------------ pre-verification head + halting test
+// xn: final-norm output of M_B, rows grouped per sequence (b rows each).  alpha_j = softmax(z)[1]
+// = 1/(1+exp(z0-z1)); stop = (mean alpha <= t) with the mean summed in index order in f32.
+struct HaltArgs { int n_seqs; float t[PK_MAXB]; };
+__global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const float* __restrict__ cls, int d, int b, HaltArgs ha,
+                               float* __restrict__ alpha, int* __restrict__ stop) {
+  __shared__ float al[32];
+  const int si = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (int j = wv; j < b; j += nw) {
+    const float* x = xn + (size_t)(si * b + j) * ldx;
+    float z0 = 0.f, z1 = 0.f;
+    for (int k = lane; k < d; k += 64) { z0 += x[k] * cls[k]; z1 += x[k] * cls[d + k]; }
+    z0 = wave_sum(z0); z1 = wave_sum(z1);
+    if (lane == 0) al[j] = 1.0f / (1.0f + expf(z0 - z1));
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.f;
+    for (int j = 0; j < b; ++j) { s += al[j]; alpha[si * b + j] = al[j]; }
+    stop[si] = (s / (float)b <= ha.t[si]) ? 1 : 0;
+  }
+}
+
+// ------------------------------------------------------------------ acceptance (Eq. 5)
+struct AccArgs { int n_seqs; int seq[PK_MAXB]; int gamma[PK_MAXB]; int len[PK_MAXB]; float beta[PK_MAXB]; };
+
+// grid (gamma_max+1, n_seqs): row i of sequence slot si.  Writes cand (token emitted if this row
+// is where drafting is cut) and rej (row's draft rejected).
+__global__ __launch_bounds__(1024) void accept_rows_kernel(const float* __restrict__ tl, const float* __restrict__ ring,
+                                                           const int* __restrict__ draft_tok, AccArgs aa, int G1, int V, int mode,
+                                                           uint64_t seed, uint32_t step, int* __restrict__ cand, int* __restrict__ rej) {
+  __shared__ float redv[16];
+  __shared__ int redi[16];
+  const int i = blockIdx.x, si = blockIdx.y, s = aa.seq[si];
+  const int gamma = aa.gamma[si];
+  if (i > gamma) return;
+  const float beta = aa.beta[si];
+  const float* t = tl + (size_t)(si * G1 + i) * V;
+  const float* q = ring + (size_t)(s * G1 + i) * V;
+  const int y = i < gamma ? draft_tok[s * G1 + i] : -1;
+  if (mode == 0) {
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int v = threadIdx.x; v < V; v += blockDim.x) {
+      const float e = t[v] + beta * q[v];
+      if (e > best) { best = e; bi = v; }
+    }
+    block_argmax(best, bi, redv, redi);
+    if (threadIdx.x == 0) { cand[si * G1 + i] = bi; rej[si * G1 + i] = (i < gamma && bi != y) ? 1 : 0; }
+    return;
+  }
+  // log-sum-exp of effective target and of draft logits
+  float mp = -INFINITY, mq = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += blockDim.x) { mp = fmaxf(mp, t[v] + beta * q[v]); mq = fmaxf(mq, q[v]); }
+  mp = block_max(mp, redv);
+  mq = block_max(mq, redv);
+  float sp = 0.f, sq = 0.f;
+  for (int v = threadIdx.x; v < V; v += blockDim.x) { sp += expf(t[v] + beta * q[v] - mp); sq += expf(q[v] - mq); }
+  sp = block_sum(sp, redv);
+  sq = block_sum(sq, redv);
+  const float lsp = mp + logf(sp), lsq = mq + logf(sq);
+  // candidate token: Gumbel-max over log max(0, p - q) (rows < gamma) or log p (bonus row);
+  // if no residual mass exists the row falls back to log p with the same noise
+  float best = -INFINITY, bestp = -INFINITY;
+  int bi = 0x7fffffff, bip = 0x7fffffff;
+  for (int blk = threadIdx.x; blk * 4 < V; blk += blockDim.x) {
+    const uint4 b = vocab_bits(seed, s, step, (uint32_t)(i + 1), PURPOSE_NEXT, (uint32_t)blk);
+    const float g4[4] = {gumbel(u01(b.x)), gumbel(u01(b.y)), gumbel(u01(b.z)), gumbel(u01(b.w))};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int v = blk * 4 + e;
+      if (v < V) {
+        const float lp = t[v] + beta * q[v] - lsp;
+        const float kp = lp + g4[e];
+        if (kp > bestp) { bestp = kp; bip = v; }
+        if (i < gamma) {
+          const float w = expf(lp) - expf(q[v] - lsq);
+          if (w > 0.f) {
+            const float kr = logf(w) + g4[e];
+            if (kr > best) { best = kr; bi = v; }
+          }
+        }
+      }
+    }
+  }
+  block_argmax(bestp, bip, redv, redi);
+  int c = bip;
+  if (i < gamma) {
+    block_argmax(best, bi, redv, redi);
+    if (best > -INFINITY) c = bi;
+  }
+  if (threadIdx.x == 0) {
+    cand[si * G1 + i] = c;
+    int rj = 0;
+    if (i < gamma) {
+      const float ratio = expf((t[y] + beta * q[y] - lsp) - (q[y] - lsq));
+      const uint4 b = vocab_bits(seed, s, step, (uint32_t)(i + 1), PURPOSE_ACCEPT, 0u);
+      rj = (u01(b.x) > ratio) ? 1 : 0;
+    }
+    rej[si * G1 + i] = rj;
+  }
+}
+
+// n = first rejected row (or gamma); next token = that row's candidate; append to committed tokens
+__global__ void accept_finalize_kernel(const int* __restrict__ cand, const int* __restrict__ rej, const int* __restrict__ draft_tok,
+                                       AccArgs aa, int G1, int max_seq, int* __restrict__ tokens, int* __restrict__ out_n,
+                                       int* __restrict__ out_z, int* __restrict__ host_res) {
+  const int si = blockIdx.x, s = aa.seq[si];
+  const int gamma = aa.gamma[si];
+  int n = gamma;
+  for (int i = gamma - 1; i >= 0; --i)
+    if (rej[si * G1 + i]) n = i;
+  const int z = cand[si * G1 + n];
+  int* tk = tokens + (size_t)s * max_seq + aa.len[si];
+  for (int k = threadIdx.x; k < n; k += blockDim.x) tk[k] = draft_tok[s * G1 + k];
+  if (threadIdx.x == 0) {
+    tk[n] = z;
+    out_n[si] = n;
+    out_z[si] = z;
+    host_res[2 * s] = n;
+    host_res[2 * s + 1] = z;
+  }
+}
+
+__global__ void copy_i32_kernel(int* __restrict__ dst, const int* __restrict__ src, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = src[i];
+}

@@ -1,0 +1,752 @@
+// Host side of the Pacer hot-path library: argument validation, per-sequence bookkeeping and
+// kernel sequencing for the C ABI declared in include/pacer.h.  No device memory is allocated
+// here; everything lives in buffers the caller binds.
+#include "../../include/pacer.h"
+#include "kernels.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+constexpr int kChunkRows = 32;       // rows per prefill chunk and per MFMA GEMM launch
+constexpr int kMaxChunks = 64;       // attention: key chunks per (head, sequence)
+constexpr int kProfEvents = 8192;
+
+struct Model {
+  pacer_model_cfg cfg{};
+  const void* embed = nullptr;
+  const float* final_norm = nullptr;
+  const void* head = nullptr;
+  std::vector<const float*> attn_norm, ffn_norm;
+  std::vector<const void*> wqkv, wo, wgu, wd;
+  const float* posemb = nullptr;
+  const float* cls = nullptr;
+  void* kv = nullptr;
+};
+
+struct Seq {
+  int len = 0;        // committed tokens
+  int gamma = 0;      // drafts made in the current step
+  int mb_done = 0;    // drafts already covered by pre-verification calls
+  int verified = -1;  // gamma used by the last pacer_verify of this step, -1 = none
+  float t = 0.f;      // current threshold
+  bool pending = false;
+  bool in_step = false;
+  int last_n = -1, last_z = -1;
+};
+
+}  // namespace
+
+struct pacer_ctx {
+  Model m[3];
+  pacer_pv_cfg pv{};
+  int max_batch = 0;
+  hipStream_t stream = nullptr;
+  Seq seq[PACER_MAX_BATCH];
+  char err[256] = {0};
+  // workspace carve-up
+  bool ws_bound = false;
+  int G1 = 0, rcap = 0, dmax = 0, fmax = 0, kmax = 0, hmax = 0, hdmax = 0, max_seq = 0;
+  int *tokens = nullptr, *draft_tok = nullptr, *cand = nullptr, *rej = nullptr;
+  float *ring = nullptr, *hidden = nullptr, *x = nullptr, *xn = nullptr, *qkv = nullptr, *ao = nullptr, *gu = nullptr,
+        *rope = nullptr, *part = nullptr;
+  _Float16* xp = nullptr;
+  int* host_res = nullptr;      // pinned host memory [max_batch][2]
+  int* host_res_dev = nullptr;  // its device alias
+  // profiling of the GEMM kernel
+  bool prof = false;
+  std::vector<hipEvent_t> ev;
+  int n_ev = 0;
+  double prof_bytes = 0.0;
+};
+
+namespace {
+
+int fail(pacer_ctx* c, int code, const char* fmt, ...) {
+  if (c) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(c->err, sizeof(c->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+#define HIPCHK(c, call)                                                                    \
+  do {                                                                                     \
+    hipError_t e_ = (call);                                                                \
+    if (e_ != hipSuccess) return fail(c, PACER_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+size_t esize(int dtype) { return dtype == PACER_BF16 ? 2 : 4; }
+
+bool cfg_ok(const pacer_model_cfg& m) {
+  if (m.n_layers < 1 || m.d_model < 1 || m.n_heads < 1 || m.d_ffn < 1 || m.vocab < 1 || m.max_seq < 2) return false;
+  if (m.head_dim != 64 && m.head_dim != 128) return false;
+  if (m.n_heads * m.head_dim != m.d_model) return false;
+  if (m.dtype != PACER_F32 && m.dtype != PACER_BF16) return false;
+  if (m.dtype == PACER_BF16 && (m.d_model % 32 || m.d_ffn % 32 || m.vocab % 16)) return false;
+  if (m.d_model % 8 || m.d_ffn % 8) return false;
+  if (!(m.rms_eps > 0.f) || !(m.rope_theta > 0.f)) return false;
+  if (m.dtype == PACER_F32 && m.head_dim != 64) return false;  // f32 KV tiles are staged for head_dim 64 only
+  return true;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Carve {
+  size_t off = 0;
+  char* base;
+  explicit Carve(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T> T* take(size_t n) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off = align_up(off + n * sizeof(T), 256);
+    return p;
+  }
+};
+
+size_t carve(pacer_ctx* c, void* base) {
+  Carve k(base);
+  const int B = c->max_batch, G1 = c->G1, V = c->m[PACER_DRAFT].cfg.vocab, dD = c->m[PACER_DRAFT].cfg.d_model;
+  const int mtcap = (c->rcap + 15) / 16;
+  c->tokens = k.take<int>((size_t)B * c->max_seq);
+  c->draft_tok = k.take<int>((size_t)B * G1);
+  c->cand = k.take<int>((size_t)B * G1);
+  c->rej = k.take<int>((size_t)B * G1);
+  c->ring = k.take<float>((size_t)B * G1 * V);
+  c->hidden = k.take<float>((size_t)B * G1 * dD);
+  c->x = k.take<float>((size_t)c->rcap * c->dmax);
+  c->xn = k.take<float>((size_t)c->rcap * c->kmax);
+  c->qkv = k.take<float>((size_t)c->rcap * 3 * c->dmax);
+  c->ao = k.take<float>((size_t)c->rcap * c->dmax);
+  c->gu = k.take<float>((size_t)c->rcap * 2 * c->fmax);
+  c->rope = k.take<float>((size_t)c->rcap * c->hdmax);
+  c->part = k.take<float>((size_t)c->rcap * c->hmax * kMaxChunks * (c->hdmax + 2));
+  c->xp = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
+  return k.off;
+}
+
+Model* model_of(pacer_ctx* c, int which) { return (which >= 0 && which <= 2) ? &c->m[which] : nullptr; }
+
+bool model_bound(const Model& m, int which) {
+  if (!m.kv) return false;
+  for (int l = 0; l < m.cfg.n_layers; ++l)
+    if (!m.attn_norm[l] || !m.ffn_norm[l] || !m.wqkv[l] || !m.wo[l] || !m.wgu[l] || !m.wd[l]) return false;
+  if (!m.final_norm) return false;
+  if (which == PACER_PREVERIFY) return m.posemb && m.cls;
+  return m.embed && m.head;
+}
+
+int ready(pacer_ctx* c) {
+  if (!c->ws_bound) return fail(c, PACER_ESTATE, "workspace not bound");
+  for (int w = 0; w < 3; ++w)
+    if (!model_bound(c->m[w], w)) return fail(c, PACER_ESTATE, "model %d: weights or KV cache not bound", w);
+  return PACER_OK;
+}
+
+int check_seqs(pacer_ctx* c, const int32_t* seqs, int n) {
+  if (!seqs || n < 1 || n > c->max_batch) return fail(c, PACER_EINVAL, "bad sequence list (n_seqs=%d)", n);
+  for (int i = 0; i < n; ++i) {
+    if (seqs[i] < 0 || seqs[i] >= c->max_batch) return fail(c, PACER_EINVAL, "sequence id %d out of range", seqs[i]);
+    for (int j = 0; j < i; ++j)
+      if (seqs[j] == seqs[i]) return fail(c, PACER_EINVAL, "sequence id %d listed twice", seqs[i]);
+  }
+  return PACER_OK;
+}
+
+// ---- launches -------------------------------------------------------------------------------
+
+void prof_begin(pacer_ctx* c) {
+  if (c->prof && c->n_ev + 2 <= (int)c->ev.size()) (void)hipEventRecord(c->ev[c->n_ev], c->stream);
+}
+void prof_end(pacer_ctx* c, double bytes) {
+  if (c->prof && c->n_ev + 2 <= (int)c->ev.size()) {
+    (void)hipEventRecord(c->ev[c->n_ev + 1], c->stream);
+    c->n_ev += 2;
+    c->prof_bytes += bytes;
+  }
+}
+
+template <int MT, int NT>
+void launch_w16(pacer_ctx* c, const void* W, float* out, int ldo, int R, int N, int K, int mt0, int mt_total, int acc,
+                const SeqRows& sr, int rowmap) {
+  constexpr int WAVES = 8;
+  hipLaunchKernelGGL((gemm_w16_kernel<MT, NT, WAVES>), dim3(N / 16 / NT), dim3(WAVES * 64), 0, c->stream,
+                     static_cast<const u32x4*>(W), reinterpret_cast<const u32x4*>(c->xp), out, ldo, R, K / 32, mt0, mt_total, acc,
+                     sr, rowmap, c->G1);
+}
+
+// out[r][n] (+)= sum_k act[r][k] W[n][k].  bf16 models read the packed operand in c->xp (which the
+// producer of `act` has filled); f32 models read actf (f32 rows).
+void gemm(pacer_ctx* c, const Model& m, const void* W, const float* actf, int lda, float* out, int ldo, int R, int N, int K,
+          int acc, const SeqRows& sr, int rowmap) {
+  if (m.cfg.dtype == PACER_BF16) {
+    const int mt_total = (R + 15) / 16;
+    const int tiles = N / 16;
+    const bool nt2 = (tiles % 2 == 0) && (tiles / 2 >= 512);
+    for (int mt0 = 0; mt0 < mt_total; mt0 += 2) {
+      const int mt = std::min(2, mt_total - mt0);
+      prof_begin(c);
+      if (mt == 1) {
+        if (nt2) launch_w16<1, 2>(c, W, out, ldo, R, N, K, mt0, mt_total, acc, sr, rowmap);
+        else launch_w16<1, 1>(c, W, out, ldo, R, N, K, mt0, mt_total, acc, sr, rowmap);
+      } else {
+        if (nt2) launch_w16<2, 2>(c, W, out, ldo, R, N, K, mt0, mt_total, acc, sr, rowmap);
+        else launch_w16<2, 1>(c, W, out, ldo, R, N, K, mt0, mt_total, acc, sr, rowmap);
+      }
+      prof_end(c, (double)N * K * 2.0);
+    }
+  } else {
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, static_cast<const float*>(W), actf, lda, out,
+                       ldo, R, N, K, acc, sr, rowmap, c->G1);
+  }
+}
+
+void rmsnorm(pacer_ctx* c, const Model& m, const float* g, int R, float* hid_out, const SeqRows& sr) {
+  const bool pk = m.cfg.dtype == PACER_BF16;
+  const int mt_total = (R + 15) / 16;
+  hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(pk ? mt_total * 16 : R), dim3(256), 0, c->stream, c->x, c->dmax, g, m.cfg.rms_eps, R,
+                     m.cfg.d_model, c->xn, c->kmax, pk ? c->xp : nullptr, mt_total, hid_out, c->G1, sr);
+}
+
+template <typename KVT>
+void attention_t(pacer_ctx* c, const Model& m, int layer, int R, const SeqRows& sr, int kv_only) {
+  const pacer_model_cfg& g = m.cfg;
+  const int d = g.d_model, hd = g.head_dim, H = g.n_heads;
+  hipLaunchKernelGGL((rope_append_kernel<KVT>), dim3(R, H), dim3(hd / 2), 0, c->stream, c->qkv, 3 * c->dmax, c->rope, sr, d, hd,
+                     static_cast<KVT*>(m.kv), layer, g.n_layers, g.max_seq, kv_only);
+  if (kv_only) return;
+  int max_keys = 0;
+  for (int i = 0; i < sr.n_seqs; ++i) max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
+  const int n_tiles = (max_keys + ATT_TILE - 1) / ATT_TILE;
+  int chunks = std::min(std::min(n_tiles, kMaxChunks), std::max(1, 1024 / (H * sr.n_seqs)));
+  const int tpc = (n_tiles + chunks - 1) / chunks;
+  chunks = (n_tiles + tpc - 1) / tpc;
+  if (hd == 128)
+    hipLaunchKernelGGL((attn_partial_kernel<KVT, 128>), dim3(chunks, H, sr.n_seqs), dim3(256), 0, c->stream, c->qkv, 3 * c->dmax,
+                       static_cast<const KVT*>(m.kv), layer, g.n_layers, g.max_seq, d, sr, tpc, chunks, H, c->part);
+  else
+    hipLaunchKernelGGL((attn_partial_kernel<KVT, 64>), dim3(chunks, H, sr.n_seqs), dim3(256), 0, c->stream, c->qkv, 3 * c->dmax,
+                       static_cast<const KVT*>(m.kv), layer, g.n_layers, g.max_seq, d, sr, tpc, chunks, H, c->part);
+  hipLaunchKernelGGL(attn_combine_kernel, dim3(R, H), dim3(hd), 0, c->stream, c->part, chunks, H, hd, c->ao, c->dmax);
+  if (g.dtype == PACER_BF16) {
+    const int mt_total = (R + 15) / 16;
+    hipLaunchKernelGGL(pack_act_kernel, dim3(mt_total * 16), dim3(256), 0, c->stream, c->ao, c->dmax, R, d, c->xp, mt_total);
+  }
+}
+
+// The decoder stack on the R rows already present in c->x (f32 [R][dmax]); rows of one sequence
+// occupy consecutive positions.  kv_only: stop each layer after writing K/V (prefix rows of M_B).
+// Leaves the final-norm output in c->xn (and, for bf16, the packed operand in c->xp).
+void run_layers(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool kv_only, float* hid_out) {
+  const pacer_model_cfg& g = m.cfg;
+  const int d = g.d_model, F = g.d_ffn;
+  const SeqRows none{};
+  hipLaunchKernelGGL(rope_table_kernel, dim3(R), dim3(g.head_dim / 2), 0, c->stream, sr, g.head_dim, g.rope_theta, c->rope);
+  for (int l = 0; l < g.n_layers; ++l) {
+    rmsnorm(c, m, m.attn_norm[l], R, nullptr, sr);
+    gemm(c, m, m.wqkv[l], c->xn, c->kmax, c->qkv, 3 * c->dmax, R, 3 * d, d, 0, none, ROWMAP_ID);
+    if (g.dtype == PACER_BF16) attention_t<uint16_t>(c, m, l, R, sr, kv_only);
+    else attention_t<float>(c, m, l, R, sr, kv_only);
+    if (kv_only) continue;
+    gemm(c, m, m.wo[l], c->ao, c->dmax, c->x, c->dmax, R, d, d, 1, none, ROWMAP_ID);
+    rmsnorm(c, m, m.ffn_norm[l], R, nullptr, sr);
+    gemm(c, m, m.wgu[l], c->xn, c->kmax, c->gu, 2 * c->fmax, R, 2 * F, d, 0, none, ROWMAP_ID);
+    {
+      const bool pk = g.dtype == PACER_BF16;
+      const int mt_total = (R + 15) / 16;
+      hipLaunchKernelGGL(swiglu_pack_kernel, dim3((F / 8 + 255) / 256, pk ? mt_total * 16 : R), dim3(256), 0, c->stream, c->gu,
+                         2 * c->fmax, R, F, c->xn, c->kmax, pk ? c->xp : nullptr, mt_total);
+    }
+    gemm(c, m, m.wd[l], c->xn, c->kmax, c->x, c->dmax, R, d, F, 1, none, ROWMAP_ID);
+  }
+  if (!kv_only) rmsnorm(c, m, m.final_norm, R, hid_out, sr);
+}
+
+void embed(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
+  if (m.cfg.dtype == PACER_BF16)
+    hipLaunchKernelGGL((embed_rows_kernel<uint16_t>), dim3(R), dim3(256), 0, c->stream, static_cast<const uint16_t*>(m.embed),
+                       c->tokens, c->draft_tok, sr, c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax);
+  else
+    hipLaunchKernelGGL((embed_rows_kernel<float>), dim3(R), dim3(256), 0, c->stream, static_cast<const float*>(m.embed), c->tokens,
+                       c->draft_tok, sr, c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax);
+}
+
+void lm_head(pacer_ctx* c, const Model& m, int R, float* out, const SeqRows& sr, int rowmap) {
+  gemm(c, m, m.head, c->xn, c->kmax, out, m.cfg.vocab, R, m.cfg.vocab, m.cfg.d_model, 0, sr, rowmap);
+}
+
+// M_B over rows whose inputs are src rows + PosEmb; kv_only for prefix rows.
+void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr, const float* src, int lds, bool kv_only) {
+  const Model& mb = c->m[PACER_PREVERIFY];
+  hipLaunchKernelGGL(mb_input_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax);
+  run_layers(c, mb, R, sr, kv_only, nullptr);
+}
+
+// one draft forward at draft index j[s] (0-based) for each listed sequence; logits and hidden
+// state go to ring slot j, and a token is picked into draft_tok[j]
+void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int mode, uint64_t seed, uint64_t ctr) {
+  const Model& md = c->m[PACER_DRAFT];
+  SeqRows sr{};
+  PickArgs pa{};
+  sr.n_seqs = pa.n_seqs = n;
+  for (int i = 0; i < n; ++i) {
+    const Seq& s = c->seq[seqs[i]];
+    sr.seq[i] = pa.seq[i] = seqs[i];
+    sr.row_off[i] = i;
+    sr.pos0[i] = s.len - 1 + j[i];
+    sr.len[i] = s.len;
+    pa.j[i] = j[i];
+  }
+  sr.row_off[n] = n;
+  embed(c, md, n, sr);
+  run_layers(c, md, n, sr, false, c->hidden);
+  lm_head(c, md, n, c->ring, sr, ROWMAP_RING);
+  hipLaunchKernelGGL(pick_token_kernel, dim3(n), dim3(1024), 0, c->stream, c->ring, c->draft_tok, pa, c->G1, md.cfg.vocab, mode, seed,
+                     (uint32_t)ctr);
+}
+
+int fold(pacer_ctx* c, int s) {
+  Seq& q = c->seq[s];
+  if (!q.pending) return PACER_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (int i = 0; i < c->max_batch; ++i) {
+    Seq& o = c->seq[i];
+    if (!o.pending) continue;
+    o.last_n = c->host_res[2 * i];
+    o.last_z = c->host_res[2 * i + 1];
+    o.len += o.last_n + 1;
+    o.pending = false;
+  }
+  return PACER_OK;
+}
+
+}  // namespace
+
+// =============================================================================================
+extern "C" {
+
+int32_t pacer_create(pacer_ctx** out, const pacer_model_cfg* target, const pacer_model_cfg* draft, const pacer_pv_cfg* pv,
+                     int32_t max_batch, void* hip_stream) {
+  if (!out || !target || !draft || !pv) return PACER_EINVAL;
+  *out = nullptr;
+  if (!cfg_ok(*target) || !cfg_ok(*draft)) return PACER_EINVAL;
+  if (target->vocab != draft->vocab || target->max_seq != draft->max_seq) return PACER_EINVAL;
+  if (pv->block < 1 || pv->gamma_max < pv->block || pv->gamma_max % pv->block || pv->gamma_max > 31) return PACER_EINVAL;
+  if (!(pv->t0 >= 0.f) || !(pv->rho > 0.f)) return PACER_EINVAL;
+  if (max_batch < 1 || max_batch > PACER_MAX_BATCH) return PACER_EINVAL;
+  if (target->max_seq <= pv->gamma_max + 2) return PACER_EINVAL;
+  pacer_ctx* c = new (std::nothrow) pacer_ctx();
+  if (!c) return PACER_EINVAL;
+  c->m[PACER_TARGET].cfg = *target;
+  c->m[PACER_DRAFT].cfg = *draft;
+  c->m[PACER_PREVERIFY].cfg = *draft;
+  c->m[PACER_PREVERIFY].cfg.n_layers = 1;
+  for (int w = 0; w < 3; ++w) {
+    const int L = c->m[w].cfg.n_layers;
+    c->m[w].attn_norm.assign(L, nullptr);
+    c->m[w].ffn_norm.assign(L, nullptr);
+    c->m[w].wqkv.assign(L, nullptr);
+    c->m[w].wo.assign(L, nullptr);
+    c->m[w].wgu.assign(L, nullptr);
+    c->m[w].wd.assign(L, nullptr);
+  }
+  c->pv = *pv;
+  c->max_batch = max_batch;
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  c->G1 = pv->gamma_max + 1;
+  c->rcap = std::max(kChunkRows, max_batch * c->G1);
+  c->dmax = std::max(target->d_model, draft->d_model);
+  c->fmax = std::max(target->d_ffn, draft->d_ffn);
+  c->kmax = std::max(c->dmax, c->fmax);
+  c->hmax = std::max(target->n_heads, draft->n_heads);
+  c->hdmax = std::max(target->head_dim, draft->head_dim);
+  c->max_seq = target->max_seq;
+  *out = c;
+  return PACER_OK;
+}
+
+void pacer_destroy(pacer_ctx* c) {
+  if (!c) return;
+  if (c->ws_bound) {
+    (void)hipStreamSynchronize(c->stream);
+    for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+    if (c->host_res) (void)hipHostFree(c->host_res);
+  }
+  delete c;
+}
+
+const char* pacer_last_error(const pacer_ctx* c) { return c ? c->err : "null context"; }
+
+int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int32_t n_in, void* hip_stream) {
+  if (!dev_dst || !dev_src || dev_dst == dev_src || n_out < 16 || n_in < 32 || n_out % 16 || n_in % 32) return PACER_EINVAL;
+  hipLaunchKernelGGL(pack_weight_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(hip_stream), static_cast<uint4*>(dev_dst),
+                     static_cast<const uint16_t*>(dev_src), n_out, n_in);
+  return hipGetLastError() == hipSuccess ? PACER_OK : PACER_EHIP;
+}
+
+int32_t pacer_bind(pacer_ctx* c, int32_t which, int32_t tensor_id, int32_t layer, const void* p, uint64_t nbytes) {
+  if (!c) return PACER_EINVAL;
+  Model* m = model_of(c, which);
+  if (!m || !p) return fail(c, PACER_EINVAL, "bind: bad model id or null pointer");
+  const pacer_model_cfg& g = m->cfg;
+  const uint64_t d = g.d_model, F = g.d_ffn, V = g.vocab, es = esize(g.dtype);
+  const bool per_layer = tensor_id >= PACER_T_ATTN_NORM && tensor_id <= PACER_T_WD;
+  if (per_layer && (layer < 0 || layer >= g.n_layers)) return fail(c, PACER_EINVAL, "bind: layer %d out of range", layer);
+  uint64_t want = 0;
+  switch (tensor_id) {
+    case PACER_T_EMBED: want = V * d * es; break;
+    case PACER_T_HEAD: want = V * d * es; break;
+    case PACER_T_FINAL_NORM: case PACER_T_ATTN_NORM: case PACER_T_FFN_NORM: want = d * 4; break;
+    case PACER_T_WQKV: want = 3 * d * d * es; break;
+    case PACER_T_WO: want = d * d * es; break;
+    case PACER_T_WGU: want = 2 * F * d * es; break;
+    case PACER_T_WD: want = d * F * es; break;
+    case PACER_T_POSEMB: want = (uint64_t)(c->pv.gamma_max + 1) * d * 4; break;
+    case PACER_T_CLS: want = 2 * d * 4; break;
+    default: return fail(c, PACER_EINVAL, "bind: unknown tensor id %d", tensor_id);
+  }
+  const bool mb_only = tensor_id == PACER_T_POSEMB || tensor_id == PACER_T_CLS;
+  const bool lm_only = tensor_id == PACER_T_EMBED || tensor_id == PACER_T_HEAD;
+  if ((mb_only && which != PACER_PREVERIFY) || (lm_only && which == PACER_PREVERIFY))
+    return fail(c, PACER_EINVAL, "bind: tensor %d does not belong to model %d", tensor_id, which);
+  if (nbytes != want) return fail(c, PACER_EINVAL, "bind: tensor %d expects %llu bytes, got %llu", tensor_id,
+                                  (unsigned long long)want, (unsigned long long)nbytes);
+  if (reinterpret_cast<uintptr_t>(p) % 16) return fail(c, PACER_EINVAL, "bind: pointer must be 16-byte aligned");
+  switch (tensor_id) {
+    case PACER_T_EMBED: m->embed = p; break;
+    case PACER_T_HEAD: m->head = p; break;
+    case PACER_T_FINAL_NORM: m->final_norm = static_cast<const float*>(p); break;
+    case PACER_T_ATTN_NORM: m->attn_norm[layer] = static_cast<const float*>(p); break;
+    case PACER_T_FFN_NORM: m->ffn_norm[layer] = static_cast<const float*>(p); break;
+    case PACER_T_WQKV: m->wqkv[layer] = p; break;
+    case PACER_T_WO: m->wo[layer] = p; break;
+    case PACER_T_WGU: m->wgu[layer] = p; break;
+    case PACER_T_WD: m->wd[layer] = p; break;
+    case PACER_T_POSEMB: m->posemb = static_cast<const float*>(p); break;
+    case PACER_T_CLS: m->cls = static_cast<const float*>(p); break;
+  }
+  return PACER_OK;
+}
+
+uint64_t pacer_kv_bytes(const pacer_ctx* c, int32_t which) {
+  if (!c || which < 0 || which > 2) return 0;
+  const pacer_model_cfg& g = c->m[which].cfg;
+  return (uint64_t)c->max_batch * g.n_layers * 2 * g.max_seq * g.d_model * esize(g.dtype);
+}
+
+int32_t pacer_bind_kv(pacer_ctx* c, int32_t which, void* p, uint64_t nbytes) {
+  if (!c) return PACER_EINVAL;
+  if (which < 0 || which > 2 || !p) return fail(c, PACER_EINVAL, "bind_kv: bad model id or null pointer");
+  if (nbytes != pacer_kv_bytes(c, which)) return fail(c, PACER_EINVAL, "bind_kv: expected %llu bytes",
+                                                      (unsigned long long)pacer_kv_bytes(c, which));
+  if (reinterpret_cast<uintptr_t>(p) % 16) return fail(c, PACER_EINVAL, "bind_kv: pointer must be 16-byte aligned");
+  c->m[which].kv = p;
+  return PACER_OK;
+}
+
+uint64_t pacer_workspace_bytes(const pacer_ctx* c) {
+  if (!c) return 0;
+  pacer_ctx tmp = *c;   // carve on a copy with a null base only computes the size
+  return carve(&tmp, nullptr);
+}
+
+int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
+  if (!c) return PACER_EINVAL;
+  if (!p || reinterpret_cast<uintptr_t>(p) % 256) return fail(c, PACER_EINVAL, "workspace must be non-null and 256-byte aligned");
+  if (nbytes < pacer_workspace_bytes(c)) return fail(c, PACER_EINVAL, "workspace too small: need %llu bytes",
+                                                     (unsigned long long)pacer_workspace_bytes(c));
+  if (c->ws_bound) return fail(c, PACER_ESTATE, "workspace already bound");
+  carve(c, p);
+  void* hp = nullptr;
+  HIPCHK(c, hipHostMalloc(&hp, sizeof(int) * 2 * PACER_MAX_BATCH, hipHostMallocMapped));
+  c->host_res = static_cast<int*>(hp);
+  void* dp = nullptr;
+  HIPCHK(c, hipHostGetDevicePointer(&dp, hp, 0));
+  c->host_res_dev = static_cast<int*>(dp);
+  c->ws_bound = true;
+  return PACER_OK;
+}
+
+int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_t n) {
+  if (!c) return PACER_EINVAL;
+  if (int rc = ready(c)) return rc;
+  if (s < 0 || s >= c->max_batch || !dev_tokens || n < 1) return fail(c, PACER_EINVAL, "prefill: bad arguments");
+  if (n + c->G1 + 1 > c->max_seq) return fail(c, PACER_EOVERFLOW, "prefill: %d tokens leave no room for a step (max_seq %d)", n, c->max_seq);
+  Seq& q = c->seq[s];
+  q = Seq();
+  q.len = n;
+  hipLaunchKernelGGL(copy_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->tokens + (size_t)s * c->max_seq, dev_tokens, n);
+  for (int p0 = 0; p0 < n - 1; p0 += kChunkRows) {
+    const int R = std::min(kChunkRows, n - 1 - p0);
+    SeqRows sr{};
+    sr.n_seqs = 1;
+    sr.seq[0] = s;
+    sr.row_off[0] = 0;
+    sr.row_off[1] = R;
+    sr.pos0[0] = p0;
+    sr.len[0] = n;
+    embed(c, c->m[PACER_TARGET], R, sr);
+    run_layers(c, c->m[PACER_TARGET], R, sr, false, nullptr);
+    embed(c, c->m[PACER_DRAFT], R, sr);
+    run_layers(c, c->m[PACER_DRAFT], R, sr, false, nullptr);
+    // the draft's hidden states (final-norm output, now in xn) feed M_B's prefix rows
+    (void)hipMemcpy2DAsync(c->ao, (size_t)c->dmax * 4, c->xn, (size_t)c->kmax * 4, (size_t)c->m[PACER_DRAFT].cfg.d_model * 4, R,
+                     hipMemcpyDeviceToDevice, c->stream);
+    MbRows mr{};
+    mr.src_row0[0] = 0;
+    mr.e0[0] = -1;
+    run_preverify_rows(c, R, sr, mr, c->ao, c->dmax, true);
+  }
+  HIPCHK(c, hipGetLastError());
+  return PACER_OK;
+}
+
+int32_t pacer_force_commit(pacer_ctx* c, int32_t s, int32_t from, const int32_t* host_tokens, int32_t n) {
+  if (!c) return PACER_EINVAL;
+  if (!c->ws_bound) return fail(c, PACER_ESTATE, "workspace not bound");
+  if (s < 0 || s >= c->max_batch || !host_tokens || n < 1 || from < 0) return fail(c, PACER_EINVAL, "force_commit: bad arguments");
+  if (from + n + c->G1 + 1 > c->max_seq) return fail(c, PACER_EOVERFLOW, "force_commit: beyond max_seq");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(c->tokens + (size_t)s * c->max_seq + from, host_tokens, sizeof(int) * n, hipMemcpyHostToDevice));
+  Seq& q = c->seq[s];
+  q.pending = false;
+  q.in_step = false;
+  q.len = from + n;
+  q.gamma = q.mb_done = 0;
+  q.verified = -1;
+  return PACER_OK;
+}
+
+int32_t pacer_begin_step(pacer_ctx* c, int32_t s) {
+  if (!c) return PACER_EINVAL;
+  if (int rc = ready(c)) return rc;
+  if (s < 0 || s >= c->max_batch) return fail(c, PACER_EINVAL, "begin_step: sequence id %d out of range", s);
+  if (int rc = fold(c, s)) return rc;
+  Seq& q = c->seq[s];
+  if (q.len < 1) return fail(c, PACER_ESTATE, "begin_step: sequence %d has no committed tokens (prefill first)", s);
+  if (q.len + c->G1 + 1 > c->max_seq) return fail(c, PACER_EOVERFLOW, "begin_step: sequence %d is full", s);
+  q.t = c->pv.t0;
+  q.gamma = q.mb_done = 0;
+  q.verified = -1;
+  q.in_step = true;
+  return PACER_OK;
+}
+
+int32_t pacer_draft_step(pacer_ctx* c, const int32_t* seqs, int32_t n, int32_t mode, uint64_t seed, uint64_t ctr) {
+  if (!c) return PACER_EINVAL;
+  if (int rc = ready(c)) return rc;
+  if (int rc = check_seqs(c, seqs, n)) return rc;
+  if (mode != PACER_GREEDY && mode != PACER_SAMPLE) return fail(c, PACER_EINVAL, "draft_step: bad mode %d", mode);
+  int j[PACER_MAX_BATCH];
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = c->seq[seqs[i]];
+    if (!q.in_step || q.verified >= 0) return fail(c, PACER_ESTATE, "draft_step: sequence %d is not drafting (begin_step first)", seqs[i]);
+    if (q.gamma >= c->pv.gamma_max) return fail(c, PACER_EOVERFLOW, "draft_step: sequence %d already holds gamma_max drafts", seqs[i]);
+    j[i] = q.gamma;
+  }
+  draft_forward(c, seqs, n, j, mode, seed, ctr);
+  for (int i = 0; i < n; ++i) c->seq[seqs[i]].gamma++;
+  HIPCHK(c, hipGetLastError());
+  return PACER_OK;
+}
+
+int32_t pacer_preverify_block(pacer_ctx* c, const int32_t* seqs, int32_t n, float* dev_alpha, int32_t* dev_stop) {
+  if (!c) return PACER_EINVAL;
+  if (int rc = ready(c)) return rc;
+  if (int rc = check_seqs(c, seqs, n)) return rc;
+  if (!dev_alpha || !dev_stop) return fail(c, PACER_EINVAL, "preverify_block: null output");
+  const int b = c->pv.block;
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = c->seq[seqs[i]];
+    if (!q.in_step || q.verified >= 0 || q.gamma - q.mb_done != b)
+      return fail(c, PACER_ESTATE, "preverify_block: sequence %d needs exactly %d new drafts", seqs[i], b);
+  }
+  SeqRows sr{};
+  MbRows mr{};
+  HaltArgs ha{};
+  sr.n_seqs = ha.n_seqs = n;
+  for (int i = 0; i < n; ++i) {
+    Seq& q = c->seq[seqs[i]];
+    sr.seq[i] = seqs[i];
+    sr.row_off[i] = i * b;
+    sr.pos0[i] = q.len - 1 + q.mb_done;
+    sr.len[i] = q.len;
+    mr.src_row0[i] = seqs[i] * c->G1 + q.mb_done;
+    mr.e0[i] = q.mb_done + 1;                 // draft positions i, i+1, ... (1-based)
+    ha.t[i] = q.t;
+  }
+  sr.row_off[n] = n * b;
+  const Model& mb = c->m[PACER_PREVERIFY];
+  run_preverify_rows(c, n * b, sr, mr, c->hidden, mb.cfg.d_model, false);
+  hipLaunchKernelGGL(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha,
+                     dev_stop);
+  for (int i = 0; i < n; ++i) {
+    Seq& q = c->seq[seqs[i]];
+    q.mb_done += b;
+    q.t = q.t * c->pv.rho;
+  }
+  HIPCHK(c, hipGetLastError());
+  return PACER_OK;
+}
+
+int32_t pacer_verify(pacer_ctx* c, const int32_t* seqs, int32_t n, const int32_t* gamma_override, float* dev_logits) {
+  if (!c) return PACER_EINVAL;
+  if (int rc = ready(c)) return rc;
+  if (int rc = check_seqs(c, seqs, n)) return rc;
+  if (!dev_logits) return fail(c, PACER_EINVAL, "verify: null output");
+  int g[PACER_MAX_BATCH];
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = c->seq[seqs[i]];
+    if (!q.in_step) return fail(c, PACER_ESTATE, "verify: sequence %d has no step in progress", seqs[i]);
+    g[i] = (gamma_override && gamma_override[i] >= 0) ? gamma_override[i] : q.gamma;
+    if (g[i] > q.gamma) return fail(c, PACER_EINVAL, "verify: gamma %d exceeds the %d drafts made", g[i], q.gamma);
+  }
+  SeqRows sr{};
+  sr.n_seqs = n;
+  int R = 0;
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = c->seq[seqs[i]];
+    sr.seq[i] = seqs[i];
+    sr.row_off[i] = R;
+    sr.pos0[i] = q.len - 1;
+    sr.len[i] = q.len;
+    R += g[i] + 1;
+  }
+  sr.row_off[n] = R;
+  const Model& mt = c->m[PACER_TARGET];
+  embed(c, mt, R, sr);
+  run_layers(c, mt, R, sr, false, nullptr);
+  lm_head(c, mt, R, dev_logits, sr, ROWMAP_LIST);
+  for (int i = 0; i < n; ++i) c->seq[seqs[i]].verified = g[i];
+  HIPCHK(c, hipGetLastError());
+  return PACER_OK;
+}
+
+int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int32_t mode, const float* beta, uint64_t seed,
+                              uint64_t ctr, const float* dev_logits, int32_t* dev_n, int32_t* dev_z) {
+  if (!c) return PACER_EINVAL;
+  if (int rc = ready(c)) return rc;
+  if (int rc = check_seqs(c, seqs, n)) return rc;
+  if (!beta || !dev_logits || !dev_n || !dev_z) return fail(c, PACER_EINVAL, "accept_rollback: null argument");
+  if (mode != PACER_GREEDY && mode != PACER_SAMPLE) return fail(c, PACER_EINVAL, "accept_rollback: bad mode %d", mode);
+  for (int i = 0; i < n; ++i)
+    if (!c->seq[seqs[i]].in_step || c->seq[seqs[i]].verified < 0)
+      return fail(c, PACER_ESTATE, "accept_rollback: sequence %d has not been verified", seqs[i]);
+  // draft forward on y_gamma: completes the draft cache for the all-accepted case and yields the
+  // draft logits of the bonus row
+  int j[PACER_MAX_BATCH];
+  for (int i = 0; i < n; ++i) j[i] = c->seq[seqs[i]].verified;
+  draft_forward(c, seqs, n, j, PACER_GREEDY, 0, 0);
+  // M_B prefix rows for draft positions no pre-verification call covered (incl. the bonus position)
+  {
+    SeqRows sr{};
+    MbRows mr{};
+    int R = 0, k = 0;
+    for (int i = 0; i < n; ++i) {
+      const Seq& q = c->seq[seqs[i]];
+      const int first = std::min(q.mb_done, q.verified + 1);
+      const int cnt = q.verified + 1 - first;
+      if (cnt <= 0) continue;
+      sr.seq[k] = seqs[i];
+      sr.row_off[k] = R;
+      sr.pos0[k] = q.len - 1 + first;
+      sr.len[k] = q.len;
+      mr.src_row0[k] = seqs[i] * c->G1 + first;
+      mr.e0[k] = -1;
+      R += cnt;
+      ++k;
+    }
+    sr.n_seqs = k;
+    sr.row_off[k] = R;
+    if (R > 0) run_preverify_rows(c, R, sr, mr, c->hidden, c->m[PACER_PREVERIFY].cfg.d_model, true);
+  }
+  AccArgs aa{};
+  aa.n_seqs = n;
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = c->seq[seqs[i]];
+    aa.seq[i] = seqs[i];
+    aa.gamma[i] = q.verified;
+    aa.len[i] = q.len;
+    aa.beta[i] = beta[i];
+  }
+  const int V = c->m[PACER_TARGET].cfg.vocab;
+  hipLaunchKernelGGL(accept_rows_kernel, dim3(c->G1, n), dim3(1024), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode,
+                     seed, (uint32_t)ctr, c->cand, c->rej);
+  hipLaunchKernelGGL(accept_finalize_kernel, dim3(n), dim3(64), 0, c->stream, c->cand, c->rej, c->draft_tok, aa, c->G1, c->max_seq,
+                     c->tokens, dev_n, dev_z, c->host_res_dev);
+  for (int i = 0; i < n; ++i) {
+    Seq& q = c->seq[seqs[i]];
+    q.pending = true;
+    q.in_step = false;
+  }
+  HIPCHK(c, hipGetLastError());
+  return PACER_OK;
+}
+
+int32_t pacer_get_state(pacer_ctx* c, int32_t s, int32_t* gamma, int32_t* len, float* t, int32_t* n_acc, int32_t* next) {
+  if (!c) return PACER_EINVAL;
+  if (s < 0 || s >= c->max_batch) return fail(c, PACER_EINVAL, "get_state: sequence id %d out of range", s);
+  if (c->ws_bound) {
+    if (int rc = fold(c, s)) return rc;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  const Seq& q = c->seq[s];
+  if (gamma) *gamma = q.gamma;
+  if (len) *len = q.len;
+  if (t) *t = q.t;
+  if (n_acc) *n_acc = q.last_n;
+  if (next) *next = q.last_z;
+  return PACER_OK;
+}
+
+int32_t pacer_peek(pacer_ctx* c, int32_t s, int32_t what, void** p, uint64_t* nbytes) {
+  if (!c) return PACER_EINVAL;
+  if (!c->ws_bound) return fail(c, PACER_ESTATE, "workspace not bound");
+  if (s < 0 || s >= c->max_batch || !p || !nbytes) return fail(c, PACER_EINVAL, "peek: bad arguments");
+  const int V = c->m[PACER_DRAFT].cfg.vocab, dD = c->m[PACER_DRAFT].cfg.d_model, G1 = c->G1;
+  switch (what) {
+    case PACER_PEEK_DRAFT_LOGITS: *p = c->ring + (size_t)s * G1 * V; *nbytes = (uint64_t)G1 * V * 4; break;
+    case PACER_PEEK_DRAFT_HIDDEN: *p = c->hidden + (size_t)s * G1 * dD; *nbytes = (uint64_t)G1 * dD * 4; break;
+    case PACER_PEEK_DRAFT_TOKENS: *p = c->draft_tok + s * G1; *nbytes = (uint64_t)G1 * 4; break;
+    case PACER_PEEK_TOKENS: *p = c->tokens + (size_t)s * c->max_seq; *nbytes = (uint64_t)c->max_seq * 4; break;
+    default: return fail(c, PACER_EINVAL, "peek: unknown buffer %d", what);
+  }
+  return PACER_OK;
+}
+
+int32_t pacer_profile_enable(pacer_ctx* c, int32_t on) {
+  if (!c) return PACER_EINVAL;
+  if (!c->ws_bound) return fail(c, PACER_ESTATE, "workspace not bound");
+  if (on && c->ev.empty()) {
+    c->ev.resize(kProfEvents);
+    for (auto& e : c->ev) HIPCHK(c, hipEventCreate(&e));
+  }
+  c->prof = on != 0;
+  return PACER_OK;
+}
+
+int32_t pacer_profile_read(pacer_ctx* c, int64_t* n_launches, double* total_ms, double* weight_bytes) {
+  if (!c) return PACER_EINVAL;
+  if (!c->ws_bound) return fail(c, PACER_ESTATE, "workspace not bound");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  double ms = 0.0;
+  for (int i = 0; i + 1 < c->n_ev; i += 2) {
+    float t = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&t, c->ev[i], c->ev[i + 1]));
+    ms += t;
+  }
+  if (n_launches) *n_launches = c->n_ev / 2;
+  if (total_ms) *total_ms = ms;
+  if (weight_bytes) *weight_bytes = c->prof_bytes;
+  c->n_ev = 0;
+  c->prof_bytes = 0.0;
+  return PACER_OK;
+}
+
+}  // extern "C"

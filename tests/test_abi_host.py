@@ -1,0 +1,101 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and validates
+arguments on the host before touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    so = os.path.join(ROOT, "paper_2602_01274_amd", "libpacer.so")
+    if not os.path.exists(so):
+        import __graft_entry__ as g
+        g.build()
+    import paper_2602_01274_amd.binding as b
+    return b
+
+
+def test_library_exports_every_declared_symbol(B):
+    hdr = open(os.path.join(ROOT, "include", "pacer.h")).read()
+    declared = set(re.findall(r"\b(pacer_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(B._lib, name) is not None
+
+
+def _cfgs(B, **over):
+    t = dict(n_layers=2, d_model=128, n_heads=2, head_dim=64, d_ffn=256, vocab=64, rope_theta=1e4, rms_eps=1e-5)
+    t.update(over)
+    return B.model_cfg(t, 64, "bf16"), B.model_cfg(dict(t, n_layers=1), 64, "bf16")
+
+
+def test_create_validates_shapes(B):
+    t, d = _cfgs(B)
+    ctx = B.pacer_create(t, d, B.PvCfg(2, 8, 0.5, 1.05), 1, 0)
+    assert B.pacer_workspace_bytes(ctx) > 0
+    assert B.pacer_kv_bytes(ctx, B.TARGET) == 1 * 2 * 2 * 64 * 128 * 2
+    B.pacer_destroy(ctx)
+    bad = [
+        (dict(head_dim=32), B.PvCfg(2, 8, 0.5, 1.05), 1),       # unsupported head size
+        (dict(d_model=120), B.PvCfg(2, 8, 0.5, 1.05), 1),       # heads * head_dim != d_model
+        (dict(d_ffn=250), B.PvCfg(2, 8, 0.5, 1.05), 1),         # bf16 needs multiples of 32
+        (dict(), B.PvCfg(3, 8, 0.5, 1.05), 1),                  # gamma_max not a multiple of b
+        (dict(), B.PvCfg(0, 8, 0.5, 1.05), 1),
+        (dict(), B.PvCfg(2, 8, 0.5, 1.05), 17),                 # batch too large
+        (dict(), B.PvCfg(2, 8, 0.5, 0.0), 1),                   # rho must be positive
+    ]
+    for over, pv, mb in bad:
+        t, d = _cfgs(B, **over)
+        with pytest.raises(B.PacerError) as e:
+            B.pacer_create(t, d, pv, mb, 0)
+        assert e.value.code == B.EINVAL
+
+
+def test_calls_out_of_order_and_bad_arguments_fail_on_the_host(B):
+    import numpy as np
+    t, d = _cfgs(B)
+    ctx = B.pacer_create(t, d, B.PvCfg(2, 8, 0.5, 1.05), 2, 0)
+
+    class Fake:            # a host buffer posing as a tensor: bind only records the pointer
+        def __init__(self, nbytes):
+            self.a = np.zeros(nbytes + 512, dtype=np.uint8)
+            self.n = nbytes
+        def data_ptr(self):
+            return (self.a.ctypes.data + 255) // 256 * 256
+        def numel(self):
+            return self.n
+        def element_size(self):
+            return 1
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_bind(ctx, B.TARGET, B.T_WO, 0, Fake(100))
+    assert e.value.code == B.EINVAL and "expects" in str(e.value)
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_bind(ctx, B.TARGET, B.T_WO, 5, Fake(128 * 128 * 2))
+    assert e.value.code == B.EINVAL
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_bind(ctx, B.TARGET, B.T_CLS, 0, Fake(2 * 128 * 4))     # M_B-only tensor
+    assert e.value.code == B.EINVAL
+    keep = Fake(128 * 128 * 2)
+    B.pacer_bind(ctx, B.TARGET, B.T_WO, 1, keep)
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_bind_kv(ctx, B.DRAFT, Fake(10))
+    assert e.value.code == B.EINVAL
+    # nothing bound yet: every hot call reports a state error, never reaches the GPU
+    for call in (lambda: B.pacer_begin_step(ctx, 0),
+                 lambda: B.pacer_draft_step(ctx, [0], B.GREEDY, 0, 0),
+                 lambda: B.pacer_verify(ctx, [0], None, Fake(8)),
+                 lambda: B.pacer_prefill(ctx, 0, Fake(8))):
+        with pytest.raises(B.PacerError) as e:
+            call()
+        assert e.value.code == B.ESTATE
+    assert "workspace" in B.pacer_last_error(ctx)
+    st = B.pacer_get_state(ctx, 1)
+    assert st["len"] == 0 and st["n_accepted"] == -1
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_get_state(ctx, 2)
+    assert e.value.code == B.EINVAL
+    B.pacer_destroy(ctx)
