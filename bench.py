@@ -1,0 +1,183 @@
+"""Benchmark of the Pacer hot path on one MI355X.
+
+One "step" is one outer iteration of Alg. 1 through the four hot calls (b x draft_step +
+preverify_block per round, verify, accept_rollback) on the 7B/68M-shaped synthetic pair:
+512-token uniform-random prompt, stochastic sampling at temperature 1, gamma_max 16, b 4, beta 3.
+Prints ONE JSON line (see the fields at the bottom).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def weight_bytes(shape, n_layers=None):
+    d, f, v = shape["d_model"], shape["d_ffn"], shape["vocab"]
+    L = shape["n_layers"] if n_layers is None else n_layers
+    return 2.0 * (L * (4 * d * d + 3 * d * f) + v * d)
+
+
+def run_steps(sess, n, mode, seed, **kw):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    toks, gam, acc = 0, 0, 0
+    for _ in range(n):
+        r = sess.step(mode=mode, seed=seed, **kw)
+        toks += r["n"] + 1
+        gam += r["gamma"]
+        acc += r["n"]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dict(tokens=toks, seconds=dt, tok_s=toks / dt, ms_per_step=1e3 * dt / n,
+                mean_gamma=gam / n, tau=acc / n)
+
+
+def cpu_baseline(w, tgt, drf, mb, prompt, mode, budget_steps=2, n_prompt=16):
+    """The CPU oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    import numpy as np
+    import helpers
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=3, max_seq=n_prompt + 64)
+    o.prefill(prompt[:n_prompt])
+    t0 = time.perf_counter()
+    toks = 0
+    for _ in range(budget_steps):
+        r = o.step()
+        toks += r["n"] + 1
+    dt = time.perf_counter() - t0
+    return {"value": toks / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{budget_steps} Pacer steps ({toks} tokens, {dt:.1f} s) of the same pair after a "
+                      f"{n_prompt}-token prompt; numpy float64 oracle, BLAS threads = cores"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="7b")
+    ap.add_argument("--layers", type=int, default=None, help="truncate target depth (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context", action="store_true", help="skip the AR / fixed-gamma context runs")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_01274_amd import synth
+    from paper_2602_01274_amd import binding as B
+    from paper_2602_01274_amd.engine import Session
+
+    torch.cuda.set_device(0)
+    w = synth.workload(a.workload)
+    mode = B.SAMPLE if w["mode"] == "sample" else B.GREEDY
+    K, W = a.steps, a.warmup
+    n_prompt = w["prompt"]
+    max_seq = n_prompt + (K + W) * (w["gamma_max"] + 1) + 64
+    tgt, drf, mb = synth.make_pair(w, seed=0, device="cuda", n_layers_target=a.layers)
+    prompt = synth.make_prompt(w["target"]["vocab"], n_prompt, 1).tolist()
+    sess = Session(w, tgt, drf, mb, max_seq=max_seq)
+    host = None
+    if not a.no_cpu_baseline:
+        to_host = lambda x: ({k: to_host(v) for k, v in x.items()} if isinstance(x, dict)
+                             else [to_host(v) for v in x] if isinstance(x, list) else x.cpu())
+        host = (to_host(tgt), to_host(drf), to_host(mb))
+    del tgt, drf, mb
+    torch.cuda.empty_cache()
+
+    def fresh():
+        sess.prefill(prompt)
+        sess.counts = dict(draft=0, target=0, preverify=0)
+
+    # ---- the timed region: W warm-up steps, then exactly K steps ----
+    fresh()
+    run_steps(sess, W, mode, 3)
+    main_run = run_steps(sess, K, mode, 3)
+    counts = dict(sess.counts)
+
+    # ---- same K steps with HIP events around every launch of the weight-streaming GEMM ----
+    fresh()
+    run_steps(sess, W, mode, 3)
+    B.pacer_profile_enable(sess.ctx, True)
+    B.pacer_profile_read(sess.ctx)
+    prof_steps = min(K, 40)
+    run_steps(sess, prof_steps, mode, 3)
+    n_launch, gemm_ms, gemm_bytes = B.pacer_profile_read(sess.ctx)
+    B.pacer_profile_enable(sess.ctx, False)
+
+    # ---- per-call timing (events around each C call) ----
+    fresh()
+    run_steps(sess, W, mode, 3)
+    sess.timers = {}
+    run_steps(sess, prof_steps, mode, 3)
+    tm = sess.read_timers()
+    sess.timers = None
+    L = a.layers if a.layers else w["target"]["n_layers"]
+    ctx_len = n_prompt + 0.5 * main_run["tokens"]
+    kv_t = 2.0 * 2 * w["target"]["d_model"] * L * ctx_len
+    kv_d = 2.0 * 2 * w["draft"]["d_model"] * w["draft"]["n_layers"] * ctx_len
+    alg = {"verify": weight_bytes(w["target"], L) + kv_t,
+           "draft_step": weight_bytes(w["draft"]) + kv_d,
+           "preverify_block": weight_bytes(w["draft"], 1) - 2.0 * w["draft"]["vocab"] * w["draft"]["d_model"] + kv_d / w["draft"]["n_layers"]}
+    calls = {}
+    for name, ts in tm.items():
+        ms = sum(ts) / len(ts)
+        calls[name] = {"mean_ms": round(ms, 4), "n": len(ts)}
+        if name in alg:
+            calls[name]["algorithmic_GB"] = round(alg[name] / 1e9, 4)
+            calls[name]["GBps"] = round(alg[name] / 1e6 / ms, 1)
+            calls[name]["hbm_frac"] = round(alg[name] / 1e6 / ms / HBM_PEAK_GBS, 4)
+
+    context = {}
+    if not a.no_context:
+        n_ctx = max(8, K // 4)
+        fresh(); run_steps(sess, 3, mode, 3, fixed_gamma=0)
+        context["autoregressive_tok_s"] = round(run_steps(sess, n_ctx, mode, 3, fixed_gamma=0)["tok_s"], 2)
+        for g in (4, 8):
+            fresh(); run_steps(sess, 3, mode, 3, fixed_gamma=g)
+            context[f"fixed_gamma_{g}_tok_s"] = round(run_steps(sess, n_ctx, mode, 3, fixed_gamma=g)["tok_s"], 2)
+
+    cpu = None
+    if host is not None:
+        cpu = cpu_baseline(w, host[0], host[1], host[2], prompt, 1 if mode == B.SAMPLE else 0)
+
+    achieved = gemm_bytes / 1e9 / (gemm_ms / 1e3) if gemm_ms > 0 else 0.0
+    out = {
+        "metric": "decode tokens/s (7B-shape target, bs1) + verify-step achieved HBM GB/s",
+        "value": round(main_run["tok_s"], 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(main_run["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: {L}-layer d{w['target']['d_model']} target + 68M-shaped draft, "
+                               f"prompt {n_prompt}, {'sampling T=1' if mode else 'greedy'}, gamma_max {w['gamma_max']}, "
+                               f"b {w['block']}, beta {w['beta']}, t0 {w['t0']}, rho {w['rho']}",
+                   "batch": 1, "new_tokens": main_run["tokens"]},
+        "tau": round(main_run["tau"], 3), "mean_gamma": round(main_run["mean_gamma"], 3),
+        "forwards": counts, "verify_GBps": calls.get("verify", {}).get("GBps"),
+        "calls": calls, "context": context,
+        "roofline": {"bound": "hbm", "kernel": "gemm_w16_kernel (all instantiations, all launches of the run)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launches": int(n_launch), "avg_launch_us": round(1e3 * gemm_ms / max(1, n_launch), 3),
+                     "avg_launch_bytes": round(gemm_bytes / max(1, n_launch), 1)},
+        "cpu_baseline": cpu,
+    }
+    sess.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

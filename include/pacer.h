@@ -79,7 +79,7 @@ typedef struct pacer_ctx pacer_ctx;
 typedef struct {
   int32_t n_layers, d_model, n_heads, head_dim /* 64 or 128 */, d_ffn, vocab, max_seq;
   float rope_theta, rms_eps;
-  int32_t dtype; /* PACER_F32 or PACER_BF16: type of matrices, embedding and KV cache */
+  int32_t dtype; /* PACER_F32 or PACER_BF16: type of the matrices and the embedding */
 } pacer_model_cfg;
 
 /* Inputs of Alg. 1: block size b, initial threshold t, growth factor rho; gamma_max caps the
@@ -108,8 +108,8 @@ int32_t pacer_bind(pacer_ctx* ctx, int32_t which, int32_t tensor_id, int32_t lay
                    const void* dev_ptr, uint64_t nbytes);
 
 /* KV cache of one model for all max_batch sequences:
- * [max_batch][n_layers][2 (K,V)][max_seq][d_model] in the model dtype.  Contents need not be
- * initialised.  pacer_kv_bytes returns the exact size pacer_bind_kv expects. */
+ * [max_batch][n_layers][2 (K,V)][max_seq][d_model]; elements are f32 for a PACER_F32 model and
+ * 2-byte IEEE half floats for a PACER_BF16 model.  Contents need not be initialised.  pacer_kv_bytes returns the exact size pacer_bind_kv expects. */
 uint64_t pacer_kv_bytes(const pacer_ctx* ctx, int32_t which);
 int32_t pacer_bind_kv(pacer_ctx* ctx, int32_t which, void* dev_ptr, uint64_t nbytes);
 

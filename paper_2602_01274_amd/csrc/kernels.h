@@ -9,7 +9,9 @@
 //   packed weights ..... bf16, same tiling: tile (nt, kt) holds outputs nt*16..+15 and inputs
 //                        kt*32..+31, tiles ordered [nt][kt], so a wave that walks along K for
 //                        one output tile reads one contiguous stream.
-//   KV cache ........... [seq][layer][K|V][position][d_model]
+//   KV cache ........... [seq][layer][K|V][position][d_model]; f32 for f32 models, IEEE f16 for bf16
+//                        models (same bytes as bf16, 3 more mantissa bits: K after RoPE and V are
+//                        O(1) quantities, so range is no concern and rounding is what matters)
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -52,6 +54,7 @@ template <> __device__ __forceinline__ float ld_f32<uint16_t>(const uint16_t* p)
 template <typename T> __device__ __forceinline__ void st_f32(T* p, float v);
 template <> __device__ __forceinline__ void st_f32<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void st_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+template <> __device__ __forceinline__ void st_f32<_Float16>(_Float16* p, float v) { *p = (_Float16)v; }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -440,12 +443,14 @@ __global__ void rope_append_kernel(float* __restrict__ qkv, int ld, const float*
 // tiles of the chunk; the chunk's (max, sum, weighted values) go to `part` for attn_combine.
 template <typename KVT> struct KvWords;
 template <> struct KvWords<float> { static constexpr int per_word = 1; };
-template <> struct KvWords<uint16_t> { static constexpr int per_word = 2; };
+template <> struct KvWords<_Float16> { static constexpr int per_word = 2; };
+__device__ __forceinline__ float f16lo(uint32_t w) { return (float)__builtin_bit_cast(half2v, w)[0]; }
+__device__ __forceinline__ float f16hi(uint32_t w) { return (float)__builtin_bit_cast(half2v, w)[1]; }
 template <typename KVT> __device__ __forceinline__ float kv_dim(const uint32_t* row, int dim);
 template <> __device__ __forceinline__ float kv_dim<float>(const uint32_t* row, int dim) { return __uint_as_float(row[dim]); }
-template <> __device__ __forceinline__ float kv_dim<uint16_t>(const uint32_t* row, int dim) {
+template <> __device__ __forceinline__ float kv_dim<_Float16>(const uint32_t* row, int dim) {
   const uint32_t w = row[dim >> 1];
-  return __uint_as_float((dim & 1) ? (w & 0xffff0000u) : (w << 16));
+  return (dim & 1) ? f16hi(w) : f16lo(w);
 }
 
 template <typename KVT, int HD>
@@ -507,7 +512,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
       for (int w = 0; w < WORDS; ++w) {
         const uint32_t kw = krow[w];
         if (KvWords<KVT>::per_word == 2) {
-          const float k0 = __uint_as_float(kw << 16), k1 = __uint_as_float(kw & 0xffff0000u);
+          const float k0 = f16lo(kw), k1 = f16hi(kw);
 #pragma unroll
           for (int i = 0; i < ATT_MAXR / 4; ++i) {
             const int r = wv + 4 * i;

@@ -251,7 +251,7 @@ void run_layers(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool kv_
   for (int l = 0; l < g.n_layers; ++l) {
     rmsnorm(c, m, m.attn_norm[l], R, nullptr, sr);
     gemm(c, m, m.wqkv[l], c->xn, c->kmax, c->qkv, 3 * c->dmax, R, 3 * d, d, 0, none, ROWMAP_ID);
-    if (g.dtype == PACER_BF16) attention_t<uint16_t>(c, m, l, R, sr, kv_only);
+    if (g.dtype == PACER_BF16) attention_t<_Float16>(c, m, l, R, sr, kv_only);
     else attention_t<float>(c, m, l, R, sr, kv_only);
     if (kv_only) continue;
     gemm(c, m, m.wo[l], c->ao, c->dmax, c->x, c->dmax, R, d, d, 1, none, ROWMAP_ID);

@@ -55,6 +55,7 @@ class Session:
         self.next_tok = torch.zeros(max_batch, dtype=torch.int32, device="cuda")
         self.step_idx = [0] * max_batch
         self.counts = dict(draft=0, target=0, preverify=0)
+        self.timers = None                  # dict name -> [(start_event, stop_event)] when timing calls
         torch.cuda.synchronize()
 
     # ---- weight upload -------------------------------------------------------------------
@@ -122,6 +123,22 @@ class Session:
         n = B.pacer_get_state(self.ctx, seq)["len"]
         return self._peek(seq, B.PEEK_TOKENS, torch.int32)[:n].tolist()
 
+    # ---- per-call timing (benchmarks) ------------------------------------------------------
+    def _call(self, name, fn, *a):
+        if self.timers is None:
+            return fn(*a)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn(*a)
+        e1.record()
+        self.timers.setdefault(name, []).append((e0, e1))
+
+    def read_timers(self):
+        torch.cuda.synchronize()
+        out = {k: [a.elapsed_time(b) for a, b in v] for k, v in (self.timers or {}).items()}
+        self.timers = {} if self.timers is not None else None
+        return out
+
     # ---- decoding --------------------------------------------------------------------------
     def prefill(self, prompt, seq=0):
         t = torch.as_tensor(prompt, dtype=torch.int32).to("cuda")
@@ -141,16 +158,16 @@ class Session:
         gamma, rnd = 0, 0
         if fixed_gamma is not None:
             for _ in range(fixed_gamma):
-                B.pacer_draft_step(ctx, seqs, mode, seed, ctr)
+                self._call("draft_step", B.pacer_draft_step, ctx, seqs, mode, seed, ctr)
             gamma = fixed_gamma
             self.counts["draft"] += gamma
         else:
             while True:
                 for _ in range(self.block):
-                    B.pacer_draft_step(ctx, seqs, mode, seed, ctr)
+                    self._call("draft_step", B.pacer_draft_step, ctx, seqs, mode, seed, ctr)
                 gamma += self.block
                 self.counts["draft"] += self.block
-                B.pacer_preverify_block(ctx, seqs, self.alpha, self.stop)
+                self._call("preverify_block", B.pacer_preverify_block, ctx, seqs, self.alpha, self.stop)
                 self.counts["preverify"] += 1
                 stop = bool(self.stop[0].item())                  # the only read-back of the drafting loop
                 if record:
@@ -161,9 +178,10 @@ class Session:
                 rnd += 1
                 if stop or gamma + self.block > self.gamma_max:
                     break
-        B.pacer_verify(ctx, seqs, None, self.logits)
+        self._call("verify", B.pacer_verify, ctx, seqs, None, self.logits)
         self.counts["target"] += 1
-        B.pacer_accept_rollback(ctx, seqs, mode, [beta], seed, ctr, self.logits, self.n_acc, self.next_tok)
+        self._call("accept_rollback", B.pacer_accept_rollback, ctx, seqs, mode, [beta], seed, ctr, self.logits,
+                   self.n_acc, self.next_tok)
         st = B.pacer_get_state(ctx, seq)
         self.step_idx[seq] += 1
         out = dict(gamma=gamma, n=st["n_accepted"], z=st["next_token"], len=st["len"])
