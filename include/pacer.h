@@ -99,17 +99,23 @@ void pacer_destroy(pacer_ctx* ctx);
 const char* pacer_last_error(const pacer_ctx* ctx);
 
 /* Re-tiles a row-major bf16 matrix [n_out][n_in] (dev_src) into the layout the bf16 kernels
- * stream (dev_dst, same size, must not alias).  Enqueued on hip_stream. */
+ * stream (dev_dst, same size, must not alias).  The tiling depends on the role of the matrix:
+ * tensor_id is the PACER_T_* id it will be bound as (WQKV, WO, WGU, WD or HEAD); head_dim is
+ * needed for WQKV (rotation pairs of a head share a tile) and ignored otherwise.
+ * Enqueued on hip_stream. */
 int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int32_t n_in,
-                          void* hip_stream);
+                          int32_t tensor_id, int32_t head_dim, void* hip_stream);
 
 /* Borrow one weight tensor.  nbytes must equal the tensor's size for the model's shape. */
 int32_t pacer_bind(pacer_ctx* ctx, int32_t which, int32_t tensor_id, int32_t layer,
                    const void* dev_ptr, uint64_t nbytes);
 
-/* KV cache of one model for all max_batch sequences:
- * [max_batch][n_layers][2 (K,V)][max_seq][d_model]; elements are f32 for a PACER_F32 model and
- * 2-byte IEEE half floats for a PACER_BF16 model.  Contents need not be initialised.  pacer_kv_bytes returns the exact size pacer_bind_kv expects. */
+/* KV cache of one model for all max_batch sequences, max_batch * n_layers * 2 * max_seq *
+ * d_model elements: f32 for a PACER_F32 model ([seq][layer][K|V][position][d_model]), 2-byte
+ * IEEE half floats for a PACER_BF16 model ([seq][layer] x { K as [position][d_model], then V
+ * transposed as [d_model][max_seq] }; max_seq must be a multiple of 32).  The layout is the
+ * library's own; contents need not be initialised.  pacer_kv_bytes returns the exact size
+ * pacer_bind_kv expects. */
 uint64_t pacer_kv_bytes(const pacer_ctx* ctx, int32_t which);
 int32_t pacer_bind_kv(pacer_ctx* ctx, int32_t which, void* dev_ptr, uint64_t nbytes);
 

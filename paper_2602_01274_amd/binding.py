@@ -56,7 +56,7 @@ def _load():
         "pacer_create": (i32, [C.POINTER(vp), C.POINTER(ModelCfg), C.POINTER(ModelCfg), C.POINTER(PvCfg), i32, vp]),
         "pacer_destroy": (None, [vp]),
         "pacer_last_error": (C.c_char_p, [vp]),
-        "pacer_pack_weight": (i32, [vp, vp, i32, i32, vp]),
+        "pacer_pack_weight": (i32, [vp, vp, i32, i32, i32, i32, vp]),
         "pacer_bind": (i32, [vp, i32, i32, i32, vp, u64]),
         "pacer_kv_bytes": (u64, [vp, i32]),
         "pacer_bind_kv": (i32, [vp, i32, vp, u64]),
@@ -118,9 +118,9 @@ def pacer_last_error(ctx):
     return _lib.pacer_last_error(ctx).decode()
 
 
-def pacer_pack_weight(dst, src, stream):
+def pacer_pack_weight(dst, src, tensor_id, head_dim, stream):
     n_out, n_in = src.shape
-    _chk(None, _lib.pacer_pack_weight(_ptr(dst), _ptr(src), n_out, n_in, C.c_void_p(stream)))
+    _chk(None, _lib.pacer_pack_weight(_ptr(dst), _ptr(src), n_out, n_in, tensor_id, head_dim, C.c_void_p(stream)))
 
 
 def pacer_bind(ctx, which, tensor_id, layer, t):

@@ -129,20 +129,6 @@ __device__ __forceinline__ uint4 vocab_bits(uint64_t seed, int seq, uint32_t ste
   return philox4x32_10(make_uint4(blk, row, step, purpose | ((uint32_t)seq << 8)), (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
-// ------------------------------------------------------------------ weight re-tiling
-__global__ void pack_weight_kernel(uint4* __restrict__ dst, const uint16_t* __restrict__ src, int N, int K) {
-  const int KT = K >> 5;
-  const size_t total = (size_t)(N >> 4) * KT * 64;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-    const int lane = (int)(i & 63);
-    const size_t tile = i >> 6;
-    const int kt = (int)(tile % KT);
-    const int nt = (int)(tile / KT);
-    const uint16_t* p = src + (size_t)(nt * 16 + (lane & 15)) * K + kt * 32 + (lane >> 4) * 8;
-    dst[i] = *reinterpret_cast<const uint4*>(p);
-  }
-}
-
 // ------------------------------------------------------------------ embedding gather
 // token of (sequence, position): committed token below len, else the draft made at that position
 template <typename T>
@@ -219,18 +205,6 @@ __global__ void rmsnorm_pack_kernel(const float* __restrict__ x, int ldx, const 
   }
 }
 
-// f32 rows -> packed f16 operand (grid: MT_total*16 rows; rows >= R zero filled)
-__global__ void pack_act_kernel(const float* __restrict__ src, int lds, int R, int K, _Float16* __restrict__ xp, int MT_total) {
-  const int r = blockIdx.x;
-  const int ng = K >> 3;
-  for (int kg = threadIdx.x; kg < ng; kg += blockDim.x) {
-    float v[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = r < R ? src[(size_t)r * lds + kg * 8 + i] : 0.f;
-    store_packed8(xp, MT_total, r, kg * 8, v);
-  }
-}
-
 // SwiGLU: act = silu(gate) * up for gu = [gate | up] rows; f32 out + optional packed operand
 __global__ void swiglu_pack_kernel(const float* __restrict__ gu, int ldg, int R, int F, float* __restrict__ act, int lda,
                                    _Float16* __restrict__ xp, int MT_total) {
@@ -266,11 +240,7 @@ __device__ __forceinline__ int map_row(const SeqRows& sr, int mode, int G1, int 
   return sr.seq[si] * G1 + (sr.pos0[si] + rr - (sr.len[si] - 1));
 }
 
-// ------------------------------------------------------------------ weight-streaming small-M GEMM
-// out[m][n] (+)= sum_k X[m][k] * W[n][k]  for m < R <= 16*MT, bf16 packed W, f16 packed X, f32 accumulate
-// on v_mfma_f32_16x16x32_f16.  One block = NT adjacent output tiles; its WAVES waves split K into
-// contiguous ranges, each wave streaming its part of the weight tiles straight from HBM into
-// registers (bf16 -> f16 is exact for normal-range weights), partial sums meet in LDS in a fixed order.
+// bf16 -> f16 of one weight tile fragment (exact for normal-range weights)
 __device__ __forceinline__ half8 bf16x8_to_f16x8(u32x4 w) {
   half8 h;
   const uint32_t u[4] = {w[0], w[1], w[2], w[3]};
@@ -281,93 +251,6 @@ __device__ __forceinline__ half8 bf16x8_to_f16x8(u32x4 w) {
     h[2 * i + 1] = (_Float16)hi;
   }
   return h;
-}
-
-template <int MT, int NT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const u32x4* __restrict__ Wp, const u32x4* __restrict__ Xp,
-                                                              float* __restrict__ out, int ldo, int R, int KT, int mt0,
-                                                              int MT_total, int accumulate, SeqRows sr, int rowmap, int G1) {
-  constexpr int U = 4;
-  __shared__ f32x4 red[WAVES][NT * MT][64];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nt0 = blockIdx.x * NT;
-  const int per = (KT + WAVES - 1) / WAVES;
-  const int kb = wave * per;
-  const int ke = min(KT, kb + per);
-  f32x4 acc[NT][MT];
-#pragma unroll
-  for (int a = 0; a < NT; ++a)
-#pragma unroll
-    for (int b = 0; b < MT; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  const u32x4* wp[NT];
-#pragma unroll
-  for (int a = 0; a < NT; ++a) wp[a] = Wp + (size_t)(nt0 + a) * KT * 64 + lane;
-  const u32x4* xp = Xp + (size_t)mt0 * 64 + lane;
-
-  u32x4 A0[U][NT], A1[U][NT], B0[U][MT], B1[U][MT];
-  const u32x4 zero = {0u, 0u, 0u, 0u};
-  auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][MT], int k0) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kt = k0 + u;
-      if (kt < ke) {
-#pragma unroll
-        for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + (size_t)kt * 64);
-#pragma unroll
-        for (int b = 0; b < MT; ++b) B[u][b] = xp[((size_t)kt * MT_total + b) * 64];
-      } else {
-#pragma unroll
-        for (int a = 0; a < NT; ++a) A[u][a] = zero;
-#pragma unroll
-        for (int b = 0; b < MT; ++b) B[u][b] = zero;
-      }
-    }
-  };
-  auto compute = [&](u32x4(&A)[U][NT], u32x4(&B)[U][MT]) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      half8 bh[MT];
-#pragma unroll
-      for (int b = 0; b < MT; ++b) bh[b] = __builtin_bit_cast(half8, B[u][b]);
-#pragma unroll
-      for (int a = 0; a < NT; ++a) {
-        const half8 ah = bf16x8_to_f16x8(A[u][a]);
-#pragma unroll
-        for (int b = 0; b < MT; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[b], acc[a][b], 0, 0, 0);
-      }
-    }
-  };
-  load(A0, B0, kb);
-  for (int k0 = kb; k0 < ke; k0 += 2 * U) {
-    load(A1, B1, k0 + U);
-    compute(A0, B0);
-    load(A0, B0, k0 + 2 * U);
-    compute(A1, B1);
-  }
-#pragma unroll
-  for (int a = 0; a < NT; ++a)
-#pragma unroll
-    for (int b = 0; b < MT; ++b) red[wave][a * MT + b][lane] = acc[a][b];
-  __syncthreads();
-  // D tile: lane l holds column j = l%16 (the activation row) and rows 4*(l/16)..+3 (outputs)
-  for (int t = threadIdx.x; t < NT * MT * 64; t += WAVES * 64) {
-    const int l = t & 63, ab = t >> 6;
-    const int a = ab / MT, b = ab % MT;
-    f32x4 s = red[0][ab][l];
-#pragma unroll
-    for (int w = 1; w < WAVES; ++w) s += red[w][ab][l];
-    const int m = (mt0 + b) * 16 + (l & 15);
-    if (m < R) {
-      const int n = (nt0 + a) * 16 + (l >> 4) * 4;
-      float* o = out + (size_t)map_row(sr, rowmap, G1, m) * ldo + n;
-      if (accumulate) {
-        const f32x4 old = *reinterpret_cast<const f32x4*>(o);
-        s += old;
-      }
-      *reinterpret_cast<f32x4*>(o) = s;
-    }
-  }
 }
 
 // Plain f32 GEMM for f32 models and tiny heads: one wave per output feature, rows in groups of 8.

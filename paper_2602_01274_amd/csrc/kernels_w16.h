@@ -1,0 +1,536 @@
+// Fused kernels of the bf16-weight path (gfx950, wave64, v_mfma_f32_16x16x32_f16).
+//
+// One decoder layer is six launches:
+//   QKV GEMM   (epilogue: row scale of the RMSNorm, RoPE, Q -> f16 attention operand, K/V -> cache)
+//   attention  (MFMA scores and weighted values, one wave per 128..-key range, no LDS)
+//   combine    (merge the ranges, write the f16 operand of the O projection)
+//   O GEMM     (epilogue: residual add, next norm's operand x*g as f16, row sum of squares)
+//   gate/up GEMM (epilogue: row scale, SwiGLU, f16 operand of the down projection)
+//   down GEMM  (epilogue: residual add, next norm's operand, row sum of squares)
+//
+// RMSNorm never runs as a kernel: x*g is what the consuming GEMM multiplies, and the per-row factor
+// 1/sqrt(mean x^2 + eps) commutes with the matrix product, so it is applied to the accumulators.  The
+// row sums of squares are accumulated by the producing GEMM's blocks with integer (fixed point,
+// 2^-26) atomics: integer addition is associative, so the result does not depend on block order.
+//
+// Weight tile layouts (written by pack_weight_kernel):
+//   PLAIN   tile nt, row i  <- matrix row 16*nt + i
+//   QKV     Q and K parts: a tile holds 8 rotation pairs of one head: row i<8 <- dim 8t+i, row i+8 <-
+//           dim 8t+i+hd/2 (t = tile within the head); V part plain.  RoPE then stays inside a tile.
+//   GATEUP  tile nt: rows 0..7 <- gate rows 8nt..8nt+7, rows 8..15 <- up rows 8nt..8nt+7.
+// KV cache of a bf16 model, per (sequence, layer): K as [position][d] f16, then V transposed as
+// [d][max_seq] f16, so that both MFMA operands of attention are contiguous 8/16-byte loads.
+#pragma once
+#include "kernels.h"
+
+#define PACK_PLAIN 0
+#define PACK_QKV 1
+#define PACK_GATEUP 2
+
+#define EPI_STORE 0
+#define EPI_RESID 1
+#define EPI_QKV 2
+#define EPI_SWIGLU 3
+
+#define SSQ_SCALE 67108864.0f            // 2^26
+#define SSQ_INV_SCALE 1.4901161193847656e-08f
+
+typedef unsigned long long u64;
+
+__device__ __forceinline__ float row_scale(const u64* ssq, int m, float inv_dim, float eps) {
+  return 1.0f / sqrtf((float)ssq[m] * SSQ_INV_SCALE * inv_dim + eps);
+}
+
+__global__ void pack_weight_kind_kernel(uint4* __restrict__ dst, const uint16_t* __restrict__ src, int N, int K, int kind, int param) {
+  const int KT = K >> 5;
+  const size_t total = (size_t)(N >> 4) * KT * 64;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(idx & 63);
+    const size_t tile = idx >> 6;
+    const int kt = (int)(tile % KT);
+    const int nt = (int)(tile / KT);
+    const int i = lane & 15;
+    int row = nt * 16 + i;
+    if (kind == PACK_QKV) {
+      const int hd = param, d = N / 3;
+      if (row < 2 * d) {
+        const int part = (nt * 16) / d;                 // 0 = Q, 1 = K
+        const int tq = nt - part * (d / 16);            // tile within the part
+        const int tph = hd / 16;                        // tiles per head
+        const int h = tq / tph, t = tq % tph;
+        row = part * d + h * hd + 8 * t + (i & 7) + (i >> 3) * (hd / 2);
+      }
+    } else if (kind == PACK_GATEUP) {
+      const int F = N / 2;
+      row = (i < 8) ? (8 * nt + i) : (F + 8 * nt + (i - 8));
+    }
+    const uint16_t* p = src + (size_t)row * K + kt * 32 + (lane >> 4) * 8;
+    dst[idx] = *reinterpret_cast<const uint4*>(p);
+  }
+}
+
+// ------------------------------------------------------------------ producers of layer-0 input
+// 4 consecutive features of row m into the packed f16 operand
+__device__ __forceinline__ void store_packed4(_Float16* __restrict__ xp, int MT_total, int m, int k0, float a, float b, float c, float d) {
+  const int kt = k0 >> 5, g = (k0 & 31) >> 3, e = k0 & 7;
+  typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+  half4 h = {(_Float16)a, (_Float16)b, (_Float16)c, (_Float16)d};
+  *reinterpret_cast<half4*>(xp + ((size_t)(kt * MT_total + (m >> 4)) * 64 + (g * 16 + (m & 15))) * 8 + e) = h;
+}
+
+// x = E[token]; operand = f16(x * g); ssq slot 0 = sum x^2.  Block 0 also clears the other slots.
+__global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __restrict__ tokens, const int* __restrict__ draft_tok,
+                                 SeqRows sr, int max_seq, int G1, int d, float* __restrict__ x, int ldx, const float* __restrict__ g,
+                                 _Float16* __restrict__ xp, int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  if (r == 0)
+    for (int i = threadIdx.x + slot_stride; i < n_slots * slot_stride; i += blockDim.x) ssq[i] = 0ull;
+  const int si = find_seq(sr, r);
+  const int s = sr.seq[si];
+  const int p = sr.pos0[si] + (r - sr.row_off[si]);
+  const int tok = p < sr.len[si] ? tokens[(size_t)s * max_seq + p] : draft_tok[s * G1 + (p - sr.len[si])];
+  const uint16_t* e = E + (size_t)tok * d;
+  float ss = 0.f;
+  for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
+    const uint2 w = *reinterpret_cast<const uint2*>(e + k);
+    const float v0 = __uint_as_float(w.x << 16), v1 = __uint_as_float(w.x & 0xffff0000u);
+    const float v2 = __uint_as_float(w.y << 16), v3 = __uint_as_float(w.y & 0xffff0000u);
+    *reinterpret_cast<float4*>(x + (size_t)r * ldx + k) = make_float4(v0, v1, v2, v3);
+    store_packed4(xp, MT_total, r, k, v0 * g[k], v1 * g[k + 1], v2 * g[k + 2], v3 * g[k + 3]);
+    ss += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
+  }
+  ss = block_sum(ss, red);
+  if (threadIdx.x == 0) ssq[r] = (u64)(ss * SSQ_SCALE + 0.5f);
+}
+
+// input rows of the pre-verification layer: x = hidden + PosEmb[e]; operand and ssq as above
+__global__ void mb_input_w16_kernel(const float* __restrict__ src, int lds, const float* __restrict__ posemb, SeqRows sr, MbRows mr,
+                                    int d, float* __restrict__ x, int ldx, const float* __restrict__ g, _Float16* __restrict__ xp,
+                                    int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  if (r == 0)
+    for (int i = threadIdx.x + slot_stride; i < n_slots * slot_stride; i += blockDim.x) ssq[i] = 0ull;
+  const int si = find_seq(sr, r);
+  const int rr = r - sr.row_off[si];
+  const float* h = src + (size_t)(mr.src_row0[si] + rr) * lds;
+  const float* e = posemb + (size_t)(mr.e0[si] < 0 ? 0 : mr.e0[si] + rr) * d;
+  float ss = 0.f;
+  for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
+    const float4 a = *reinterpret_cast<const float4*>(h + k), b = *reinterpret_cast<const float4*>(e + k);
+    const float v0 = a.x + b.x, v1 = a.y + b.y, v2 = a.z + b.z, v3 = a.w + b.w;
+    *reinterpret_cast<float4*>(x + (size_t)r * ldx + k) = make_float4(v0, v1, v2, v3);
+    store_packed4(xp, MT_total, r, k, v0 * g[k], v1 * g[k + 1], v2 * g[k + 2], v3 * g[k + 3]);
+    ss += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
+  }
+  ss = block_sum(ss, red);
+  if (threadIdx.x == 0) ssq[r] = (u64)(ss * SSQ_SCALE + 0.5f);
+}
+
+// hidden = x * g * row_scale for R rows (prompt ingestion: feeds M_B's prefix rows)
+__global__ void hidden_rows_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
+                                   float inv_dim, float eps, int d, float* __restrict__ out, int ldo) {
+  const int r = blockIdx.x;
+  const float rs = row_scale(ssq, r, inv_dim, eps);
+  for (int k = threadIdx.x; k < d; k += blockDim.x) out[(size_t)r * ldo + k] = x[(size_t)r * ldx + k] * g[k] * rs;
+}
+
+// ------------------------------------------------------------------ weight-streaming small-M GEMM, fused epilogues
+struct GemmArgs {
+  const u32x4* W;        // packed weights
+  const u32x4* X;        // packed f16 operand [kt][mt_total][lane]
+  int KT, R, mt0, mt_total, nt_begin;
+  const u64* ssq_in;     // row sums of squares of the operand's source rows (null: no row scale)
+  float inv_dim, eps;
+  float* out;            // STORE: [rows][ldo] ; RESID: the residual stream x (read, add, write)
+  int ldo, rowmap, G1;
+  _Float16* xp_out;      // RESID: next operand f16(x*g_next) ; SWIGLU: f16(act)
+  int mt_total_out;
+  const float* g_next;
+  u64* ssq_out;
+  _Float16* qp;          // QKV: attention operand [slot][head][kt][2][lane][8]
+  _Float16* kv;          // QKV: cache base of the model
+  const float* rope;     // QKV: [R][hd/2][2] cos, sin
+  int d, hd, layer, n_layers, max_seq, H;
+  SeqRows sr;
+};
+
+template <int EPI, int MT, int NT, int WAVES, int U, int TAG>
+__global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const GemmArgs ga) {
+  __shared__ f32x4 red[WAVES][NT * MT][64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nt0 = ga.nt_begin + blockIdx.x * NT;
+  const int KT = ga.KT;
+  const int per = (KT + WAVES - 1) / WAVES;
+  const int kb = wave * per;
+  const int ke = min(KT, kb + per);
+  f32x4 acc[NT][MT];
+#pragma unroll
+  for (int a = 0; a < NT; ++a)
+#pragma unroll
+    for (int b = 0; b < MT; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const u32x4* wp[NT];
+#pragma unroll
+  for (int a = 0; a < NT; ++a) wp[a] = ga.W + (size_t)(nt0 + a) * KT * 64 + lane;
+  const u32x4* xp = ga.X + (size_t)ga.mt0 * 64 + lane;
+  const int mtt = ga.mt_total;
+
+  u32x4 A0[U][NT], A1[U][NT], B0[U][MT], B1[U][MT];
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][MT], int k0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kt = k0 + u;
+      if (kt < ke) {
+#pragma unroll
+        for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + (size_t)kt * 64);
+#pragma unroll
+        for (int b = 0; b < MT; ++b) B[u][b] = xp[((size_t)kt * mtt + b) * 64];
+      } else {
+#pragma unroll
+        for (int a = 0; a < NT; ++a) A[u][a] = zero;
+#pragma unroll
+        for (int b = 0; b < MT; ++b) B[u][b] = zero;
+      }
+    }
+  };
+  auto compute = [&](u32x4(&A)[U][NT], u32x4(&B)[U][MT]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      half8 bh[MT];
+#pragma unroll
+      for (int b = 0; b < MT; ++b) bh[b] = __builtin_bit_cast(half8, B[u][b]);
+#pragma unroll
+      for (int a = 0; a < NT; ++a) {
+        const half8 ah = bf16x8_to_f16x8(A[u][a]);
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[b], acc[a][b], 0, 0, 0);
+      }
+    }
+  };
+  load(A0, B0, kb);
+  for (int k0 = kb; k0 < ke; k0 += 2 * U) {
+    load(A1, B1, k0 + U);
+    compute(A0, B0);
+    load(A0, B0, k0 + 2 * U);
+    compute(A1, B1);
+  }
+#pragma unroll
+  for (int a = 0; a < NT; ++a)
+#pragma unroll
+    for (int b = 0; b < MT; ++b) red[wave][a * MT + b][lane] = acc[a][b];
+  __syncthreads();
+
+  // Epilogue.  One wave-sized group of threads per (tile a, row tile b); thread l of the group owns the
+  // accumulator lane l: activation row m = 16*(mt0+b) + l%16, tile rows 4*(l/16)..+3.
+  for (int t = threadIdx.x; t < NT * MT * 64; t += WAVES * 64) {
+    const int l = t & 63, ab = t >> 6;
+    const int a = ab / MT, b = ab % MT;
+    const int g4 = l >> 4;
+    const int m = (ga.mt0 + b) * 16 + (l & 15);
+    const int nt = nt0 + a;
+    const bool paired = (EPI == EPI_SWIGLU) || (EPI == EPI_QKV);
+    f32x4 s = red[0][ab][l];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) s += red[w][ab][l];
+    f32x4 s2 = {0.f, 0.f, 0.f, 0.f};                   // partner rows i+8 (paired layouts, threads with g4 < 2)
+    if (paired && g4 < 2) {
+      s2 = red[0][ab][l + 32];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) s2 += red[w][ab][l + 32];
+    }
+    const bool live = m < ga.R;
+    float rs = 1.f;
+    if (ga.ssq_in && live) rs = row_scale(ga.ssq_in, m, ga.inv_dim, ga.eps);
+
+    if (EPI == EPI_STORE) {
+      if (live) {
+        const int n = nt * 16 + g4 * 4;
+        float* o = ga.out + (size_t)map_row(ga.sr, ga.rowmap, ga.G1, m) * ga.ldo + n;
+        *reinterpret_cast<f32x4*>(o) = s * rs;
+      }
+    } else if (EPI == EPI_RESID) {
+      float sq = 0.f;
+      if (live) {
+        const int n = nt * 16 + g4 * 4;
+        float* o = ga.out + (size_t)m * ga.ldo + n;
+        const f32x4 xn = *reinterpret_cast<const f32x4*>(o) + s;
+        *reinterpret_cast<f32x4*>(o) = xn;
+        const float4 gn = *reinterpret_cast<const float4*>(ga.g_next + n);
+        store_packed4(ga.xp_out, ga.mt_total_out, m, n, xn[0] * gn.x, xn[1] * gn.y, xn[2] * gn.z, xn[3] * gn.w);
+        sq = xn[0] * xn[0] + xn[1] * xn[1] + xn[2] * xn[2] + xn[3] * xn[3];
+      }
+      sq += __shfl_xor(sq, 16, 64);
+      sq += __shfl_xor(sq, 32, 64);
+      if (live && g4 == 0) atomicAdd(ga.ssq_out + m, (u64)(sq * SSQ_SCALE + 0.5f));
+    } else if (EPI == EPI_SWIGLU) {
+      if (live && g4 < 2) {
+        const int f = nt * 8 + g4 * 4;
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float gt = s[r] * rs, up = s2[r] * rs;
+          v[r] = gt / (1.0f + expf(-gt)) * up;
+        }
+        store_packed4(ga.xp_out, ga.mt_total_out, m, f, v[0], v[1], v[2], v[3]);
+      }
+    } else {  // EPI_QKV
+      if (live) {
+        const int d = ga.d, hd = ga.hd, half = hd >> 1;
+        const int si = find_seq(ga.sr, m);
+        const int rl = m - ga.sr.row_off[si];
+        const int pos = ga.sr.pos0[si] + rl;
+        _Float16* Kc = ga.kv + (((size_t)ga.sr.seq[si] * ga.n_layers + ga.layer) * 2) * (size_t)ga.max_seq * d;
+        _Float16* Vt = Kc + (size_t)ga.max_seq * d;
+        const int tiles_d = d >> 4;
+        typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+        if (nt < 2 * tiles_d) {
+          if (g4 < 2) {
+            const int part = nt / tiles_d;
+            const int tq = nt - part * tiles_d;
+            const int tph = hd >> 4;
+            const int h = tq / tph, tt = tq % tph;
+            const int j0 = 8 * tt + 4 * g4;                   // rotation pairs j0..j0+3
+            const float* tb = ga.rope + ((size_t)m * half + j0) * 2;
+            float va[4], vb[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float cs = tb[2 * r], sn = tb[2 * r + 1];
+              const float x0 = s[r] * rs, x1 = s2[r] * rs;
+              va[r] = x0 * cs - x1 * sn;
+              vb[r] = x1 * cs + x0 * sn;
+            }
+            const half4 ha = {(_Float16)va[0], (_Float16)va[1], (_Float16)va[2], (_Float16)va[3]};
+            const half4 hb = {(_Float16)vb[0], (_Float16)vb[1], (_Float16)vb[2], (_Float16)vb[3]};
+            if (part == 0) {
+              // attention operand: [slot][head][kt][2 row tiles][lane][8], lane = 16*(dim%32/8) + row%16
+              const int kts = hd >> 5;
+              auto qidx = [&](int dim) {
+                return ((((size_t)si * ga.H + h) * kts + (dim >> 5)) * 2 + (rl >> 4)) * 512 + (((dim & 31) >> 3) * 16 + (rl & 15)) * 8 + (dim & 7);
+              };
+              *reinterpret_cast<half4*>(ga.qp + qidx(j0)) = ha;
+              *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half)) = hb;
+            } else {
+              _Float16* kr = Kc + (size_t)pos * d + h * hd;
+              *reinterpret_cast<half4*>(kr + j0) = ha;
+              *reinterpret_cast<half4*>(kr + j0 + half) = hb;
+            }
+          }
+        } else {
+          const int c0 = (nt - 2 * tiles_d) * 16 + g4 * 4;       // V feature index
+#pragma unroll
+          for (int r = 0; r < 4; ++r) Vt[(size_t)(c0 + r) * ga.max_seq + pos] = (_Float16)(s[r] * rs);
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ MFMA attention over the f16 KV cache
+// grid (key ranges / 4, heads, sequences), 4 independent waves per block, one key range per wave.
+// Scores: S^T[key][row] = K[key][:] . Q[row][:]  (A = K tile straight from the cache, B = Q operand).
+// Values: O^T[dim][row] += V^T[dim][keys] P^T[keys][row]; the probabilities leave the first MFMA in
+// exactly the lane layout the second one wants for B (contraction index = the 8 keys a lane holds),
+// and V^T rows are contiguous along keys.  Online softmax per query row (= per lane column).
+template <int HD, int MT>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const _Float16* __restrict__ qp, const _Float16* __restrict__ kv, int layer,
+                                                        int n_layers, int max_seq, int d, SeqRows sr, int kpw, int n_part_max, int H,
+                                                        float* __restrict__ part) {
+  constexpr int KTS = HD / 32, DTS = HD / 16;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
+  const int h = blockIdx.y, si = blockIdx.z;
+  const int r0 = sr.row_off[si], Rs = sr.row_off[si + 1] - r0, pos0 = sr.pos0[si];
+  const int n_keys = pos0 + Rs;
+  const int pidx = blockIdx.x * 4 + wave;
+  const int k_begin = pidx * kpw;
+  if (k_begin >= n_keys) return;
+  const int k_end = min(n_keys, k_begin + kpw);
+  const _Float16* Kc = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2) * (size_t)max_seq * d + h * HD;
+  const _Float16* Vt = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2 + 1) * (size_t)max_seq * d + (size_t)h * HD * max_seq;
+  const float scale = 1.0f / sqrtf((float)HD);
+
+  half8 q[KTS][MT];
+#pragma unroll
+  for (int kt = 0; kt < KTS; ++kt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      q[kt][mt] = *reinterpret_cast<const half8*>(qp + ((((size_t)si * H + h) * KTS + kt) * 2 + mt) * 512 + lane * 8);
+  f32x4 acc[DTS][MT];
+  float mrun[MT], lrun[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    mrun[mt] = -INFINITY;
+    lrun[mt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DTS; ++dt) acc[dt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int kk = k_begin; kk < k_end; kk += 32) {
+    // scores of keys kk..kk+31 (two 16-key tiles)
+    f32x4 st[2][MT];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int key = min(kk + 16 * t + j, n_keys - 1);
+      const _Float16* kr = Kc + (size_t)key * d + 8 * g;
+      half8 ka[KTS];
+#pragma unroll
+      for (int kt = 0; kt < KTS; ++kt) ka[kt] = *reinterpret_cast<const half8*>(kr + kt * 32);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kt = 0; kt < KTS; ++kt) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[kt], q[kt][mt], s, 0, 0, 0);
+        st[t][mt] = s;
+      }
+    }
+    // values operand: V^T[dim][keys kk+4g..+3 and kk+16+4g..+3]
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    half8 va[DTS];
+    const bool tail = kk + 32 > n_keys;
+#pragma unroll
+    for (int dt = 0; dt < DTS; ++dt) {
+      const _Float16* vr = Vt + (size_t)(dt * 16 + j) * max_seq + kk + 4 * g;
+      half4 lo = *reinterpret_cast<const half4*>(vr), hi = *reinterpret_cast<const half4*>(vr + 16);
+      if (tail) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (kk + 4 * g + e >= n_keys) lo[e] = (_Float16)0.f;
+          if (kk + 16 + 4 * g + e >= n_keys) hi[e] = (_Float16)0.f;
+        }
+      }
+      va[dt] = half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int pos = pos0 + mt * 16 + j;                // this lane's query row
+      float sv[8];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = kk + 16 * t + 4 * g + r;
+          const float v = (key <= pos && key < n_keys) ? st[t][mt][r] * scale : -INFINITY;
+          sv[t * 4 + r] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(mrun[mt], mx);
+      float ps = 0.f;
+      half8 pb;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float p = (mn == -INFINITY) ? 0.f : expf(sv[e] - mn);
+        ps += p;
+        pb[e] = (_Float16)p;
+      }
+      ps += __shfl_xor(ps, 16, 64);
+      ps += __shfl_xor(ps, 32, 64);
+      const float corr = (mrun[mt] == -INFINITY) ? 0.f : expf(mrun[mt] - mn);
+      lrun[mt] = lrun[mt] * corr + ps;
+      mrun[mt] = mn;
+#pragma unroll
+      for (int dt = 0; dt < DTS; ++dt) {
+        acc[dt][mt] *= corr;
+        acc[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[dt], pb, acc[dt][mt], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int rl = mt * 16 + j;
+    if (rl < Rs) {
+      float* o = part + (((size_t)(r0 + rl) * H + h) * n_part_max + pidx) * (HD + 2);
+#pragma unroll
+      for (int dt = 0; dt < DTS; ++dt) *reinterpret_cast<f32x4*>(o + dt * 16 + 4 * g) = acc[dt][mt];
+      if (g == 0) { o[HD] = mrun[mt]; o[HD + 1] = lrun[mt]; }
+    }
+  }
+}
+
+// merge the key ranges of one (row, head) and write the f16 operand of the O projection
+__global__ void attn_combine_w16_kernel(const float* __restrict__ part, SeqRows sr, int kpw, int n_part_max, int H, int HD,
+                                        _Float16* __restrict__ xp, int MT_total) {
+  const int r = blockIdx.x, h = blockIdx.y, dim = threadIdx.x;
+  const int si = find_seq(sr, r);
+  const int n_keys = sr.pos0[si] + (sr.row_off[si + 1] - sr.row_off[si]);
+  const int n_part = (n_keys + kpw - 1) / kpw;
+  const float* p = part + ((size_t)r * H + h) * n_part_max * (HD + 2);
+  float M = -INFINITY;
+  for (int c = 0; c < n_part; ++c) M = fmaxf(M, p[(size_t)c * (HD + 2) + HD]);
+  float L = 0.f, a = 0.f;
+  for (int c = 0; c < n_part; ++c) {
+    const float m = p[(size_t)c * (HD + 2) + HD];
+    if (m == -INFINITY) continue;
+    const float w = expf(m - M);
+    L += p[(size_t)c * (HD + 2) + HD + 1] * w;
+    a += p[(size_t)c * (HD + 2) + dim] * w;
+  }
+  const int k = h * HD + dim;
+  xp[((size_t)((k >> 5) * MT_total + (r >> 4)) * 64 + (((k & 31) >> 3) * 16 + (r & 15))) * 8 + (k & 7)] = (_Float16)(a / L);
+}
+
+// ------------------------------------------------------------------ tail of a draft forward
+// one block per listed sequence: hidden state h = x * g_final * row_scale into the ring, then the token
+__global__ __launch_bounds__(1024) void draft_tail_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g,
+                                                          const u64* __restrict__ ssq, float inv_dim, float eps, int d,
+                                                          float* __restrict__ hidden, const float* __restrict__ ring,
+                                                          int* __restrict__ draft_tok, PickArgs pa, int G1, int V, int mode,
+                                                          uint64_t seed, uint32_t step) {
+  __shared__ float redv[16];
+  __shared__ int redi[16];
+  const int si = blockIdx.x, s = pa.seq[si], j = pa.j[si];
+  const float rs = row_scale(ssq, si, inv_dim, eps);
+  float* ho = hidden + (size_t)(s * G1 + j) * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) ho[k] = x[(size_t)si * ldx + k] * g[k] * rs;
+  const float* lg = ring + (size_t)(s * G1 + j) * V;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int blk = threadIdx.x; blk * 4 < V; blk += blockDim.x) {
+    float g4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (mode) {
+      const uint4 b = vocab_bits(seed, s, step, (uint32_t)(j + 1), PURPOSE_DRAFT, (uint32_t)blk);
+      g4[0] = gumbel(u01(b.x)); g4[1] = gumbel(u01(b.y)); g4[2] = gumbel(u01(b.z)); g4[3] = gumbel(u01(b.w));
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int v = blk * 4 + e;
+      if (v < V) {
+        const float val = lg[v] + g4[e];
+        if (val > best) { best = val; bi = v; }
+      }
+    }
+  }
+  block_argmax(best, bi, redv, redi);
+  if (threadIdx.x == 0) draft_tok[s * G1 + j] = bi;
+}
+
+// pre-verification head on the un-normalised residual rows: z = (x*g*rs) . cls
+__global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
+                                   float inv_dim, float eps, const float* __restrict__ cls, int d, int b, HaltArgs ha,
+                                   float* __restrict__ alpha, int* __restrict__ stop) {
+  __shared__ float al[32];
+  const int si = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (int jj = wv; jj < b; jj += nw) {
+    const int r = si * b + jj;
+    const float* xr = x + (size_t)r * ldx;
+    float z0 = 0.f, z1 = 0.f;
+    for (int k = lane; k < d; k += 64) {
+      const float v = xr[k] * g[k];
+      z0 += v * cls[k];
+      z1 += v * cls[d + k];
+    }
+    const float rs = row_scale(ssq, r, inv_dim, eps);
+    z0 = wave_sum(z0) * rs;
+    z1 = wave_sum(z1) * rs;
+    if (lane == 0) al[jj] = 1.0f / (1.0f + expf(z0 - z1));
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.f;
+    for (int jj = 0; jj < b; ++jj) { s += al[jj]; alpha[si * b + jj] = al[jj]; }
+    stop[si] = (s / (float)b <= ha.t[si]) ? 1 : 0;
+  }
+}

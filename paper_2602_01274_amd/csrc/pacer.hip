@@ -3,6 +3,7 @@
 // here; everything lives in buffers the caller binds.
 #include "../../include/pacer.h"
 #include "kernels.h"
+#include "kernels_w16.h"
 
 #include <algorithm>
 #include <cstdarg>
@@ -55,7 +56,9 @@ struct pacer_ctx {
   int *tokens = nullptr, *draft_tok = nullptr, *cand = nullptr, *rej = nullptr;
   float *ring = nullptr, *hidden = nullptr, *x = nullptr, *xn = nullptr, *qkv = nullptr, *ao = nullptr, *gu = nullptr,
         *rope = nullptr, *part = nullptr;
-  _Float16* xp = nullptr;
+  _Float16 *xpA = nullptr, *xpB = nullptr, *qp = nullptr;   // bf16 path: ping-pong f16 operands, attention Q operand
+  u64* ssq = nullptr;                                         // bf16 path: row sums of squares, [2*Lmax+1][rcap]
+  int lmax = 0;
   int* host_res = nullptr;      // pinned host memory [max_batch][2]
   int* host_res_dev = nullptr;  // its device alias
   // profiling of the GEMM kernel
@@ -90,7 +93,7 @@ bool cfg_ok(const pacer_model_cfg& m) {
   if (m.head_dim != 64 && m.head_dim != 128) return false;
   if (m.n_heads * m.head_dim != m.d_model) return false;
   if (m.dtype != PACER_F32 && m.dtype != PACER_BF16) return false;
-  if (m.dtype == PACER_BF16 && (m.d_model % 32 || m.d_ffn % 32 || m.vocab % 16)) return false;
+  if (m.dtype == PACER_BF16 && (m.d_model % 32 || m.d_ffn % 32 || m.vocab % 16 || m.max_seq % 32)) return false;
   if (m.d_model % 8 || m.d_ffn % 8) return false;
   if (!(m.rms_eps > 0.f) || !(m.rope_theta > 0.f)) return false;
   if (m.dtype == PACER_F32 && m.head_dim != 64) return false;  // f32 KV tiles are staged for head_dim 64 only
@@ -127,7 +130,10 @@ size_t carve(pacer_ctx* c, void* base) {
   c->gu = k.take<float>((size_t)c->rcap * 2 * c->fmax);
   c->rope = k.take<float>((size_t)c->rcap * c->hdmax);
   c->part = k.take<float>((size_t)c->rcap * c->hmax * kMaxChunks * (c->hdmax + 2));
-  c->xp = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
+  c->xpA = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
+  c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
+  c->qp = k.take<_Float16>((size_t)c->max_batch * (c->dmax / 32) * 2 * 512);
+  c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * c->rcap);
   return k.off;
 }
 
@@ -172,120 +178,226 @@ void prof_end(pacer_ctx* c, double bytes) {
   }
 }
 
-template <int MT, int NT>
-void launch_w16(pacer_ctx* c, const void* W, float* out, int ldo, int R, int N, int K, int mt0, int mt_total, int acc,
-                const SeqRows& sr, int rowmap) {
-  constexpr int WAVES = 8;
-  hipLaunchKernelGGL((gemm_w16_kernel<MT, NT, WAVES>), dim3(N / 16 / NT), dim3(WAVES * 64), 0, c->stream,
-                     static_cast<const u32x4*>(W), reinterpret_cast<const u32x4*>(c->xp), out, ldo, R, K / 32, mt0, mt_total, acc,
-                     sr, rowmap, c->G1);
+bool is_w16(const Model& m) { return m.cfg.dtype == PACER_BF16; }
+u64* slot(pacer_ctx* c, int s) { return c->ssq + (size_t)s * c->rcap; }
+
+// ===== bf16-weight path: fused GEMM epilogues, MFMA attention ================================
+
+template <int EPI, int TAG, int MT, int NT>
+void launch_w16(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
+  constexpr int WAVES = 8, U = 4;
+  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG>), dim3(n_tiles / NT), dim3(WAVES * 64), 0, c->stream, ga);
 }
 
-// out[r][n] (+)= sum_k act[r][k] W[n][k].  bf16 models read the packed operand in c->xp (which the
-// producer of `act` has filled); f32 models read actf (f32 rows).
-void gemm(pacer_ctx* c, const Model& m, const void* W, const float* actf, int lda, float* out, int ldo, int R, int N, int K,
-          int acc, const SeqRows& sr, int rowmap) {
-  if (m.cfg.dtype == PACER_BF16) {
-    const int mt_total = (R + 15) / 16;
-    const int tiles = N / 16;
-    const bool nt2 = (tiles % 2 == 0) && (tiles / 2 >= 512);
-    for (int mt0 = 0; mt0 < mt_total; mt0 += 2) {
-      const int mt = std::min(2, mt_total - mt0);
-      prof_begin(c);
-      if (mt == 1) {
-        if (nt2) launch_w16<1, 2>(c, W, out, ldo, R, N, K, mt0, mt_total, acc, sr, rowmap);
-        else launch_w16<1, 1>(c, W, out, ldo, R, N, K, mt0, mt_total, acc, sr, rowmap);
-      } else {
-        if (nt2) launch_w16<2, 2>(c, W, out, ldo, R, N, K, mt0, mt_total, acc, sr, rowmap);
-        else launch_w16<2, 1>(c, W, out, ldo, R, N, K, mt0, mt_total, acc, sr, rowmap);
-      }
-      prof_end(c, (double)N * K * 2.0);
+// Launches the GEMM over `n_tiles` output tiles starting at ga.nt_begin, in chunks of <= 32 rows.
+// TAG only gives the target model's launches their own kernel symbol (profiling); only the target
+// model's launches are counted by the GEMM profile.
+template <int EPI>
+void gemm_w16(pacer_ctx* c, int tag, GemmArgs ga, int n_tiles, int K) {
+  const int mt_total = (ga.R + 15) / 16;
+  ga.mt_total = mt_total;
+  ga.KT = K / 32;
+  const bool nt2 = (n_tiles % 2 == 0) && (n_tiles / 2 >= 512);
+  for (int mt0 = 0; mt0 < mt_total; mt0 += 2) {
+    const int mt = std::min(2, mt_total - mt0);
+    ga.mt0 = mt0;
+    if (tag == 0) prof_begin(c);
+#define PACER_GO(TAG_, MT_, NT_) launch_w16<EPI, TAG_, MT_, NT_>(c, ga, n_tiles)
+    if (tag == 0) {
+      if (mt == 1) { if (nt2) PACER_GO(0, 1, 2); else PACER_GO(0, 1, 1); }
+      else         { if (nt2) PACER_GO(0, 2, 2); else PACER_GO(0, 2, 1); }
+    } else {
+      if (mt == 1) { if (nt2) PACER_GO(1, 1, 2); else PACER_GO(1, 1, 1); }
+      else         { if (nt2) PACER_GO(1, 2, 2); else PACER_GO(1, 2, 1); }
     }
-  } else {
-    hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, static_cast<const float*>(W), actf, lda, out,
-                       ldo, R, N, K, acc, sr, rowmap, c->G1);
+#undef PACER_GO
+    if (tag == 0) prof_end(c, (double)n_tiles * 16.0 * K * 2.0);
   }
 }
 
-void rmsnorm(pacer_ctx* c, const Model& m, const float* g, int R, float* hid_out, const SeqRows& sr) {
-  const bool pk = m.cfg.dtype == PACER_BF16;
+void rope_table(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
+  hipLaunchKernelGGL(rope_table_kernel, dim3(R), dim3(m.cfg.head_dim / 2), 0, c->stream, sr, m.cfg.head_dim, m.cfg.rope_theta, c->rope);
+}
+
+// Decoder stack of a bf16 model on R rows.  On entry x holds the rows, xpA their f16 operand x*g of
+// the first norm and slot 0 their sums of squares.  On exit (not kv_only) x holds the final residual
+// rows, xpA = f16(x * g_final) and slot 2L their sums of squares.
+void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows& sr, bool kv_only) {
+  const pacer_model_cfg& g = m.cfg;
+  const int d = g.d_model, F = g.d_ffn, L = g.n_layers, H = g.n_heads, hd = g.head_dim;
   const int mt_total = (R + 15) / 16;
-  hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(pk ? mt_total * 16 : R), dim3(256), 0, c->stream, c->x, c->dmax, g, m.cfg.rms_eps, R,
-                     m.cfg.d_model, c->xn, c->kmax, pk ? c->xp : nullptr, mt_total, hid_out, c->G1, sr);
-}
-
-template <typename KVT>
-void attention_t(pacer_ctx* c, const Model& m, int layer, int R, const SeqRows& sr, int kv_only) {
-  const pacer_model_cfg& g = m.cfg;
-  const int d = g.d_model, hd = g.head_dim, H = g.n_heads;
-  hipLaunchKernelGGL((rope_append_kernel<KVT>), dim3(R, H), dim3(hd / 2), 0, c->stream, c->qkv, 3 * c->dmax, c->rope, sr, d, hd,
-                     static_cast<KVT*>(m.kv), layer, g.n_layers, g.max_seq, kv_only);
-  if (kv_only) return;
-  int max_keys = 0;
-  for (int i = 0; i < sr.n_seqs; ++i) max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
-  const int n_tiles = (max_keys + ATT_TILE - 1) / ATT_TILE;
-  int chunks = std::min(std::min(n_tiles, kMaxChunks), std::max(1, 1024 / (H * sr.n_seqs)));
-  const int tpc = (n_tiles + chunks - 1) / chunks;
-  chunks = (n_tiles + tpc - 1) / tpc;
-  if (hd == 128)
-    hipLaunchKernelGGL((attn_partial_kernel<KVT, 128>), dim3(chunks, H, sr.n_seqs), dim3(256), 0, c->stream, c->qkv, 3 * c->dmax,
-                       static_cast<const KVT*>(m.kv), layer, g.n_layers, g.max_seq, d, sr, tpc, chunks, H, c->part);
-  else
-    hipLaunchKernelGGL((attn_partial_kernel<KVT, 64>), dim3(chunks, H, sr.n_seqs), dim3(256), 0, c->stream, c->qkv, 3 * c->dmax,
-                       static_cast<const KVT*>(m.kv), layer, g.n_layers, g.max_seq, d, sr, tpc, chunks, H, c->part);
-  hipLaunchKernelGGL(attn_combine_kernel, dim3(R, H), dim3(hd), 0, c->stream, c->part, chunks, H, hd, c->ao, c->dmax);
-  if (g.dtype == PACER_BF16) {
-    const int mt_total = (R + 15) / 16;
-    hipLaunchKernelGGL(pack_act_kernel, dim3(mt_total * 16), dim3(256), 0, c->stream, c->ao, c->dmax, R, d, c->xp, mt_total);
+  rope_table(c, m, R, sr);
+  int max_keys = 0, max_rows = 0;
+  for (int i = 0; i < sr.n_seqs; ++i) {
+    max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
+    max_rows = std::max(max_rows, sr.row_off[i + 1] - sr.row_off[i]);
   }
-}
-
-// The decoder stack on the R rows already present in c->x (f32 [R][dmax]); rows of one sequence
-// occupy consecutive positions.  kv_only: stop each layer after writing K/V (prefix rows of M_B).
-// Leaves the final-norm output in c->xn (and, for bf16, the packed operand in c->xp).
-void run_layers(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool kv_only, float* hid_out) {
-  const pacer_model_cfg& g = m.cfg;
-  const int d = g.d_model, F = g.d_ffn;
-  const SeqRows none{};
-  hipLaunchKernelGGL(rope_table_kernel, dim3(R), dim3(g.head_dim / 2), 0, c->stream, sr, g.head_dim, g.rope_theta, c->rope);
-  for (int l = 0; l < g.n_layers; ++l) {
-    rmsnorm(c, m, m.attn_norm[l], R, nullptr, sr);
-    gemm(c, m, m.wqkv[l], c->xn, c->kmax, c->qkv, 3 * c->dmax, R, 3 * d, d, 0, none, ROWMAP_ID);
-    if (g.dtype == PACER_BF16) attention_t<_Float16>(c, m, l, R, sr, kv_only);
-    else attention_t<float>(c, m, l, R, sr, kv_only);
-    if (kv_only) continue;
-    gemm(c, m, m.wo[l], c->ao, c->dmax, c->x, c->dmax, R, d, d, 1, none, ROWMAP_ID);
-    rmsnorm(c, m, m.ffn_norm[l], R, nullptr, sr);
-    gemm(c, m, m.wgu[l], c->xn, c->kmax, c->gu, 2 * c->fmax, R, 2 * F, d, 0, none, ROWMAP_ID);
+  int kpw = std::max(128, ((max_keys + kMaxChunks - 1) / kMaxChunks + 31) / 32 * 32);
+  const int n_part = (max_keys + kpw - 1) / kpw;
+  GemmArgs base{};
+  base.R = R;
+  base.sr = sr;
+  base.G1 = c->G1;
+  base.rowmap = ROWMAP_ID;
+  base.eps = g.rms_eps;
+  base.d = d; base.hd = hd; base.n_layers = L; base.max_seq = g.max_seq; base.H = H;
+  base.mt_total_out = mt_total;
+  for (int l = 0; l < L; ++l) {
     {
-      const bool pk = g.dtype == PACER_BF16;
-      const int mt_total = (R + 15) / 16;
-      hipLaunchKernelGGL(swiglu_pack_kernel, dim3((F / 8 + 255) / 256, pk ? mt_total * 16 : R), dim3(256), 0, c->stream, c->gu,
-                         2 * c->fmax, R, F, c->xn, c->kmax, pk ? c->xp : nullptr, mt_total);
+      GemmArgs ga = base;
+      ga.W = static_cast<const u32x4*>(m.wqkv[l]);
+      ga.X = reinterpret_cast<const u32x4*>(c->xpA);
+      ga.ssq_in = slot(c, 2 * l);
+      ga.inv_dim = 1.0f / d;
+      ga.qp = c->qp;
+      ga.kv = static_cast<_Float16*>(m.kv);
+      ga.rope = c->rope;
+      ga.layer = l;
+      ga.nt_begin = kv_only ? d / 16 : 0;
+      gemm_w16<EPI_QKV>(c, tag, ga, (kv_only ? 2 : 3) * d / 16, d);
     }
-    gemm(c, m, m.wd[l], c->xn, c->kmax, c->x, c->dmax, R, d, F, 1, none, ROWMAP_ID);
+    if (kv_only) continue;
+    {
+      const dim3 grid((n_part + 3) / 4, H, sr.n_seqs);
+      const _Float16* kv = static_cast<const _Float16*>(m.kv);
+#define PACER_ATT(HD_, MT_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_>), grid, dim3(256), 0, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kpw, n_part, H, c->part)
+      if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2); else PACER_ATT(128, 1); }
+      else           { if (max_rows > 16) PACER_ATT(64, 2); else PACER_ATT(64, 1); }
+#undef PACER_ATT
+      hipLaunchKernelGGL(attn_combine_w16_kernel, dim3(R, H), dim3(hd), 0, c->stream, c->part, sr, kpw, n_part, H, hd, c->xpB, mt_total);
+    }
+    {
+      GemmArgs ga = base;
+      ga.W = static_cast<const u32x4*>(m.wo[l]);
+      ga.X = reinterpret_cast<const u32x4*>(c->xpB);
+      ga.out = c->x; ga.ldo = c->dmax;
+      ga.g_next = m.ffn_norm[l];
+      ga.xp_out = c->xpA;
+      ga.ssq_out = slot(c, 2 * l + 1);
+      gemm_w16<EPI_RESID>(c, tag, ga, d / 16, d);
+    }
+    {
+      GemmArgs ga = base;
+      ga.W = static_cast<const u32x4*>(m.wgu[l]);
+      ga.X = reinterpret_cast<const u32x4*>(c->xpA);
+      ga.ssq_in = slot(c, 2 * l + 1);
+      ga.inv_dim = 1.0f / d;
+      ga.xp_out = c->xpB;
+      gemm_w16<EPI_SWIGLU>(c, tag, ga, 2 * F / 16, d);
+    }
+    {
+      GemmArgs ga = base;
+      ga.W = static_cast<const u32x4*>(m.wd[l]);
+      ga.X = reinterpret_cast<const u32x4*>(c->xpB);
+      ga.out = c->x; ga.ldo = c->dmax;
+      ga.g_next = (l + 1 < L) ? m.attn_norm[l + 1] : m.final_norm;
+      ga.xp_out = c->xpA;
+      ga.ssq_out = slot(c, 2 * l + 2);
+      gemm_w16<EPI_RESID>(c, tag, ga, d / 16, F);
+    }
   }
-  if (!kv_only) rmsnorm(c, m, m.final_norm, R, hid_out, sr);
 }
 
-void embed(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
-  if (m.cfg.dtype == PACER_BF16)
-    hipLaunchKernelGGL((embed_rows_kernel<uint16_t>), dim3(R), dim3(256), 0, c->stream, static_cast<const uint16_t*>(m.embed),
-                       c->tokens, c->draft_tok, sr, c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax);
-  else
+void embed_w16(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
+  hipLaunchKernelGGL(embed_w16_kernel, dim3(R), dim3(256), 0, c->stream, static_cast<const uint16_t*>(m.embed), c->tokens, c->draft_tok, sr,
+                     c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax, m.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq,
+                     2 * m.cfg.n_layers + 1, c->rcap);
+}
+
+void lm_head_w16(pacer_ctx* c, const Model& m, int tag, int R, float* out, const SeqRows& sr, int rowmap) {
+  GemmArgs ga{};
+  ga.R = R; ga.sr = sr; ga.G1 = c->G1; ga.rowmap = rowmap; ga.eps = m.cfg.rms_eps;
+  ga.W = static_cast<const u32x4*>(m.head);
+  ga.X = reinterpret_cast<const u32x4*>(c->xpA);
+  ga.ssq_in = slot(c, 2 * m.cfg.n_layers);
+  ga.inv_dim = 1.0f / m.cfg.d_model;
+  ga.out = out; ga.ldo = m.cfg.vocab;
+  gemm_w16<EPI_STORE>(c, tag, ga, m.cfg.vocab / 16, m.cfg.d_model);
+}
+
+// ===== f32 path (tiny pair): plain kernels, one per operation ================================
+
+void gemm_f32(pacer_ctx* c, const void* W, const float* act, int lda, float* out, int ldo, int R, int N, int K, int acc,
+              const SeqRows& sr, int rowmap) {
+  hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, static_cast<const float*>(W), act, lda, out, ldo, R, N,
+                     K, acc, sr, rowmap, c->G1);
+}
+
+void rmsnorm_f32(pacer_ctx* c, const Model& m, const float* g, int R, float* hid_out, const SeqRows& sr) {
+  hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(R), dim3(256), 0, c->stream, c->x, c->dmax, g, m.cfg.rms_eps, R, m.cfg.d_model, c->xn,
+                     c->kmax, (_Float16*)nullptr, 0, hid_out, c->G1, sr);
+}
+
+void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool kv_only, float* hid_out) {
+  const pacer_model_cfg& g = m.cfg;
+  const int d = g.d_model, F = g.d_ffn, H = g.n_heads, hd = g.head_dim;
+  const SeqRows none{};
+  rope_table(c, m, R, sr);
+  for (int l = 0; l < g.n_layers; ++l) {
+    rmsnorm_f32(c, m, m.attn_norm[l], R, nullptr, sr);
+    gemm_f32(c, m.wqkv[l], c->xn, c->kmax, c->qkv, 3 * c->dmax, R, 3 * d, d, 0, none, ROWMAP_ID);
+    hipLaunchKernelGGL((rope_append_kernel<float>), dim3(R, H), dim3(hd / 2), 0, c->stream, c->qkv, 3 * c->dmax, c->rope, sr, d, hd,
+                       static_cast<float*>(m.kv), l, g.n_layers, g.max_seq, kv_only ? 1 : 0);
+    if (kv_only) continue;
+    int max_keys = 0;
+    for (int i = 0; i < sr.n_seqs; ++i) max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
+    const int n_tiles = (max_keys + ATT_TILE - 1) / ATT_TILE;
+    int chunks = std::min(std::min(n_tiles, kMaxChunks), std::max(1, 1024 / (H * sr.n_seqs)));
+    const int tpc = (n_tiles + chunks - 1) / chunks;
+    chunks = (n_tiles + tpc - 1) / tpc;
+    hipLaunchKernelGGL((attn_partial_kernel<float, 64>), dim3(chunks, H, sr.n_seqs), dim3(256), 0, c->stream, c->qkv, 3 * c->dmax,
+                       static_cast<const float*>(m.kv), l, g.n_layers, g.max_seq, d, sr, tpc, chunks, H, c->part);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(R, H), dim3(hd), 0, c->stream, c->part, chunks, H, hd, c->ao, c->dmax);
+    gemm_f32(c, m.wo[l], c->ao, c->dmax, c->x, c->dmax, R, d, d, 1, none, ROWMAP_ID);
+    rmsnorm_f32(c, m, m.ffn_norm[l], R, nullptr, sr);
+    gemm_f32(c, m.wgu[l], c->xn, c->kmax, c->gu, 2 * c->fmax, R, 2 * F, d, 0, none, ROWMAP_ID);
+    hipLaunchKernelGGL(swiglu_pack_kernel, dim3((F / 8 + 255) / 256, R), dim3(256), 0, c->stream, c->gu, 2 * c->fmax, R, F, c->xn, c->kmax,
+                       (_Float16*)nullptr, 0);
+    gemm_f32(c, m.wd[l], c->xn, c->kmax, c->x, c->dmax, R, d, F, 1, none, ROWMAP_ID);
+  }
+  if (!kv_only) rmsnorm_f32(c, m, m.final_norm, R, hid_out, sr);
+}
+
+// ===== model-level steps, both paths ==========================================================
+
+// rows -> x (embedding gather) and the decoder stack; `tag` 0 = target model
+void forward_lm(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows& sr) {
+  if (is_w16(m)) {
+    embed_w16(c, m, R, sr);
+    run_layers_w16(c, m, tag, R, sr, false);
+  } else {
     hipLaunchKernelGGL((embed_rows_kernel<float>), dim3(R), dim3(256), 0, c->stream, static_cast<const float*>(m.embed), c->tokens,
                        c->draft_tok, sr, c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax);
+    run_layers_f32(c, m, R, sr, false, nullptr);
+  }
 }
 
-void lm_head(pacer_ctx* c, const Model& m, int R, float* out, const SeqRows& sr, int rowmap) {
-  gemm(c, m, m.head, c->xn, c->kmax, out, m.cfg.vocab, R, m.cfg.vocab, m.cfg.d_model, 0, sr, rowmap);
+void lm_head(pacer_ctx* c, const Model& m, int tag, int R, float* out, const SeqRows& sr, int rowmap) {
+  if (is_w16(m)) lm_head_w16(c, m, tag, R, out, sr, rowmap);
+  else gemm_f32(c, m.head, c->xn, c->kmax, out, m.cfg.vocab, R, m.cfg.vocab, m.cfg.d_model, 0, sr, rowmap);
 }
 
 // M_B over rows whose inputs are src rows + PosEmb; kv_only for prefix rows.
 void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr, const float* src, int lds, bool kv_only) {
   const Model& mb = c->m[PACER_PREVERIFY];
-  hipLaunchKernelGGL(mb_input_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax);
-  run_layers(c, mb, R, sr, kv_only, nullptr);
+  if (is_w16(mb)) {
+    hipLaunchKernelGGL(mb_input_w16_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax,
+                       mb.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq, 3, c->rcap);
+    run_layers_w16(c, mb, 1, R, sr, kv_only);
+  } else {
+    hipLaunchKernelGGL(mb_input_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax);
+    run_layers_f32(c, mb, R, sr, kv_only, nullptr);
+  }
+}
+
+// the 2-class head, block mean and stop flag for n sequences of b rows each (after run_preverify_rows)
+void preverify_head(pacer_ctx* c, int n, int b, const HaltArgs& ha, float* dev_alpha, int* dev_stop) {
+  const Model& mb = c->m[PACER_PREVERIFY];
+  if (is_w16(mb))
+    hipLaunchKernelGGL(mb_head_w16_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, mb.final_norm, slot(c, 2), 1.0f / mb.cfg.d_model,
+                       mb.cfg.rms_eps, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop);
+  else
+    hipLaunchKernelGGL(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop);
 }
 
 // one draft forward at draft index j[s] (0-based) for each listed sequence; logits and hidden
@@ -304,11 +416,20 @@ void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int m
     pa.j[i] = j[i];
   }
   sr.row_off[n] = n;
-  embed(c, md, n, sr);
-  run_layers(c, md, n, sr, false, c->hidden);
-  lm_head(c, md, n, c->ring, sr, ROWMAP_RING);
-  hipLaunchKernelGGL(pick_token_kernel, dim3(n), dim3(1024), 0, c->stream, c->ring, c->draft_tok, pa, c->G1, md.cfg.vocab, mode, seed,
-                     (uint32_t)ctr);
+  if (is_w16(md)) {
+    forward_lm(c, md, 1, n, sr);
+    lm_head(c, md, 1, n, c->ring, sr, ROWMAP_RING);
+    hipLaunchKernelGGL(draft_tail_kernel, dim3(n), dim3(1024), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
+                       1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->ring, c->draft_tok, pa, c->G1, md.cfg.vocab,
+                       mode, seed, (uint32_t)ctr);
+  } else {
+    hipLaunchKernelGGL((embed_rows_kernel<float>), dim3(n), dim3(256), 0, c->stream, static_cast<const float*>(md.embed), c->tokens,
+                       c->draft_tok, sr, c->max_seq, c->G1, md.cfg.d_model, c->x, c->dmax);
+    run_layers_f32(c, md, n, sr, false, c->hidden);
+    lm_head(c, md, 1, n, c->ring, sr, ROWMAP_RING);
+    hipLaunchKernelGGL(pick_token_kernel, dim3(n), dim3(1024), 0, c->stream, c->ring, c->draft_tok, pa, c->G1, md.cfg.vocab, mode, seed,
+                       (uint32_t)ctr);
+  }
 }
 
 int fold(pacer_ctx* c, int s) {
@@ -367,6 +488,7 @@ int32_t pacer_create(pacer_ctx** out, const pacer_model_cfg* target, const pacer
   c->hmax = std::max(target->n_heads, draft->n_heads);
   c->hdmax = std::max(target->head_dim, draft->head_dim);
   c->max_seq = target->max_seq;
+  c->lmax = std::max(target->n_layers, draft->n_layers);
   *out = c;
   return PACER_OK;
 }
@@ -383,10 +505,21 @@ void pacer_destroy(pacer_ctx* c) {
 
 const char* pacer_last_error(const pacer_ctx* c) { return c ? c->err : "null context"; }
 
-int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int32_t n_in, void* hip_stream) {
+int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int32_t n_in, int32_t tensor_id, int32_t head_dim,
+                          void* hip_stream) {
   if (!dev_dst || !dev_src || dev_dst == dev_src || n_out < 16 || n_in < 32 || n_out % 16 || n_in % 32) return PACER_EINVAL;
-  hipLaunchKernelGGL(pack_weight_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(hip_stream), static_cast<uint4*>(dev_dst),
-                     static_cast<const uint16_t*>(dev_src), n_out, n_in);
+  int kind = PACK_PLAIN;
+  if (tensor_id == PACER_T_WQKV) {
+    if ((head_dim != 64 && head_dim != 128) || n_out % 3 || (n_out / 3) % head_dim) return PACER_EINVAL;
+    kind = PACK_QKV;
+  } else if (tensor_id == PACER_T_WGU) {
+    if (n_out % 32) return PACER_EINVAL;
+    kind = PACK_GATEUP;
+  } else if (tensor_id != PACER_T_WO && tensor_id != PACER_T_WD && tensor_id != PACER_T_HEAD) {
+    return PACER_EINVAL;
+  }
+  hipLaunchKernelGGL(pack_weight_kind_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(hip_stream), static_cast<uint4*>(dev_dst),
+                     static_cast<const uint16_t*>(dev_src), n_out, n_in, kind, head_dim);
   return hipGetLastError() == hipSuccess ? PACER_OK : PACER_EHIP;
 }
 
@@ -491,13 +624,16 @@ int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_
     sr.row_off[1] = R;
     sr.pos0[0] = p0;
     sr.len[0] = n;
-    embed(c, c->m[PACER_TARGET], R, sr);
-    run_layers(c, c->m[PACER_TARGET], R, sr, false, nullptr);
-    embed(c, c->m[PACER_DRAFT], R, sr);
-    run_layers(c, c->m[PACER_DRAFT], R, sr, false, nullptr);
-    // the draft's hidden states (final-norm output, now in xn) feed M_B's prefix rows
-    (void)hipMemcpy2DAsync(c->ao, (size_t)c->dmax * 4, c->xn, (size_t)c->kmax * 4, (size_t)c->m[PACER_DRAFT].cfg.d_model * 4, R,
-                     hipMemcpyDeviceToDevice, c->stream);
+    forward_lm(c, c->m[PACER_TARGET], 0, R, sr);
+    const Model& md = c->m[PACER_DRAFT];
+    forward_lm(c, md, 1, R, sr);
+    // the draft's hidden states (final-norm output) feed M_B's prefix rows; staged in ao
+    if (is_w16(md))
+      hipLaunchKernelGGL(hidden_rows_kernel, dim3(R), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
+                         1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->ao, c->dmax);
+    else
+      (void)hipMemcpy2DAsync(c->ao, (size_t)c->dmax * 4, c->xn, (size_t)c->kmax * 4, (size_t)md.cfg.d_model * 4, R, hipMemcpyDeviceToDevice,
+                             c->stream);
     MbRows mr{};
     mr.src_row0[0] = 0;
     mr.e0[0] = -1;
@@ -584,8 +720,7 @@ int32_t pacer_preverify_block(pacer_ctx* c, const int32_t* seqs, int32_t n, floa
   sr.row_off[n] = n * b;
   const Model& mb = c->m[PACER_PREVERIFY];
   run_preverify_rows(c, n * b, sr, mr, c->hidden, mb.cfg.d_model, false);
-  hipLaunchKernelGGL(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha,
-                     dev_stop);
+  preverify_head(c, n, b, ha, dev_alpha, dev_stop);
   for (int i = 0; i < n; ++i) {
     Seq& q = c->seq[seqs[i]];
     q.mb_done += b;
@@ -620,9 +755,8 @@ int32_t pacer_verify(pacer_ctx* c, const int32_t* seqs, int32_t n, const int32_t
   }
   sr.row_off[n] = R;
   const Model& mt = c->m[PACER_TARGET];
-  embed(c, mt, R, sr);
-  run_layers(c, mt, R, sr, false, nullptr);
-  lm_head(c, mt, R, dev_logits, sr, ROWMAP_LIST);
+  forward_lm(c, mt, 0, R, sr);
+  lm_head(c, mt, 0, R, dev_logits, sr, ROWMAP_LIST);
   for (int i = 0; i < n; ++i) c->seq[seqs[i]].verified = g[i];
   HIPCHK(c, hipGetLastError());
   return PACER_OK;

@@ -24,6 +24,7 @@ class Session:
         self.block = block or w["block"]
         self.gamma_max = gamma_max or w["gamma_max"]
         self.G1 = self.gamma_max + 1
+        max_seq = (max_seq + 31) // 32 * 32          # the f16 KV layout wants whole 32-key groups
         self.max_seq, self.max_batch = max_seq, max_batch
         self.stream = torch.cuda.current_stream().cuda_stream
         self.keep = []                      # tensors the library borrows
@@ -59,12 +60,12 @@ class Session:
         torch.cuda.synchronize()
 
     # ---- weight upload -------------------------------------------------------------------
-    def _matrix(self, parts):
+    def _matrix(self, parts, tid, head_dim=0):
         """row-major [out, in] pieces -> the library's format for this dtype (device tensor)."""
         if self.dtype == "bf16":
             src = torch.cat([_dev(p, torch.bfloat16) for p in parts], dim=0).contiguous()
             dst = torch.empty_like(src)
-            B.pacer_pack_weight(dst, src, self.stream)
+            B.pacer_pack_weight(dst, src, tid, head_dim, self.stream)
             torch.cuda.synchronize()
             del src
             return dst
@@ -76,7 +77,8 @@ class Session:
         B.pacer_bind(self.ctx, which, tid, layer, t)
 
     def _bind_mat(self, which, tid, layer, parts):
-        t = self._matrix(parts)
+        hd = (self.w["target"] if which == B.TARGET else self.w["draft"])["head_dim"]
+        t = self._matrix(parts, tid, hd)
         self.keep.append(t)
         B.pacer_bind(self.ctx, which, tid, layer, t)
         return t
@@ -98,7 +100,7 @@ class Session:
         else:
             edt = torch.bfloat16 if self.dtype == "bf16" else torch.float32
             emb = _dev(m["embed"], edt).contiguous()
-            head = self._matrix([m["head"]])
+            head = self._matrix([m["head"]], B.T_HEAD)
             self._shared = (emb, head)
         self.keep += [emb, head]
         B.pacer_bind(self.ctx, which, B.T_EMBED, 0, emb)
