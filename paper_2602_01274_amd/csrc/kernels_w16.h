@@ -1,9 +1,9 @@
 // Fused kernels of the bf16-weight path (gfx950, wave64, v_mfma_f32_16x16x32_f16).
 //
-// One decoder layer is six launches:
+// One decoder layer is five launches:
 //   QKV GEMM   (epilogue: row scale of the RMSNorm, RoPE, Q -> f16 attention operand, K/V -> cache)
-//   attention  (MFMA scores and weighted values, one wave per 128..-key range, no LDS)
-//   combine    (merge the ranges, write the f16 operand of the O projection)
+//   attention  (MFMA scores and weighted values, one wave per key range, no LDS; the wave that
+//               finishes last for a head merges the ranges into the f16 operand of the O projection)
 //   O GEMM     (epilogue: residual add, next norm's operand x*g as f16, row sum of squares)
 //   gate/up GEMM (epilogue: row scale, SwiGLU, f16 operand of the down projection)
 //   down GEMM  (epilogue: residual add, next norm's operand, row sum of squares)
@@ -156,8 +156,14 @@ struct GemmArgs {
   SeqRows sr;
 };
 
-template <int EPI, int MT, int NT, int WAVES, int U, int TAG>
+// X17 = 1 (with MT = 2): the launch covers exactly 17 rows (a full draft window plus the committed
+// token).  Only column 0 of the second row tile exists, so instead of fetching that whole 1 KiB operand
+// tile each lane reads the 16 bytes of column 0 (a 64-byte broadcast per K step) and the other columns
+// are zeroed in registers.  The second MFMA per step is idle work on an idle unit; the operand traffic
+// is what mattered.
+template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const GemmArgs ga) {
+  static_assert(!X17 || MT == 2, "the 17-row form uses two row tiles");
   __shared__ f32x4 red[WAVES][NT * MT][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nt0 = ga.nt_begin + blockIdx.x * NT;
@@ -174,6 +180,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const GemmArgs ga)
 #pragma unroll
   for (int a = 0; a < NT; ++a) wp[a] = ga.W + (size_t)(nt0 + a) * KT * 64 + lane;
   const u32x4* xp = ga.X + (size_t)ga.mt0 * 64 + lane;
+  const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 64 + (lane & 48);   // column 0 of row tile mt0+1
+  const bool col0 = (lane & 15) == 0;
   const int mtt = ga.mt_total;
 
   u32x4 A0[U][NT], A1[U][NT], B0[U][MT], B1[U][MT];
@@ -185,8 +193,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const GemmArgs ga)
       if (kt < ke) {
 #pragma unroll
         for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + (size_t)kt * 64);
+        if (X17) {
+          B[u][0] = xp[(size_t)kt * mtt * 64];
+          B[u][1] = xp17[(size_t)kt * mtt * 64];
+        } else {
 #pragma unroll
-        for (int b = 0; b < MT; ++b) B[u][b] = xp[((size_t)kt * mtt + b) * 64];
+          for (int b = 0; b < MT; ++b) B[u][b] = xp[((size_t)kt * mtt + b) * 64];
+        }
       } else {
 #pragma unroll
         for (int a = 0; a < NT; ++a) A[u][a] = zero;
@@ -200,7 +213,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const GemmArgs ga)
     for (int u = 0; u < U; ++u) {
       half8 bh[MT];
 #pragma unroll
-      for (int b = 0; b < MT; ++b) bh[b] = __builtin_bit_cast(half8, B[u][b]);
+      for (int b = 0; b < MT; ++b) bh[b] = __builtin_bit_cast(half8, (X17 && b == 1 && !col0) ? zero : B[u][b]);
 #pragma unroll
       for (int a = 0; a < NT; ++a) {
         const half8 ah = bf16x8_to_f16x8(A[u][a]);
@@ -328,27 +341,42 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const GemmArgs ga)
 }
 
 // ------------------------------------------------------------------ MFMA attention over the f16 KV cache
-// grid (key ranges / 4, heads, sequences), 4 independent waves per block, one key range per wave.
-// Scores: S^T[key][row] = K[key][:] . Q[row][:]  (A = K tile straight from the cache, B = Q operand).
-// Values: O^T[dim][row] += V^T[dim][keys] P^T[keys][row]; the probabilities leave the first MFMA in
-// exactly the lane layout the second one wants for B (contraction index = the 8 keys a lane holds),
-// and V^T rows are contiguous along keys.  Online softmax per query row (= per lane column).
+// grid (key splits, heads, sequences), 8 waves per block.  A block owns `kps` keys of one head; its
+// waves take the 32-key groups of that range round-robin, each running an online softmax in registers:
+//   scores  S^T[key][row] = K[key][:] . Q[row][:]   (A = K tile straight from the cache, B = Q operand)
+//   values  O^T[dim][row] += V^T[dim][keys] P^T[keys][row]; the probabilities leave the first MFMA in
+//           exactly the lane layout the second one wants for B (contraction index = the 8 keys a lane
+//           holds), and V^T rows are contiguous along keys.
+// The 8 wave states are merged pairwise through LDS (same lane layout on both sides, so no transposition).
+// With one split the block writes the f16 operand of the O projection directly; with several, each block
+// writes a partial and the block that arrives last (device-scope ticket) merges them.
+struct AttnState { float m, l; };
+__device__ __forceinline__ void merge_w(float m1, float m2, float& M, float& w1, float& w2) {
+  M = fmaxf(m1, m2);
+  w1 = (m1 == -INFINITY) ? 0.f : expf(m1 - M);
+  w2 = (m2 == -INFINITY) ? 0.f : expf(m2 - M);
+}
+
 template <int HD, int MT>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const _Float16* __restrict__ qp, const _Float16* __restrict__ kv, int layer,
-                                                        int n_layers, int max_seq, int d, SeqRows sr, int kpw, int n_part_max, int H,
-                                                        float* __restrict__ part) {
-  constexpr int KTS = HD / 32, DTS = HD / 16;
+__global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restrict__ qp, const _Float16* __restrict__ kv, int layer,
+                                                        int n_layers, int max_seq, int d, SeqRows sr, int kps, int S, int H,
+                                                        float* __restrict__ part, int* __restrict__ counters,
+                                                        _Float16* __restrict__ xp_out, int MT_total_out) {
+  constexpr int KTS = HD / 32, DTS = HD / 16, NW = 8;
+  __shared__ f32x4 sacc[NW / 2][DTS][64];
+  __shared__ float sm[NW / 2][64], sl[NW / 2][64];
+  __shared__ int s_last;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
-  const int h = blockIdx.y, si = blockIdx.z;
+  const int split = blockIdx.x, h = blockIdx.y, si = blockIdx.z;
   const int r0 = sr.row_off[si], Rs = sr.row_off[si + 1] - r0, pos0 = sr.pos0[si];
   const int n_keys = pos0 + Rs;
-  const int pidx = blockIdx.x * 4 + wave;
-  const int k_begin = pidx * kpw;
-  if (k_begin >= n_keys) return;
-  const int k_end = min(n_keys, k_begin + kpw);
+  const int n_split = (n_keys + kps - 1) / kps;
+  if (split >= n_split) return;
+  const int ks_begin = split * kps, ks_end = min(n_keys, ks_begin + kps);
   const _Float16* Kc = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2) * (size_t)max_seq * d + h * HD;
   const _Float16* Vt = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2 + 1) * (size_t)max_seq * d + (size_t)h * HD * max_seq;
   const float scale = 1.0f / sqrtf((float)HD);
+  typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
   half8 q[KTS][MT];
 #pragma unroll
@@ -366,27 +394,15 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const _Float16* __restri
     for (int dt = 0; dt < DTS; ++dt) acc[dt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  for (int kk = k_begin; kk < k_end; kk += 32) {
-    // scores of keys kk..kk+31 (two 16-key tiles)
-    f32x4 st[2][MT];
+  // K tiles (two 16-key tiles x KTS feature groups) and V^T fragments of one 32-key group
+  auto load_kv = [&](int kk, half8(&ka)[2][KTS], half8(&va)[DTS]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int key = min(kk + 16 * t + j, n_keys - 1);
       const _Float16* kr = Kc + (size_t)key * d + 8 * g;
-      half8 ka[KTS];
 #pragma unroll
-      for (int kt = 0; kt < KTS; ++kt) ka[kt] = *reinterpret_cast<const half8*>(kr + kt * 32);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kt = 0; kt < KTS; ++kt) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[kt], q[kt][mt], s, 0, 0, 0);
-        st[t][mt] = s;
-      }
+      for (int kt = 0; kt < KTS; ++kt) ka[t][kt] = *reinterpret_cast<const half8*>(kr + kt * 32);
     }
-    // values operand: V^T[dim][keys kk+4g..+3 and kk+16+4g..+3]
-    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-    half8 va[DTS];
     const bool tail = kk + 32 > n_keys;
 #pragma unroll
     for (int dt = 0; dt < DTS; ++dt) {
@@ -401,8 +417,18 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const _Float16* __restri
       }
       va[dt] = half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     }
+  };
+  auto step = [&](int kk, half8(&ka)[2][KTS], half8(&va)[DTS]) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
+      f32x4 st[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kt = 0; kt < KTS; ++kt) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][kt], q[kt][mt], s, 0, 0, 0);
+        st[t] = s;
+      }
       const int pos = pos0 + mt * 16 + j;                // this lane's query row
       float sv[8];
       float mx = -INFINITY;
@@ -411,7 +437,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const _Float16* __restri
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int key = kk + 16 * t + 4 * g + r;
-          const float v = (key <= pos && key < n_keys) ? st[t][mt][r] * scale : -INFINITY;
+          const float v = (key <= pos && key < n_keys) ? st[t][r] * scale : -INFINITY;
           sv[t * 4 + r] = v;
           mx = fmaxf(mx, v);
         }
@@ -437,39 +463,114 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const _Float16* __restri
         acc[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[dt], pb, acc[dt][mt], 0, 0, 0);
       }
     }
-  }
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int rl = mt * 16 + j;
-    if (rl < Rs) {
-      float* o = part + (((size_t)(r0 + rl) * H + h) * n_part_max + pidx) * (HD + 2);
-#pragma unroll
-      for (int dt = 0; dt < DTS; ++dt) *reinterpret_cast<f32x4*>(o + dt * 16 + 4 * g) = acc[dt][mt];
-      if (g == 0) { o[HD] = mrun[mt]; o[HD + 1] = lrun[mt]; }
+  };
+  // the wave's 32-key groups; with one row tile there are registers to keep the next group's loads in
+  // flight while the current one is used
+  if (MT == 1) {
+    half8 ka0[2][KTS], ka1[2][KTS], va0[DTS], va1[DTS];
+    int kk = ks_begin + 32 * wave;
+    if (kk < ks_end) load_kv(kk, ka0, va0);
+    while (kk < ks_end) {
+      const int k1 = kk + 32 * NW;
+      if (k1 < ks_end) load_kv(k1, ka1, va1);
+      step(kk, ka0, va0);
+      kk = k1;
+      if (kk >= ks_end) break;
+      const int k2 = kk + 32 * NW;
+      if (k2 < ks_end) load_kv(k2, ka0, va0);
+      step(kk, ka1, va1);
+      kk = k2;
+    }
+  } else {
+    half8 ka0[2][KTS], va0[DTS];
+    for (int kk = ks_begin + 32 * wave; kk < ks_end; kk += 32 * NW) {
+      load_kv(kk, ka0, va0);
+      step(kk, ka0, va0);
     }
   }
-}
 
-// merge the key ranges of one (row, head) and write the f16 operand of the O projection
-__global__ void attn_combine_w16_kernel(const float* __restrict__ part, SeqRows sr, int kpw, int n_part_max, int H, int HD,
-                                        _Float16* __restrict__ xp, int MT_total) {
-  const int r = blockIdx.x, h = blockIdx.y, dim = threadIdx.x;
-  const int si = find_seq(sr, r);
-  const int n_keys = sr.pos0[si] + (sr.row_off[si + 1] - sr.row_off[si]);
-  const int n_part = (n_keys + kpw - 1) / kpw;
-  const float* p = part + ((size_t)r * H + h) * n_part_max * (HD + 2);
-  float M = -INFINITY;
-  for (int c = 0; c < n_part; ++c) M = fmaxf(M, p[(size_t)c * (HD + 2) + HD]);
-  float L = 0.f, a = 0.f;
-  for (int c = 0; c < n_part; ++c) {
-    const float m = p[(size_t)c * (HD + 2) + HD];
-    if (m == -INFINITY) continue;
-    const float w = expf(m - M);
-    L += p[(size_t)c * (HD + 2) + HD + 1] * w;
-    a += p[(size_t)c * (HD + 2) + dim] * w;
+  // pairwise merge of the 8 wave states (waves s..2s-1 hand theirs to waves 0..s-1)
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int stride = NW / 2; stride >= 1; stride >>= 1) {
+      if (wave >= stride && wave < 2 * stride) {
+        const int w = wave - stride;
+        sm[w][lane] = mrun[mt];
+        sl[w][lane] = lrun[mt];
+#pragma unroll
+        for (int dt = 0; dt < DTS; ++dt) sacc[w][dt][lane] = acc[dt][mt];
+      }
+      __syncthreads();
+      if (wave < stride) {
+        float M, w1, w2;
+        merge_w(mrun[mt], sm[wave][lane], M, w1, w2);
+        lrun[mt] = lrun[mt] * w1 + sl[wave][lane] * w2;
+        mrun[mt] = M;
+#pragma unroll
+        for (int dt = 0; dt < DTS; ++dt) acc[dt][mt] = acc[dt][mt] * w1 + sacc[wave][dt][lane] * w2;
+      }
+      __syncthreads();
+    }
   }
-  const int k = h * HD + dim;
-  xp[((size_t)((k >> 5) * MT_total + (r >> 4)) * 64 + (((k & 31) >> 3) * 16 + (r & 15))) * 8 + (k & 7)] = (_Float16)(a / L);
+
+  if (n_split == 1) {
+    if (wave == 0) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int rl = mt * 16 + j;
+        if (rl < Rs) {
+          const float inv = 1.0f / lrun[mt];
+#pragma unroll
+          for (int dt = 0; dt < DTS; ++dt) {
+            const f32x4 o = acc[dt][mt] * inv;
+            store_packed4(xp_out, MT_total_out, r0 + rl, h * HD + dt * 16 + 4 * g, o[0], o[1], o[2], o[3]);
+          }
+        }
+      }
+    }
+    return;
+  }
+  // several splits: partial to global, last block merges
+  if (wave == 0) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int rl = mt * 16 + j;
+      if (rl < Rs) {
+        float* o = part + (((size_t)(r0 + rl) * H + h) * S + split) * (HD + 2);
+#pragma unroll
+        for (int dt = 0; dt < DTS; ++dt) *reinterpret_cast<f32x4*>(o + dt * 16 + 4 * g) = acc[dt][mt];
+        if (g == 0) { o[HD] = mrun[mt]; o[HD + 1] = lrun[mt]; }
+      }
+    }
+    __threadfence();
+    if (lane == 0) s_last = (atomicAdd(counters + si * H + h, 1) == n_split - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  // all 512 threads: outputs are (row, 4 consecutive dims)
+  for (int o4 = threadIdx.x; o4 < Rs * (HD / 4); o4 += 512) {
+    const int rl = o4 / (HD / 4), d4 = (o4 % (HD / 4)) * 4;
+    const float* p = part + ((size_t)(r0 + rl) * H + h) * S * (HD + 2);
+    float M = -INFINITY;
+    for (int c = 0; c < n_split; ++c) M = fmaxf(M, __builtin_nontemporal_load(p + (size_t)c * (HD + 2) + HD));
+    float L = 0.f;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < n_split; ++c) {
+      const float* pc = p + (size_t)c * (HD + 2);
+      const float m = __builtin_nontemporal_load(pc + HD);
+      const float w = (m == -INFINITY) ? 0.f : expf(m - M);
+      L += __builtin_nontemporal_load(pc + HD + 1) * w;
+      typedef float f32x2 __attribute__((ext_vector_type(2)));
+      const f32x2 a01 = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(pc + d4));
+      const f32x2 a23 = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(pc + d4 + 2));
+      a[0] += a01[0] * w; a[1] += a01[1] * w; a[2] += a23[0] * w; a[3] += a23[1] * w;
+    }
+    const float inv = 1.0f / L;
+    store_packed4(xp_out, MT_total_out, r0 + rl, h * HD + d4, a[0] * inv, a[1] * inv, a[2] * inv, a[3] * inv);
+  }
+  if (threadIdx.x == 0) counters[si * H + h] = 0;
 }
 
 // ------------------------------------------------------------------ tail of a draft forward

@@ -58,6 +58,7 @@ struct pacer_ctx {
         *rope = nullptr, *part = nullptr;
   _Float16 *xpA = nullptr, *xpB = nullptr, *qp = nullptr;   // bf16 path: ping-pong f16 operands, attention Q operand
   u64* ssq = nullptr;                                         // bf16 path: row sums of squares, [2*Lmax+1][rcap]
+  int* att_cnt = nullptr;                                     // bf16 path: arrival tickets per (sequence slot, head)
   int lmax = 0;
   int* host_res = nullptr;      // pinned host memory [max_batch][2]
   int* host_res_dev = nullptr;  // its device alias
@@ -134,6 +135,7 @@ size_t carve(pacer_ctx* c, void* base) {
   c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
   c->qp = k.take<_Float16>((size_t)c->max_batch * (c->dmax / 32) * 2 * 512);
   c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * c->rcap);
+  c->att_cnt = k.take<int>((size_t)c->max_batch * c->hmax);
   return k.off;
 }
 
@@ -183,36 +185,44 @@ u64* slot(pacer_ctx* c, int s) { return c->ssq + (size_t)s * c->rcap; }
 
 // ===== bf16-weight path: fused GEMM epilogues, MFMA attention ================================
 
-template <int EPI, int TAG, int MT, int NT>
+template <int EPI, int TAG, int MT, int NT, int WAVES, int U, int X17 = 0>
 void launch_w16(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
-  constexpr int WAVES = 8, U = 4;
-  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG>), dim3(n_tiles / NT), dim3(WAVES * 64), 0, c->stream, ga);
+  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17>), dim3(n_tiles / NT), dim3(WAVES * 64), 0, c->stream, ga);
 }
 
 // Launches the GEMM over `n_tiles` output tiles starting at ga.nt_begin, in chunks of <= 32 rows.
-// TAG only gives the target model's launches their own kernel symbol (profiling); only the target
-// model's launches are counted by the GEMM profile.
-template <int EPI>
-void gemm_w16(pacer_ctx* c, int tag, GemmArgs ga, int n_tiles, int K) {
+// Shape of a launch (measured on MI355X): few output tiles -> 8 waves per block split K so that the
+// chip is covered; many tiles -> 4 waves with a deeper prefetch, which keeps 4 blocks resident per CU so
+// one block's epilogue overlaps the others' streaming; rows beyond 16 -> two output tiles per wave so
+// that the activation operand is fetched once for both.
+// TAG only gives the target model's launches their own kernel symbol; the GEMM profile counts those.
+template <int EPI, int TAG>
+void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
   const int mt_total = (ga.R + 15) / 16;
   ga.mt_total = mt_total;
   ga.KT = K / 32;
-  const bool nt2 = (n_tiles % 2 == 0) && (n_tiles / 2 >= 512);
+  const bool many = n_tiles >= 512;
+  const bool even = n_tiles % 2 == 0;
   for (int mt0 = 0; mt0 < mt_total; mt0 += 2) {
     const int mt = std::min(2, mt_total - mt0);
     ga.mt0 = mt0;
-    if (tag == 0) prof_begin(c);
-#define PACER_GO(TAG_, MT_, NT_) launch_w16<EPI, TAG_, MT_, NT_>(c, ga, n_tiles)
-    if (tag == 0) {
-      if (mt == 1) { if (nt2) PACER_GO(0, 1, 2); else PACER_GO(0, 1, 1); }
-      else         { if (nt2) PACER_GO(0, 2, 2); else PACER_GO(0, 2, 1); }
+    if (TAG == 0) prof_begin(c);
+    if (mt == 1) {
+      if (many) launch_w16<EPI, TAG, 1, 1, 4, 8>(c, ga, n_tiles);
+      else launch_w16<EPI, TAG, 1, 1, 8, 4>(c, ga, n_tiles);
+    } else if (ga.R - 16 * mt0 == 17) {               // 17 rows: second row tile reduced to its one column
+      launch_w16<EPI, TAG, 2, 1, 8, 4, 1>(c, ga, n_tiles);
     } else {
-      if (mt == 1) { if (nt2) PACER_GO(1, 1, 2); else PACER_GO(1, 1, 1); }
-      else         { if (nt2) PACER_GO(1, 2, 2); else PACER_GO(1, 2, 1); }
+      if (many && even) launch_w16<EPI, TAG, 2, 2, 4, 4>(c, ga, n_tiles);
+      else launch_w16<EPI, TAG, 2, 1, 8, 4>(c, ga, n_tiles);
     }
-#undef PACER_GO
-    if (tag == 0) prof_end(c, (double)n_tiles * 16.0 * K * 2.0);
+    if (TAG == 0) prof_end(c, (double)n_tiles * 16.0 * K * 2.0);
   }
+}
+template <int EPI>
+void gemm_w16(pacer_ctx* c, int tag, const GemmArgs& ga, int n_tiles, int K) {
+  if (tag == 0) gemm_w16_tag<EPI, 0>(c, ga, n_tiles, K);
+  else gemm_w16_tag<EPI, 1>(c, ga, n_tiles, K);
 }
 
 void rope_table(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
@@ -232,8 +242,10 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
     max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
     max_rows = std::max(max_rows, sr.row_off[i + 1] - sr.row_off[i]);
   }
-  int kpw = std::max(128, ((max_keys + kMaxChunks - 1) / kMaxChunks + 31) / 32 * 32);
-  const int n_part = (max_keys + kpw - 1) / kpw;
+  // keys per block (8 waves): 1024 (one block per head, no global merge, up to 1k context), more
+  // when that would give over 16 splits
+  const int kps = std::max(1024, ((max_keys + 15) / 16 + 31) / 32 * 32);
+  const int S = (max_keys + kps - 1) / kps;
   GemmArgs base{};
   base.R = R;
   base.sr = sr;
@@ -258,13 +270,12 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
     }
     if (kv_only) continue;
     {
-      const dim3 grid((n_part + 3) / 4, H, sr.n_seqs);
+      const dim3 grid(S, H, sr.n_seqs);
       const _Float16* kv = static_cast<const _Float16*>(m.kv);
-#define PACER_ATT(HD_, MT_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_>), grid, dim3(256), 0, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kpw, n_part, H, c->part)
+#define PACER_ATT(HD_, MT_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_>), grid, dim3(512), 0, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->att_cnt, c->xpB, mt_total)
       if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2); else PACER_ATT(128, 1); }
       else           { if (max_rows > 16) PACER_ATT(64, 2); else PACER_ATT(64, 1); }
 #undef PACER_ATT
-      hipLaunchKernelGGL(attn_combine_w16_kernel, dim3(R, H), dim3(hd), 0, c->stream, c->part, sr, kpw, n_part, H, hd, c->xpB, mt_total);
     }
     {
       GemmArgs ga = base;
@@ -602,6 +613,7 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
   void* dp = nullptr;
   HIPCHK(c, hipHostGetDevicePointer(&dp, hp, 0));
   c->host_res_dev = static_cast<int*>(dp);
+  HIPCHK(c, hipMemsetAsync(c->att_cnt, 0, sizeof(int) * c->max_batch * c->hmax, c->stream));   // tickets reset themselves afterwards
   c->ws_bound = true;
   return PACER_OK;
 }

@@ -79,3 +79,10 @@ def test_7b_width_two_layers_bf16():
     FFN 11008, V 32000) at a depth the oracle can afford; 68M-shaped draft; gamma_max 16, b 4."""
     _run("7b", 100, 20, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2,
          w_over=dict(mode="greedy"))
+
+
+def test_7b_width_full_window_and_long_prompt():
+    """gamma = gamma_max = 16 every step (17 verify rows: MFMA tile + the extra plain row), on a
+    1100-token prompt (attention splits its keys over two blocks and merges them)."""
+    _run("7b", 1100, 12, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2, max_seq=1280,
+         w_over=dict(mode="greedy"), step_kw=dict(force_stop=lambda k, a: False))
