@@ -79,9 +79,22 @@ __device__ __forceinline__ void store_packed4(_Float16* __restrict__ xp, int MT_
 }
 
 // x = E[token]; operand = f16(x * g); ssq slot 0 = sum x^2.  Block 0 also clears the other slots.
+// cos/sin of row r's absolute position for the model's rotation frequencies, evaluated in double
+__device__ __forceinline__ void rope_row(float* __restrict__ tab, int r, int pos, int hd, float theta) {
+  const int half = hd >> 1;
+  for (int j = threadIdx.x; j < half; j += blockDim.x) {
+    const double inv = pow((double)theta, -2.0 * (double)j / (double)hd);
+    double sn, cs;
+    sincos((double)pos * inv, &sn, &cs);
+    tab[((size_t)r * half + j) * 2] = (float)cs;
+    tab[((size_t)r * half + j) * 2 + 1] = (float)sn;
+  }
+}
+
 __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __restrict__ tokens, const int* __restrict__ draft_tok,
                                  SeqRows sr, int max_seq, int G1, int d, float* __restrict__ x, int ldx, const float* __restrict__ g,
-                                 _Float16* __restrict__ xp, int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride) {
+                                 _Float16* __restrict__ xp, int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride,
+                                 float* __restrict__ rope, int hd, float theta) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   if (r == 0)
@@ -89,6 +102,7 @@ __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __re
   const int si = find_seq(sr, r);
   const int s = sr.seq[si];
   const int p = sr.pos0[si] + (r - sr.row_off[si]);
+  rope_row(rope, r, p, hd, theta);
   const int tok = p < sr.len[si] ? tokens[(size_t)s * max_seq + p] : draft_tok[s * G1 + (p - sr.len[si])];
   const uint16_t* e = E + (size_t)tok * d;
   float ss = 0.f;
@@ -107,13 +121,15 @@ __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __re
 // input rows of the pre-verification layer: x = hidden + PosEmb[e]; operand and ssq as above
 __global__ void mb_input_w16_kernel(const float* __restrict__ src, int lds, const float* __restrict__ posemb, SeqRows sr, MbRows mr,
                                     int d, float* __restrict__ x, int ldx, const float* __restrict__ g, _Float16* __restrict__ xp,
-                                    int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride) {
+                                    int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride, float* __restrict__ rope,
+                                    int hd, float theta) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   if (r == 0)
     for (int i = threadIdx.x + slot_stride; i < n_slots * slot_stride; i += blockDim.x) ssq[i] = 0ull;
   const int si = find_seq(sr, r);
   const int rr = r - sr.row_off[si];
+  rope_row(rope, r, sr.pos0[si] + rr, hd, theta);
   const float* h = src + (size_t)(mr.src_row0[si] + rr) * lds;
   const float* e = posemb + (size_t)(mr.e0[si] < 0 ? 0 : mr.e0[si] + rr) * d;
   float ss = 0.f;
@@ -153,6 +169,12 @@ struct GemmArgs {
   _Float16* kv;          // QKV: cache base of the model
   const float* rope;     // QKV: [R][hd/2][2] cos, sin
   int d, hd, layer, n_layers, max_seq, H;
+  // STORE of draft logits: per (row, output tile) candidate of the token choice
+  float* pick_val;       // [rows][pick_tiles] best logit (+ Gumbel noise when sampling); null: off
+  int* pick_idx;
+  int pick_tiles, pick_mode;
+  uint64_t pick_seed;
+  uint32_t pick_step;
   SeqRows sr;
 };
 
@@ -161,8 +183,9 @@ struct GemmArgs {
 // tile each lane reads the 16 bytes of column 0 (a 64-byte broadcast per K step) and the other columns
 // are zeroed in registers.  The second MFMA per step is idle work on an idle unit; the operand traffic
 // is what mattered.
+// 8-wave blocks are held to 128 VGPRs (4 waves per SIMD) so that two blocks fit a CU.
 template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0>
-__global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const GemmArgs ga) {
+__global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_kernel(const GemmArgs ga) {
   static_assert(!X17 || MT == 2, "the 17-row form uses two row tiles");
   __shared__ f32x4 red[WAVES][NT * MT][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -258,10 +281,41 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w16_kernel(const GemmArgs ga)
     if (ga.ssq_in && live) rs = row_scale(ga.ssq_in, m, ga.inv_dim, ga.eps);
 
     if (EPI == EPI_STORE) {
+      const int n = nt * 16 + g4 * 4;
+      const f32x4 lg = s * rs;
       if (live) {
-        const int n = nt * 16 + g4 * 4;
         float* o = ga.out + (size_t)map_row(ga.sr, ga.rowmap, ga.G1, m) * ga.ldo + n;
-        *reinterpret_cast<f32x4*>(o) = s * rs;
+        *reinterpret_cast<f32x4*>(o) = lg;
+      }
+      if (ga.pick_val) {
+        // token choice, first stage: best of this tile's 16 vocabulary entries for row m
+        // (argmax of the logits, or of logits + Gumbel noise; lowest id wins ties)
+        float best = -INFINITY;
+        int bi = 0x7fffffff;
+        if (live) {
+          float g4n[4] = {0.f, 0.f, 0.f, 0.f};
+          if (ga.pick_mode) {
+            const int si = find_seq(ga.sr, m);
+            const int jrow = ga.sr.pos0[si] + (m - ga.sr.row_off[si]) - (ga.sr.len[si] - 1);
+            const uint4 bits = vocab_bits(ga.pick_seed, ga.sr.seq[si], ga.pick_step, (uint32_t)(jrow + 1), PURPOSE_DRAFT, (uint32_t)(n >> 2));
+            g4n[0] = gumbel(u01(bits.x)); g4n[1] = gumbel(u01(bits.y)); g4n[2] = gumbel(u01(bits.z)); g4n[3] = gumbel(u01(bits.w));
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float v = lg[r] + g4n[r];
+            if (v > best) { best = v; bi = n + r; }
+          }
+        }
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+          const float ov = __shfl_xor(best, o, 64);
+          const int oi = __shfl_xor(bi, o, 64);
+          if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+        }
+        if (live && g4 == 0) {
+          ga.pick_val[(size_t)m * ga.pick_tiles + nt] = best;
+          ga.pick_idx[(size_t)m * ga.pick_tiles + nt] = bi;
+        }
       }
     } else if (EPI == EPI_RESID) {
       float sq = 0.f;
@@ -574,35 +628,23 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
 }
 
 // ------------------------------------------------------------------ tail of a draft forward
-// one block per listed sequence: hidden state h = x * g_final * row_scale into the ring, then the token
-__global__ __launch_bounds__(1024) void draft_tail_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g,
-                                                          const u64* __restrict__ ssq, float inv_dim, float eps, int d,
-                                                          float* __restrict__ hidden, const float* __restrict__ ring,
-                                                          int* __restrict__ draft_tok, PickArgs pa, int G1, int V, int mode,
-                                                          uint64_t seed, uint32_t step) {
+// one block per listed sequence: hidden state h = x * g_final * row_scale into the ring, and the token
+// = best of the per-tile candidates the LM-head GEMM left
+__global__ void draft_tail_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
+                                  float inv_dim, float eps, int d, float* __restrict__ hidden, const float* __restrict__ pick_val,
+                                  const int* __restrict__ pick_idx, int pick_tiles, int* __restrict__ draft_tok, PickArgs pa, int G1) {
   __shared__ float redv[16];
   __shared__ int redi[16];
   const int si = blockIdx.x, s = pa.seq[si], j = pa.j[si];
   const float rs = row_scale(ssq, si, inv_dim, eps);
   float* ho = hidden + (size_t)(s * G1 + j) * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) ho[k] = x[(size_t)si * ldx + k] * g[k] * rs;
-  const float* lg = ring + (size_t)(s * G1 + j) * V;
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int blk = threadIdx.x; blk * 4 < V; blk += blockDim.x) {
-    float g4[4] = {0.f, 0.f, 0.f, 0.f};
-    if (mode) {
-      const uint4 b = vocab_bits(seed, s, step, (uint32_t)(j + 1), PURPOSE_DRAFT, (uint32_t)blk);
-      g4[0] = gumbel(u01(b.x)); g4[1] = gumbel(u01(b.y)); g4[2] = gumbel(u01(b.z)); g4[3] = gumbel(u01(b.w));
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int v = blk * 4 + e;
-      if (v < V) {
-        const float val = lg[v] + g4[e];
-        if (val > best) { best = val; bi = v; }
-      }
-    }
+  for (int t = threadIdx.x; t < pick_tiles; t += blockDim.x) {
+    const float v = pick_val[(size_t)si * pick_tiles + t];
+    const int i = pick_idx[(size_t)si * pick_tiles + t];
+    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
   }
   block_argmax(best, bi, redv, redi);
   if (threadIdx.x == 0) draft_tok[s * G1 + j] = bi;

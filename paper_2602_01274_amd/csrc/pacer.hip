@@ -59,6 +59,8 @@ struct pacer_ctx {
   _Float16 *xpA = nullptr, *xpB = nullptr, *qp = nullptr;   // bf16 path: ping-pong f16 operands, attention Q operand
   u64* ssq = nullptr;                                         // bf16 path: row sums of squares, [2*Lmax+1][rcap]
   int* att_cnt = nullptr;                                     // bf16 path: arrival tickets per (sequence slot, head)
+  float* pick_val = nullptr;                                  // bf16 path: per (row, vocab tile) token candidates
+  int* pick_idx = nullptr;
   int lmax = 0;
   int* host_res = nullptr;      // pinned host memory [max_batch][2]
   int* host_res_dev = nullptr;  // its device alias
@@ -136,6 +138,8 @@ size_t carve(pacer_ctx* c, void* base) {
   c->qp = k.take<_Float16>((size_t)c->max_batch * (c->dmax / 32) * 2 * 512);
   c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * c->rcap);
   c->att_cnt = k.take<int>((size_t)c->max_batch * c->hmax);
+  c->pick_val = k.take<float>((size_t)c->max_batch * (V / 16 + 1));
+  c->pick_idx = k.take<int>((size_t)c->max_batch * (V / 16 + 1));
   return k.off;
 }
 
@@ -236,14 +240,14 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
   const pacer_model_cfg& g = m.cfg;
   const int d = g.d_model, F = g.d_ffn, L = g.n_layers, H = g.n_heads, hd = g.head_dim;
   const int mt_total = (R + 15) / 16;
-  rope_table(c, m, R, sr);
   int max_keys = 0, max_rows = 0;
   for (int i = 0; i < sr.n_seqs; ++i) {
     max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
     max_rows = std::max(max_rows, sr.row_off[i + 1] - sr.row_off[i]);
   }
-  // keys per block (8 waves): 1024 (one block per head, no global merge, up to 1k context), more
-  // when that would give over 16 splits
+  // keys per block (8 waves): 1024, i.e. one block per head and no global merge up to 1k context
+  // (measured: the device-scope fence of the split path costs more than it saves below that), more
+  // when that would exceed 16 splits
   const int kps = std::max(1024, ((max_keys + 15) / 16 + 31) / 32 * 32);
   const int S = (max_keys + kps - 1) / kps;
   GemmArgs base{};
@@ -312,11 +316,21 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
 void embed_w16(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
   hipLaunchKernelGGL(embed_w16_kernel, dim3(R), dim3(256), 0, c->stream, static_cast<const uint16_t*>(m.embed), c->tokens, c->draft_tok, sr,
                      c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax, m.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq,
-                     2 * m.cfg.n_layers + 1, c->rcap);
+                     2 * m.cfg.n_layers + 1, c->rcap, c->rope, m.cfg.head_dim, m.cfg.rope_theta);
 }
 
-void lm_head_w16(pacer_ctx* c, const Model& m, int tag, int R, float* out, const SeqRows& sr, int rowmap) {
+struct PickCfg { int on, mode; uint64_t seed; uint32_t step; };
+
+void lm_head_w16(pacer_ctx* c, const Model& m, int tag, int R, float* out, const SeqRows& sr, int rowmap, const PickCfg* pick = nullptr) {
   GemmArgs ga{};
+  if (pick && pick->on) {
+    ga.pick_val = c->pick_val;
+    ga.pick_idx = c->pick_idx;
+    ga.pick_tiles = m.cfg.vocab / 16;
+    ga.pick_mode = pick->mode;
+    ga.pick_seed = pick->seed;
+    ga.pick_step = pick->step;
+  }
   ga.R = R; ga.sr = sr; ga.G1 = c->G1; ga.rowmap = rowmap; ga.eps = m.cfg.rms_eps;
   ga.W = static_cast<const u32x4*>(m.head);
   ga.X = reinterpret_cast<const u32x4*>(c->xpA);
@@ -393,7 +407,7 @@ void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr
   const Model& mb = c->m[PACER_PREVERIFY];
   if (is_w16(mb)) {
     hipLaunchKernelGGL(mb_input_w16_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax,
-                       mb.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq, 3, c->rcap);
+                       mb.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq, 3, c->rcap, c->rope, mb.cfg.head_dim, mb.cfg.rope_theta);
     run_layers_w16(c, mb, 1, R, sr, kv_only);
   } else {
     hipLaunchKernelGGL(mb_input_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax);
@@ -429,10 +443,11 @@ void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int m
   sr.row_off[n] = n;
   if (is_w16(md)) {
     forward_lm(c, md, 1, n, sr);
-    lm_head(c, md, 1, n, c->ring, sr, ROWMAP_RING);
-    hipLaunchKernelGGL(draft_tail_kernel, dim3(n), dim3(1024), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
-                       1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->ring, c->draft_tok, pa, c->G1, md.cfg.vocab,
-                       mode, seed, (uint32_t)ctr);
+    const PickCfg pick{1, mode, seed, (uint32_t)ctr};
+    lm_head_w16(c, md, 1, n, c->ring, sr, ROWMAP_RING, &pick);
+    hipLaunchKernelGGL(draft_tail_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
+                       1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->pick_val, c->pick_idx, md.cfg.vocab / 16,
+                       c->draft_tok, pa, c->G1);
   } else {
     hipLaunchKernelGGL((embed_rows_kernel<float>), dim3(n), dim3(256), 0, c->stream, static_cast<const float*>(md.embed), c->tokens,
                        c->draft_tok, sr, c->max_seq, c->G1, md.cfg.d_model, c->x, c->dmax);
