@@ -195,6 +195,60 @@ class Session:
             out["target_logits"] = self.logits[0, :gamma + 1].clone()
         return out
 
+    def step_batch(self, seqs, mode=B.GREEDY, betas=None, seed=0, fixed_gamma=None, record=False):
+        """One outer iteration of Alg. 1 for several sequences in lock step: sequences whose block
+        fails pre-verification (or that reach gamma_max) drop out of the drafting loop, the others
+        go on; one ragged verify and one accept call serve all of them."""
+        betas = [self.w["beta"]] * len(seqs) if betas is None else list(betas)
+        ctx, ctr = self.ctx, self.step_idx[seqs[0]]
+        assert all(self.step_idx[s] == ctr for s in seqs), "lock-step sequences share the step counter"
+        for s in seqs:
+            B.pacer_begin_step(ctx, s)
+        gamma = {s: 0 for s in seqs}
+        recs = {s: dict(alpha=[], stops=[]) for s in seqs}
+        active = list(seqs)
+        if fixed_gamma is not None:
+            for _ in range(fixed_gamma):
+                self._call("draft_step", B.pacer_draft_step, ctx, active, mode, seed, ctr)
+            gamma = {s: fixed_gamma for s in seqs}
+            self.counts["draft"] += fixed_gamma * len(seqs)
+            active = []
+        while active:
+            for _ in range(self.block):
+                self._call("draft_step", B.pacer_draft_step, ctx, active, mode, seed, ctr)
+            self.counts["draft"] += self.block * len(active)
+            self._call("preverify_block", B.pacer_preverify_block, ctx, active, self.alpha, self.stop)
+            self.counts["preverify"] += len(active)
+            stops = self.stop[:len(active)].tolist()
+            alphas = self.alpha[:len(active)].tolist() if record else None
+            nxt = []
+            for i, s in enumerate(active):
+                gamma[s] += self.block
+                if record:
+                    recs[s]["alpha"] += alphas[i]
+                    recs[s]["stops"].append(bool(stops[i]))
+                if not stops[i] and gamma[s] + self.block <= self.gamma_max:
+                    nxt.append(s)
+            active = nxt
+        self._call("verify", B.pacer_verify, ctx, seqs, None, self.logits)
+        self.counts["target"] += 1
+        self._call("accept_rollback", B.pacer_accept_rollback, ctx, seqs, mode, betas, seed, ctr, self.logits,
+                   self.n_acc, self.next_tok)
+        out = []
+        for i, s in enumerate(seqs):
+            st = B.pacer_get_state(ctx, s)
+            self.step_idx[s] += 1
+            r = dict(gamma=gamma[s], n=st["n_accepted"], z=st["next_token"], len=st["len"])
+            if record:
+                g = gamma[s]
+                r.update(recs[s])
+                r["draft_tokens"] = self.draft_tokens(s)[:g].tolist()
+                r["draft_logits"] = self.draft_logits(s)[:g + 1].clone()
+                r["hidden"] = self.draft_hidden(s)[:g + 1].clone()
+                r["target_logits"] = self.logits[i, :g + 1].clone()
+            out.append(r)
+        return out
+
     def generate(self, n_new, seq=0, **kw):
         start = B.pacer_get_state(self.ctx, seq)["len"]
         recs = []

@@ -31,8 +31,8 @@ class StepChecker:
         own logits; logged as ("within_error", ...).
     After a logged flip the GPU sequence is re-prefilled with the oracle's prefix."""
 
-    def __init__(self, sess, orc, tol_logits, tol_alpha, tie=1e-3, mode=po.GREEDY, seed=0):
-        self.s, self.o = sess, orc
+    def __init__(self, sess, orc, tol_logits, tol_alpha, tie=1e-3, mode=po.GREEDY, seed=0, seq=0):
+        self.s, self.o, self.seq = sess, orc, seq
         self.tol_logits, self.tol_alpha, self.tie = tol_logits, tol_alpha, tie
         self.mode, self.seed = mode, seed
         self.flips = []
@@ -40,8 +40,8 @@ class StepChecker:
         self.steps = 0
 
     def _resync(self):
-        self.s.prefill(self.o.tokens)
-        self.s.step_idx[0] = self.o.step_idx
+        self.s.prefill(self.o.tokens, seq=self.seq)
+        self.s.step_idx[self.seq] = self.o.step_idx
 
     def _explain(self, kind, margin, k, err=0.0):
         bound = max(self.tie, 2.0 * err)
@@ -52,6 +52,10 @@ class StepChecker:
         step_idx = self.o.step_idx
         ro = self.o.step(**kw)
         rg = self.s.step(mode=self.mode, seed=self.seed, record=True, **kw)
+        return self.check(ro, rg, step_idx)
+
+    def check(self, ro, rg, step_idx):
+        """Compare one finished step of this sequence (ro: oracle record, rg: GPU record)."""
         self.steps += 1
         beta = self.o.beta
         # --- drafting: compare row by row until the first differing draft token
@@ -66,7 +70,7 @@ class StepChecker:
             if rg["draft_tokens"][k] != ro["draft_tokens"][k]:
                 row = ro["draft_logits"][k]
                 if self.mode == po.SAMPLE:
-                    u = philox.vocab_uniforms(self.seed, 0, step_idx, k + 1, philox.PURPOSE_DRAFT, len(row))
+                    u = philox.vocab_uniforms(self.seed, self.seq, step_idx, k + 1, philox.PURPOSE_DRAFT, len(row))
                     row = row + philox.gumbel(u)
                 self._explain("draft_token", top2_gap(row), k, abs_err(dl[k], ro["draft_logits"][k]))
                 self._resync()
@@ -118,7 +122,7 @@ class StepChecker:
     def _next_gap(self, ro, step_idx):
         n, gam, beta = ro["n"], ro["gamma"], self.o.beta
         V = ro["target_logits"].shape[1]
-        u = philox.vocab_uniforms(self.seed, 0, step_idx, n + 1, philox.PURPOSE_NEXT, V)
+        u = philox.vocab_uniforms(self.seed, self.seq, step_idx, n + 1, philox.PURPOSE_NEXT, V)
         if n == gam:
             keys = ro["target_logits"][gam] + beta * ro["bonus_draft_logits"] + philox.gumbel(u)
         else:

@@ -86,3 +86,46 @@ def test_7b_width_full_window_and_long_prompt():
     1100-token prompt (attention splits its keys over two blocks and merges them)."""
     _run("7b", 1100, 12, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2, max_seq=1280,
          w_over=dict(mode="greedy"), step_kw=dict(force_stop=lambda k, a: False))
+
+
+def _run_batch(name, prompt_lens, betas, n_steps, tol_logits, tol_alpha, mode=po.GREEDY, seed=5, max_seq=512,
+               n_layers_target=None):
+    """Several sequences in lock step (ragged verify batch, per-sequence gamma, beta and length)
+    against one oracle per sequence."""
+    w = synth.workload(name)
+    tgt, drf, mb = synth.make_pair(w, seed=0, gain_jitter=0.1, n_layers_target=n_layers_target)
+    nb = len(prompt_lens)
+    s = _session(w, tgt, drf, mb, max_seq, max_batch=nb)
+    cks = []
+    for i, (pl, beta) in enumerate(zip(prompt_lens, betas)):
+        prompt = synth.make_prompt(w["target"]["vocab"], pl, 10 + i).tolist()
+        o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=seed, max_seq=max_seq, cache=True, seq=i, beta=beta)
+        s.prefill(prompt, seq=i)
+        o.prefill(prompt)
+        cks.append(StepChecker(s, o, tol_logits, tol_alpha, mode=mode, seed=seed, seq=i))
+    gam = []
+    for _ in range(n_steps):
+        idx = [ck.o.step_idx for ck in cks]
+        ros = [ck.o.step() for ck in cks]
+        rgs = s.step_batch(list(range(nb)), mode=mode, betas=betas, seed=seed, record=True)
+        for ck, ro, rg, k in zip(cks, ros, rgs, idx):
+            ck.check(ro, rg, k)
+        gam.append([r["gamma"] for r in ros])
+    for i, ck in enumerate(cks):
+        assert s.tokens(i) == ck.o.tokens
+    flips = [f for ck in cks for f in ck.flips]
+    print(f"\n[batch {name} x{nb} mode={mode}] gammas={gam} max_err={[ck.max_err['target_logits'] for ck in cks]} flips={flips}")
+    assert len(flips) <= max(2, n_steps * nb // 5)
+    assert len({tuple(g) for g in gam}) > 1 or len(set(gam[0])) > 1      # the batch really was ragged
+    s.close()
+
+
+def test_batch_tiny_f32_ragged():
+    _run_batch("tiny", [5, 33, 70], [4.0, 1.0, 2.5], 10, 1e-4, 1e-4)
+    _run_batch("tiny", [9, 64], [4.0, 3.0], 8, 1e-4, 1e-4, mode=po.SAMPLE)
+
+
+def test_batch_mid_bf16_ragged():
+    """BASELINE config 5 in miniature: ragged batch, per-sequence beta in [1, 5], prompt lengths
+    spread over several attention tiles; 4 sequences x up to 13 verify rows = two 32-row GEMM chunks."""
+    _run_batch("mid", [40, 75, 150, 260], [1.0, 2.3, 3.7, 5.0], 6, 2e-2, 2e-2)
