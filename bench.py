@@ -25,20 +25,26 @@ def weight_bytes(shape, n_layers=None):
     return 2.0 * (L * (4 * d * d + 3 * d * f) + v * d)
 
 
-def run_steps(sess, n, mode, seed, **kw):
+def run_steps(sess, n, mode, seed, batch=None, **kw):
+    """n outer iterations of Alg. 1 (for a batch: n lock-step iterations of all sequences)."""
     import torch
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    toks, gam, acc = 0, 0, 0
+    toks, gam, acc, cnt = 0, 0, 0, 0
     for _ in range(n):
-        r = sess.step(mode=mode, seed=seed, **kw)
-        toks += r["n"] + 1
-        gam += r["gamma"]
-        acc += r["n"]
+        if batch is None:
+            rs = [sess.step(mode=mode, seed=seed, **kw)]
+        else:
+            rs = sess.step_batch(batch["seqs"], mode=mode, betas=batch["betas"], seed=seed, **kw)
+        for r in rs:
+            toks += r["n"] + 1
+            gam += r["gamma"]
+            acc += r["n"]
+            cnt += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     return dict(tokens=toks, seconds=dt, tok_s=toks / dt, ms_per_step=1e3 * dt / n,
-                mean_gamma=gam / n, tau=acc / n)
+                mean_gamma=gam / cnt, tau=acc / cnt)
 
 
 def cpu_baseline(w, tgt, drf, mb, prompt, mode, budget_steps=2, n_prompt=16):
@@ -86,11 +92,21 @@ def main():
     w = synth.workload(a.workload)
     mode = B.SAMPLE if w["mode"] == "sample" else B.GREEDY
     K, W = a.steps, a.warmup
-    n_prompt = w["prompt"]
+    nb = w["batch"]
+    batch = None
+    if nb > 1:
+        lens = synth.make_lengths(w["prompt"][0], w["prompt"][1], nb, 4)
+        batch = dict(seqs=list(range(nb)), betas=synth.make_betas(1.0, 5.0, nb, 5))
+        w["beta"] = sum(batch["betas"]) / nb
+        n_prompt = max(lens)
+    else:
+        lens = [w["prompt"]]
+        n_prompt = w["prompt"]
     max_seq = n_prompt + (K + W) * (w["gamma_max"] + 1) + 64
     tgt, drf, mb = synth.make_pair(w, seed=0, device="cuda", n_layers_target=a.layers)
-    prompt = synth.make_prompt(w["target"]["vocab"], n_prompt, 1).tolist()
-    sess = Session(w, tgt, drf, mb, max_seq=max_seq)
+    prompts = [synth.make_prompt(w["target"]["vocab"], n, 1 + i).tolist() for i, n in enumerate(lens)]
+    prompt = prompts[0]
+    sess = Session(w, tgt, drf, mb, max_seq=max_seq, max_batch=nb)
     host = None
     if not a.no_cpu_baseline:
         to_host = lambda x: ({k: to_host(v) for k, v in x.items()} if isinstance(x, dict)
@@ -100,34 +116,35 @@ def main():
     torch.cuda.empty_cache()
 
     def fresh():
-        sess.prefill(prompt)
+        for i, p in enumerate(prompts):
+            sess.prefill(p, seq=i)
         sess.counts = dict(draft=0, target=0, preverify=0)
 
     # ---- the timed region: W warm-up steps, then exactly K steps ----
     fresh()
-    run_steps(sess, W, mode, 3)
-    main_run = run_steps(sess, K, mode, 3)
+    run_steps(sess, W, mode, 3, batch)
+    main_run = run_steps(sess, K, mode, 3, batch)
     counts = dict(sess.counts)
 
     # ---- same K steps with HIP events around every launch of the weight-streaming GEMM ----
     fresh()
-    run_steps(sess, W, mode, 3)
+    run_steps(sess, W, mode, 3, batch)
     B.pacer_profile_enable(sess.ctx, True)
     B.pacer_profile_read(sess.ctx)
     prof_steps = min(K, 40)
-    run_steps(sess, prof_steps, mode, 3)
+    run_steps(sess, prof_steps, mode, 3, batch)
     n_launch, gemm_ms, gemm_bytes = B.pacer_profile_read(sess.ctx)
     B.pacer_profile_enable(sess.ctx, False)
 
     # ---- per-call timing (events around each C call) ----
     fresh()
-    run_steps(sess, W, mode, 3)
+    run_steps(sess, W, mode, 3, batch)
     sess.timers = {}
-    run_steps(sess, prof_steps, mode, 3)
+    run_steps(sess, prof_steps, mode, 3, batch)
     tm = sess.read_timers()
     sess.timers = None
     L = a.layers if a.layers else w["target"]["n_layers"]
-    ctx_len = n_prompt + 0.5 * main_run["tokens"]
+    ctx_len = sum(lens) + 0.5 * main_run["tokens"]        # summed over the batch
     kv_t = 2.0 * 2 * w["target"]["d_model"] * L * ctx_len
     kv_d = 2.0 * 2 * w["draft"]["d_model"] * w["draft"]["n_layers"] * ctx_len
     alg = {"verify": weight_bytes(w["target"], L) + kv_t,
@@ -145,11 +162,11 @@ def main():
     context = {}
     if not a.no_context:
         n_ctx = max(8, K // 4)
-        fresh(); run_steps(sess, 3, mode, 3, fixed_gamma=0)
-        context["autoregressive_tok_s"] = round(run_steps(sess, n_ctx, mode, 3, fixed_gamma=0)["tok_s"], 2)
+        fresh(); run_steps(sess, 3, mode, 3, batch, fixed_gamma=0)
+        context["autoregressive_tok_s"] = round(run_steps(sess, n_ctx, mode, 3, batch, fixed_gamma=0)["tok_s"], 2)
         for g in (4, 8):
-            fresh(); run_steps(sess, 3, mode, 3, fixed_gamma=g)
-            context[f"fixed_gamma_{g}_tok_s"] = round(run_steps(sess, n_ctx, mode, 3, fixed_gamma=g)["tok_s"], 2)
+            fresh(); run_steps(sess, 3, mode, 3, batch, fixed_gamma=g)
+            context[f"fixed_gamma_{g}_tok_s"] = round(run_steps(sess, n_ctx, mode, 3, batch, fixed_gamma=g)["tok_s"], 2)
 
     cpu = None
     if host is not None:
@@ -161,10 +178,11 @@ def main():
         "value": round(main_run["tok_s"], 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(main_run["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{a.workload}: {L}-layer d{w['target']['d_model']} target + 68M-shaped draft, "
-                               f"prompt {n_prompt}, {'sampling T=1' if mode else 'greedy'}, gamma_max {w['gamma_max']}, "
-                               f"b {w['block']}, beta {w['beta']}, t0 {w['t0']}, rho {w['rho']}",
-                   "batch": 1, "new_tokens": main_run["tokens"]},
+        "config": {"workload": f"{a.workload}: {L}-layer d{w['target']['d_model']} target + {w['draft']['n_layers']}-layer "
+                               f"d{w['draft']['d_model']} draft, prompt {n_prompt if nb == 1 else lens}, "
+                               f"{'sampling T=1' if mode else 'greedy'}, gamma_max {w['gamma_max']}, "
+                               f"b {w['block']}, beta {round(w['beta'], 3) if nb == 1 else 'U[1,5] per sequence'}, t0 {w['t0']}, rho {w['rho']}",
+                   "batch": nb, "new_tokens": main_run["tokens"]},
         "tau": round(main_run["tau"], 3), "mean_gamma": round(main_run["mean_gamma"], 3),
         "forwards": counts, "verify_GBps": calls.get("verify", {}).get("GBps"),
         "calls": calls, "context": context,

@@ -206,6 +206,11 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
   const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 64 + (lane & 48);   // column 0 of row tile mt0+1
   const bool col0 = (lane & 15) == 0;
   const int mtt = ga.mt_total;
+  // operand columns beyond the last row are never fetched (their accumulator columns are discarded):
+  // the operand traffic scales with the number of rows instead of with whole 16-row tiles
+  bool col_live[MT];
+#pragma unroll
+  for (int b = 0; b < MT; ++b) col_live[b] = (ga.mt0 + b) * 16 + (lane & 15) < ga.R;
 
   u32x4 A0[U][NT], A1[U][NT], B0[U][MT], B1[U][MT];
   const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -221,7 +226,10 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
           B[u][1] = xp17[(size_t)kt * mtt * 64];
         } else {
 #pragma unroll
-          for (int b = 0; b < MT; ++b) B[u][b] = xp[((size_t)kt * mtt + b) * 64];
+          for (int b = 0; b < MT; ++b) {
+            B[u][b] = zero;
+            if (col_live[b]) B[u][b] = xp[((size_t)kt * mtt + b) * 64];
+          }
         }
       } else {
 #pragma unroll
