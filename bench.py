@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="truncate target depth (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true", help="skip the AR / fixed-gamma context runs")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
@@ -172,6 +174,23 @@ def main():
     if host is not None:
         cpu = cpu_baseline(w, host[0], host[1], host[2], prompt, 1 if mode == B.SAMPLE else 0)
 
+    if a.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # HBM bytes per launch counted by rocprofv3 (FETCH_SIZE / WRITE_SIZE, scaled by a plain copy):
+    # taken from the committed summary of the same workload, if there is one
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", f"gemm_w16_{a.workload}_hbm_traffic.txt")
+    if os.path.exists(tf) and a.layers is None:
+        for line in open(tf):
+            if line.startswith("traffic_bytes_per_launch="):
+                traffic = float(line.split("=", 1)[1])
+
     achieved = gemm_bytes / 1e9 / (gemm_ms / 1e3) if gemm_ms > 0 else 0.0
     out = {
         "metric": "decode tokens/s (7B-shape target, bs1) + verify-step achieved HBM GB/s",
@@ -186,9 +205,9 @@ def main():
         "tau": round(main_run["tau"], 3), "mean_gamma": round(main_run["mean_gamma"], 3),
         "forwards": counts, "verify_GBps": calls.get("verify", {}).get("GBps"),
         "calls": calls, "context": context,
-        "roofline": {"bound": "hbm", "kernel": "gemm_w16_kernel (all instantiations, all launches of the run)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_w16_kernel, target-model launches (template TAG 0), all shapes",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "launches": int(n_launch), "avg_launch_us": round(1e3 * gemm_ms / max(1, n_launch), 3),
                      "avg_launch_bytes": round(gemm_bytes / max(1, n_launch), 1)},
         "cpu_baseline": cpu,
