@@ -82,11 +82,16 @@ typedef struct {
   int32_t dtype; /* PACER_F32 or PACER_BF16: type of the matrices and the embedding */
 } pacer_model_cfg;
 
+#define PACER_HALT_MEAN 0 /* stop if mean(alpha) <= t: the paper's criterion (Alg. 1)        */
+#define PACER_HALT_ANY 1  /* stop if any alpha_j <= t   (stricter alternative of Sec. 5.2)   */
+#define PACER_HALT_LAST 2 /* stop if the block's last alpha <= t   (Sec. 5.2)                */
+
 /* Inputs of Alg. 1: block size b, initial threshold t, growth factor rho; gamma_max caps the
  * window (the paper's inner loop has no cap) and must be a multiple of block. */
 typedef struct {
   int32_t block, gamma_max;
   float t0, rho;
+  int32_t halting; /* PACER_HALT_* */
 } pacer_pv_cfg;
 
 /* ---- set-up (not hot) ---------------------------------------------------------------- */

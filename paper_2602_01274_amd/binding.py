@@ -18,6 +18,7 @@ OK, EINVAL, ESTATE, EOVERFLOW, EHIP = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
 TARGET, DRAFT, PREVERIFY = 0, 1, 2
 GREEDY, SAMPLE = 0, 1
+HALT_MEAN, HALT_ANY, HALT_LAST = 0, 1, 2
 T_EMBED, T_FINAL_NORM, T_HEAD, T_ATTN_NORM, T_WQKV, T_WO, T_FFN_NORM, T_WGU, T_WD, T_POSEMB, T_CLS = range(11)
 PEEK_DRAFT_LOGITS, PEEK_DRAFT_HIDDEN, PEEK_DRAFT_TOKENS, PEEK_TOKENS = range(4)
 
@@ -38,7 +39,8 @@ class ModelCfg(C.Structure):
 
 
 class PvCfg(C.Structure):
-    _fields_ = [("block", C.c_int32), ("gamma_max", C.c_int32), ("t0", C.c_float), ("rho", C.c_float)]
+    _fields_ = [("block", C.c_int32), ("gamma_max", C.c_int32), ("t0", C.c_float), ("rho", C.c_float),
+                ("halting", C.c_int32)]
 
 
 class PacerError(RuntimeError):

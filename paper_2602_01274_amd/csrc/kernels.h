@@ -521,7 +521,19 @@ __global__ __launch_bounds__(1024) void pick_token_kernel(const float* __restric
 // ------------------------------------------------------------------ pre-verification head + halting test
 // xn: final-norm output of M_B, rows grouped per sequence (b rows each).  alpha_j = softmax(z)[1]
 // = 1/(1+exp(z0-z1)); stop = (mean alpha <= t) with the mean summed in index order in f32.
-struct HaltArgs { int n_seqs; float t[PK_MAXB]; };
+struct HaltArgs { int n_seqs; int rule; float t[PK_MAXB]; };   // rule: 0 mean, 1 any, 2 last
+// the halting test of one block, decided in f32 (al: the block's alpha values in index order)
+__device__ __forceinline__ int halt_decision(const float* al, int b, float t, int rule) {
+  if (rule == 1) {
+    int any = 0;
+    for (int j = 0; j < b; ++j) any |= (al[j] <= t) ? 1 : 0;
+    return any;
+  }
+  if (rule == 2) return (al[b - 1] <= t) ? 1 : 0;
+  float s = 0.f;
+  for (int j = 0; j < b; ++j) s += al[j];
+  return (s / (float)b <= t) ? 1 : 0;
+}
 __global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const float* __restrict__ cls, int d, int b, HaltArgs ha,
                                float* __restrict__ alpha, int* __restrict__ stop) {
   __shared__ float al[32];
@@ -535,9 +547,8 @@ __global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const floa
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    float s = 0.f;
-    for (int j = 0; j < b; ++j) { s += al[j]; alpha[si * b + j] = al[j]; }
-    stop[si] = (s / (float)b <= ha.t[si]) ? 1 : 0;
+    for (int j = 0; j < b; ++j) alpha[si * b + j] = al[j];
+    stop[si] = halt_decision(al, b, ha.t[si], ha.rule);
   }
 }
 

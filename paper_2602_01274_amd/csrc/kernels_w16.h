@@ -37,8 +37,18 @@
 
 typedef unsigned long long u64;
 
-__device__ __forceinline__ float row_scale(const u64* ssq, int m, float inv_dim, float eps) {
-  return 1.0f / sqrtf((float)ssq[m] * SSQ_INV_SCALE * inv_dim + eps);
+// A slot of row sums is SSQ_SUB interleaved accumulators [sub][stride] (blocks spread their atomics
+// over them to cut contention); the sum of the parts is an integer sum, so still order independent.
+#define SSQ_SUB 8
+__device__ __forceinline__ float row_scale(const u64* ssq, int stride, int m, float inv_dim, float eps) {
+  u64 t = 0;
+#pragma unroll
+  for (int i = 0; i < SSQ_SUB; ++i) t += ssq[(size_t)i * stride + m];
+  return 1.0f / sqrtf((float)t * SSQ_INV_SCALE * inv_dim + eps);
+}
+// row r's accumulators of every slot: slot 0 part 0 = v, everything else 0
+__device__ __forceinline__ void ssq_init_row(u64* ssq, int n_slots, int stride, int r, float ss) {
+  for (int i = threadIdx.x; i < n_slots * SSQ_SUB; i += blockDim.x) ssq[(size_t)i * stride + r] = (i == 0) ? (u64)(ss * SSQ_SCALE + 0.5f) : 0ull;
 }
 
 __global__ void pack_weight_kind_kernel(uint4* __restrict__ dst, const uint16_t* __restrict__ src, int N, int K, int kind, int param) {
@@ -78,7 +88,7 @@ __device__ __forceinline__ void store_packed4(_Float16* __restrict__ xp, int MT_
   *reinterpret_cast<half4*>(xp + ((size_t)(kt * MT_total + (m >> 4)) * 64 + (g * 16 + (m & 15))) * 8 + e) = h;
 }
 
-// x = E[token]; operand = f16(x * g); ssq slot 0 = sum x^2.  Block 0 also clears the other slots.
+// x = E[token]; operand = f16(x * g); ssq slot 0 = sum x^2; the row's accumulators of the other slots are cleared.
 // cos/sin of row r's absolute position for the model's rotation frequencies, evaluated in double
 __device__ __forceinline__ void rope_row(float* __restrict__ tab, int r, int pos, int hd, float theta) {
   const int half = hd >> 1;
@@ -97,8 +107,6 @@ __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __re
                                  float* __restrict__ rope, int hd, float theta) {
   __shared__ float red[16];
   const int r = blockIdx.x;
-  if (r == 0)
-    for (int i = threadIdx.x + slot_stride; i < n_slots * slot_stride; i += blockDim.x) ssq[i] = 0ull;
   const int si = find_seq(sr, r);
   const int s = sr.seq[si];
   const int p = sr.pos0[si] + (r - sr.row_off[si]);
@@ -115,7 +123,7 @@ __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __re
     ss += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
   }
   ss = block_sum(ss, red);
-  if (threadIdx.x == 0) ssq[r] = (u64)(ss * SSQ_SCALE + 0.5f);
+  ssq_init_row(ssq, n_slots, slot_stride, r, ss);
 }
 
 // input rows of the pre-verification layer: x = hidden + PosEmb[e]; operand and ssq as above
@@ -125,8 +133,6 @@ __global__ void mb_input_w16_kernel(const float* __restrict__ src, int lds, cons
                                     int hd, float theta) {
   __shared__ float red[16];
   const int r = blockIdx.x;
-  if (r == 0)
-    for (int i = threadIdx.x + slot_stride; i < n_slots * slot_stride; i += blockDim.x) ssq[i] = 0ull;
   const int si = find_seq(sr, r);
   const int rr = r - sr.row_off[si];
   rope_row(rope, r, sr.pos0[si] + rr, hd, theta);
@@ -141,14 +147,14 @@ __global__ void mb_input_w16_kernel(const float* __restrict__ src, int lds, cons
     ss += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
   }
   ss = block_sum(ss, red);
-  if (threadIdx.x == 0) ssq[r] = (u64)(ss * SSQ_SCALE + 0.5f);
+  ssq_init_row(ssq, n_slots, slot_stride, r, ss);
 }
 
 // hidden = x * g * row_scale for R rows (prompt ingestion: feeds M_B's prefix rows)
 __global__ void hidden_rows_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
-                                   float inv_dim, float eps, int d, float* __restrict__ out, int ldo) {
+                                   int ssq_stride, float inv_dim, float eps, int d, float* __restrict__ out, int ldo) {
   const int r = blockIdx.x;
-  const float rs = row_scale(ssq, r, inv_dim, eps);
+  const float rs = row_scale(ssq, ssq_stride, r, inv_dim, eps);
   for (int k = threadIdx.x; k < d; k += blockDim.x) out[(size_t)r * ldo + k] = x[(size_t)r * ldx + k] * g[k] * rs;
 }
 
@@ -158,6 +164,7 @@ struct GemmArgs {
   const u32x4* X;        // packed f16 operand [kt][mt_total][lane]
   int KT, R, mt0, mt_total, nt_begin;
   const u64* ssq_in;     // row sums of squares of the operand's source rows (null: no row scale)
+  int ssq_stride;
   float inv_dim, eps;
   float* out;            // STORE: [rows][ldo] ; RESID: the residual stream x (read, add, write)
   int ldo, rowmap, G1;
@@ -286,7 +293,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
     }
     const bool live = m < ga.R;
     float rs = 1.f;
-    if (ga.ssq_in && live) rs = row_scale(ga.ssq_in, m, ga.inv_dim, ga.eps);
+    if (ga.ssq_in && live) rs = row_scale(ga.ssq_in, ga.ssq_stride, m, ga.inv_dim, ga.eps);
 
     if (EPI == EPI_STORE) {
       const int n = nt * 16 + g4 * 4;
@@ -338,7 +345,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
       }
       sq += __shfl_xor(sq, 16, 64);
       sq += __shfl_xor(sq, 32, 64);
-      if (live && g4 == 0) atomicAdd(ga.ssq_out + m, (u64)(sq * SSQ_SCALE + 0.5f));
+      if (live && g4 == 0) atomicAdd(ga.ssq_out + (size_t)(blockIdx.x % SSQ_SUB) * ga.ssq_stride + m, (u64)(sq * SSQ_SCALE + 0.5f));
     } else if (EPI == EPI_SWIGLU) {
       if (live && g4 < 2) {
         const int f = nt * 8 + g4 * 4;
@@ -639,12 +646,12 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
 // one block per listed sequence: hidden state h = x * g_final * row_scale into the ring, and the token
 // = best of the per-tile candidates the LM-head GEMM left
 __global__ void draft_tail_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
-                                  float inv_dim, float eps, int d, float* __restrict__ hidden, const float* __restrict__ pick_val,
+                                  int ssq_stride, float inv_dim, float eps, int d, float* __restrict__ hidden, const float* __restrict__ pick_val,
                                   const int* __restrict__ pick_idx, int pick_tiles, int* __restrict__ draft_tok, PickArgs pa, int G1) {
   __shared__ float redv[16];
   __shared__ int redi[16];
   const int si = blockIdx.x, s = pa.seq[si], j = pa.j[si];
-  const float rs = row_scale(ssq, si, inv_dim, eps);
+  const float rs = row_scale(ssq, ssq_stride, si, inv_dim, eps);
   float* ho = hidden + (size_t)(s * G1 + j) * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) ho[k] = x[(size_t)si * ldx + k] * g[k] * rs;
   float best = -INFINITY;
@@ -660,7 +667,7 @@ __global__ void draft_tail_kernel(const float* __restrict__ x, int ldx, const fl
 
 // pre-verification head on the un-normalised residual rows: z = (x*g*rs) . cls
 __global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
-                                   float inv_dim, float eps, const float* __restrict__ cls, int d, int b, HaltArgs ha,
+                                   int ssq_stride, float inv_dim, float eps, const float* __restrict__ cls, int d, int b, HaltArgs ha,
                                    float* __restrict__ alpha, int* __restrict__ stop) {
   __shared__ float al[32];
   const int si = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -673,15 +680,14 @@ __global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const f
       z0 += v * cls[k];
       z1 += v * cls[d + k];
     }
-    const float rs = row_scale(ssq, r, inv_dim, eps);
+    const float rs = row_scale(ssq, ssq_stride, r, inv_dim, eps);
     z0 = wave_sum(z0) * rs;
     z1 = wave_sum(z1) * rs;
     if (lane == 0) al[jj] = 1.0f / (1.0f + expf(z0 - z1));
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    float s = 0.f;
-    for (int jj = 0; jj < b; ++jj) { s += al[jj]; alpha[si * b + jj] = al[jj]; }
-    stop[si] = (s / (float)b <= ha.t[si]) ? 1 : 0;
+    for (int jj = 0; jj < b; ++jj) alpha[si * b + jj] = al[jj];
+    stop[si] = halt_decision(al, b, ha.t[si], ha.rule);
   }
 }

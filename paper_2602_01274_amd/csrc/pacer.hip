@@ -136,7 +136,7 @@ size_t carve(pacer_ctx* c, void* base) {
   c->xpA = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
   c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
   c->qp = k.take<_Float16>((size_t)c->max_batch * (c->dmax / 32) * 2 * 512);
-  c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * c->rcap);
+  c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * SSQ_SUB * c->rcap);
   c->att_cnt = k.take<int>((size_t)c->max_batch * c->hmax);
   c->pick_val = k.take<float>((size_t)c->max_batch * (V / 16 + 1));
   c->pick_idx = k.take<int>((size_t)c->max_batch * (V / 16 + 1));
@@ -185,7 +185,7 @@ void prof_end(pacer_ctx* c, double bytes) {
 }
 
 bool is_w16(const Model& m) { return m.cfg.dtype == PACER_BF16; }
-u64* slot(pacer_ctx* c, int s) { return c->ssq + (size_t)s * c->rcap; }
+u64* slot(pacer_ctx* c, int s) { return c->ssq + (size_t)s * SSQ_SUB * c->rcap; }
 
 // ===== bf16-weight path: fused GEMM epilogues, MFMA attention ================================
 
@@ -256,6 +256,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
   base.G1 = c->G1;
   base.rowmap = ROWMAP_ID;
   base.eps = g.rms_eps;
+  base.ssq_stride = c->rcap;
   base.d = d; base.hd = hd; base.n_layers = L; base.max_seq = g.max_seq; base.H = H;
   base.mt_total_out = mt_total;
   for (int l = 0; l < L; ++l) {
@@ -335,6 +336,7 @@ void lm_head_w16(pacer_ctx* c, const Model& m, int tag, int R, float* out, const
   ga.W = static_cast<const u32x4*>(m.head);
   ga.X = reinterpret_cast<const u32x4*>(c->xpA);
   ga.ssq_in = slot(c, 2 * m.cfg.n_layers);
+  ga.ssq_stride = c->rcap;
   ga.inv_dim = 1.0f / m.cfg.d_model;
   ga.out = out; ga.ldo = m.cfg.vocab;
   gemm_w16<EPI_STORE>(c, tag, ga, m.cfg.vocab / 16, m.cfg.d_model);
@@ -419,7 +421,7 @@ void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr
 void preverify_head(pacer_ctx* c, int n, int b, const HaltArgs& ha, float* dev_alpha, int* dev_stop) {
   const Model& mb = c->m[PACER_PREVERIFY];
   if (is_w16(mb))
-    hipLaunchKernelGGL(mb_head_w16_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, mb.final_norm, slot(c, 2), 1.0f / mb.cfg.d_model,
+    hipLaunchKernelGGL(mb_head_w16_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, mb.final_norm, slot(c, 2), c->rcap, 1.0f / mb.cfg.d_model,
                        mb.cfg.rms_eps, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop);
   else
     hipLaunchKernelGGL(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop);
@@ -446,7 +448,7 @@ void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int m
     const PickCfg pick{1, mode, seed, (uint32_t)ctr};
     lm_head_w16(c, md, 1, n, c->ring, sr, ROWMAP_RING, &pick);
     hipLaunchKernelGGL(draft_tail_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
-                       1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->pick_val, c->pick_idx, md.cfg.vocab / 16,
+                       c->rcap, 1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->pick_val, c->pick_idx, md.cfg.vocab / 16,
                        c->draft_tok, pa, c->G1);
   } else {
     hipLaunchKernelGGL((embed_rows_kernel<float>), dim3(n), dim3(256), 0, c->stream, static_cast<const float*>(md.embed), c->tokens,
@@ -486,6 +488,7 @@ int32_t pacer_create(pacer_ctx** out, const pacer_model_cfg* target, const pacer
   if (target->vocab != draft->vocab || target->max_seq != draft->max_seq) return PACER_EINVAL;
   if (pv->block < 1 || pv->gamma_max < pv->block || pv->gamma_max % pv->block || pv->gamma_max > 31) return PACER_EINVAL;
   if (!(pv->t0 >= 0.f) || !(pv->rho > 0.f)) return PACER_EINVAL;
+  if (pv->halting < PACER_HALT_MEAN || pv->halting > PACER_HALT_LAST) return PACER_EINVAL;
   if (max_batch < 1 || max_batch > PACER_MAX_BATCH) return PACER_EINVAL;
   if (target->max_seq <= pv->gamma_max + 2) return PACER_EINVAL;
   pacer_ctx* c = new (std::nothrow) pacer_ctx();
@@ -657,7 +660,7 @@ int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_
     // the draft's hidden states (final-norm output) feed M_B's prefix rows; staged in ao
     if (is_w16(md))
       hipLaunchKernelGGL(hidden_rows_kernel, dim3(R), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
-                         1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->ao, c->dmax);
+                         c->rcap, 1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->ao, c->dmax);
     else
       (void)hipMemcpy2DAsync(c->ao, (size_t)c->dmax * 4, c->xn, (size_t)c->kmax * 4, (size_t)md.cfg.d_model * 4, R, hipMemcpyDeviceToDevice,
                              c->stream);
@@ -734,6 +737,7 @@ int32_t pacer_preverify_block(pacer_ctx* c, const int32_t* seqs, int32_t n, floa
   MbRows mr{};
   HaltArgs ha{};
   sr.n_seqs = ha.n_seqs = n;
+  ha.rule = c->pv.halting;
   for (int i = 0; i < n; ++i) {
     Seq& q = c->seq[seqs[i]];
     sr.seq[i] = seqs[i];

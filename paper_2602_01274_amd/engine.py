@@ -15,7 +15,7 @@ def _dev(t, dtype=None):
 
 class Session:
     def __init__(self, w, target, draft, preverify, max_seq, max_batch=1, t0=None, rho=None,
-                 block=None, gamma_max=None):
+                 block=None, gamma_max=None, halting=B.HALT_MEAN):
         """w: workload description (synth.workload); target/draft/preverify: weight dicts
         (linear weights [out, in]; any device)."""
         assert torch.cuda.is_available(), "the Pacer hot path needs a GPU"
@@ -31,7 +31,7 @@ class Session:
         cfg_t = B.model_cfg(w["target"] | {"n_layers": len(target["layers"])}, max_seq, self.dtype)
         cfg_d = B.model_cfg(w["draft"], max_seq, self.dtype)
         pv = B.PvCfg(self.block, self.gamma_max, t0 if t0 is not None else w["t0"],
-                     rho if rho is not None else w["rho"])
+                     rho if rho is not None else w["rho"], halting)
         self.ctx = B.pacer_create(cfg_t, cfg_d, pv, max_batch, self.stream)
         self.V = w["target"]["vocab"]
         self.dD = w["draft"]["d_model"]

@@ -35,18 +35,19 @@ def _cfgs(B, **over):
 
 def test_create_validates_shapes(B):
     t, d = _cfgs(B)
-    ctx = B.pacer_create(t, d, B.PvCfg(2, 8, 0.5, 1.05), 1, 0)
+    ctx = B.pacer_create(t, d, B.PvCfg(2, 8, 0.5, 1.05, 0), 1, 0)
     assert B.pacer_workspace_bytes(ctx) > 0
     assert B.pacer_kv_bytes(ctx, B.TARGET) == 1 * 2 * 2 * 64 * 128 * 2
     B.pacer_destroy(ctx)
     bad = [
-        (dict(head_dim=32), B.PvCfg(2, 8, 0.5, 1.05), 1),       # unsupported head size
-        (dict(d_model=120), B.PvCfg(2, 8, 0.5, 1.05), 1),       # heads * head_dim != d_model
-        (dict(d_ffn=250), B.PvCfg(2, 8, 0.5, 1.05), 1),         # bf16 needs multiples of 32
-        (dict(), B.PvCfg(3, 8, 0.5, 1.05), 1),                  # gamma_max not a multiple of b
-        (dict(), B.PvCfg(0, 8, 0.5, 1.05), 1),
-        (dict(), B.PvCfg(2, 8, 0.5, 1.05), 17),                 # batch too large
-        (dict(), B.PvCfg(2, 8, 0.5, 0.0), 1),                   # rho must be positive
+        (dict(head_dim=32), B.PvCfg(2, 8, 0.5, 1.05, 0), 1),       # unsupported head size
+        (dict(d_model=120), B.PvCfg(2, 8, 0.5, 1.05, 0), 1),       # heads * head_dim != d_model
+        (dict(d_ffn=250), B.PvCfg(2, 8, 0.5, 1.05, 0), 1),         # bf16 needs multiples of 32
+        (dict(), B.PvCfg(3, 8, 0.5, 1.05, 0), 1),                  # gamma_max not a multiple of b
+        (dict(), B.PvCfg(0, 8, 0.5, 1.05, 0), 1),
+        (dict(), B.PvCfg(2, 8, 0.5, 1.05, 0), 17),                 # batch too large
+        (dict(), B.PvCfg(2, 8, 0.5, 0.0, 0), 1),                   # rho must be positive
+        (dict(), B.PvCfg(2, 8, 0.5, 1.05, 3), 1),                  # unknown halting rule
     ]
     for over, pv, mb in bad:
         t, d = _cfgs(B, **over)
@@ -58,7 +59,7 @@ def test_create_validates_shapes(B):
 def test_calls_out_of_order_and_bad_arguments_fail_on_the_host(B):
     import numpy as np
     t, d = _cfgs(B)
-    ctx = B.pacer_create(t, d, B.PvCfg(2, 8, 0.5, 1.05), 2, 0)
+    ctx = B.pacer_create(t, d, B.PvCfg(2, 8, 0.5, 1.05, 0), 2, 0)
 
     class Fake:            # a host buffer posing as a tensor: bind only records the pointer
         def __init__(self, nbytes):

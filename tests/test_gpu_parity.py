@@ -18,13 +18,13 @@ def _session(w, tgt, drf, mb, max_seq, **kw):
 
 
 def _run(name, n_prompt, n_new, tol_logits, tol_alpha, mode=po.GREEDY, seed=0, gain_jitter=0.1,
-         max_seq=512, step_kw=None, w_over=None, n_layers_target=None):
+         max_seq=512, step_kw=None, w_over=None, n_layers_target=None, halting="mean"):
     w = synth.workload(name)
     w.update(w_over or {})
     tgt, drf, mb = synth.make_pair(w, seed=0, gain_jitter=gain_jitter, n_layers_target=n_layers_target)
     prompt = synth.make_prompt(w["target"]["vocab"], n_prompt, 1).tolist()
-    s = _session(w, tgt, drf, mb, max_seq)
-    o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=seed, max_seq=max_seq, cache=True)
+    s = _session(w, tgt, drf, mb, max_seq, halting={"mean": 0, "any": 1, "last": 2}[halting])
+    o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=seed, max_seq=max_seq, cache=True, halting=halting)
     s.prefill(prompt)
     o.prefill(prompt)
     ck = StepChecker(s, o, tol_logits, tol_alpha, mode=mode, seed=seed)
@@ -62,6 +62,16 @@ def test_tiny_fixed_window_and_autoregressive_modes():
 def test_tiny_forced_stop_patterns():
     _run("tiny", 20, 24, tol_logits=1e-4, tol_alpha=1e-4, step_kw=dict(force_stop=lambda k, a: False))
     _run("tiny", 20, 16, tol_logits=1e-4, tol_alpha=1e-4, step_kw=dict(force_stop=lambda k, a: True))
+
+
+def test_halting_variants_any_and_last():
+    """Sec. 5.2's stricter criteria (any token / last token below t) next to the mean criterion."""
+    g = {}
+    for h in ("mean", "any", "last"):
+        _, gammas, _ = _run("tiny", 20, 32, tol_logits=1e-4, tol_alpha=1e-4, halting=h)
+        g[h] = np.mean(gammas)
+    print("mean window per criterion:", g)
+    assert g["any"] <= g["mean"] + 2      # per block 'any' stops whenever the mean does (step boundaries differ, so only roughly)
 
 
 def test_mid_bf16_greedy_steps_match_oracle():
