@@ -215,7 +215,9 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
       if (many) launch_w16<EPI, TAG, 1, 1, 4, 8>(c, ga, n_tiles);
       else launch_w16<EPI, TAG, 1, 1, 8, 4>(c, ga, n_tiles);
     } else if (ga.R - 16 * mt0 == 17) {               // 17 rows: second row tile reduced to its one column
-      launch_w16<EPI, TAG, 2, 1, 8, 4, 1>(c, ga, n_tiles);
+      if (many && even && n_tiles >= 1024) launch_w16<EPI, TAG, 2, 2, 4, 4, 1>(c, ga, n_tiles);
+      else if (many) launch_w16<EPI, TAG, 2, 1, 4, 4, 1>(c, ga, n_tiles);
+      else launch_w16<EPI, TAG, 2, 1, 8, 4, 1>(c, ga, n_tiles);
     } else {
       if (many && even) launch_w16<EPI, TAG, 2, 2, 4, 4>(c, ga, n_tiles);
       else launch_w16<EPI, TAG, 2, 1, 8, 4>(c, ga, n_tiles);
