@@ -80,12 +80,20 @@ __global__ void pack_weight_kind_kernel(uint4* __restrict__ dst, const uint16_t*
 }
 
 // ------------------------------------------------------------------ producers of layer-0 input
-// 4 consecutive features of row m into the packed f16 operand
+// The f16 operand of a GEMM is stored as two tiles per (k tile, row tile): hi = f16(v) and
+// lo = f16(v - hi).  hi alone carries 11 significant bits; 32 layers of a 4096-wide model turn that
+// rounding into 1.5e-2 of the logit RMS (measured against the float64 oracle and reproduced by rounding
+// the oracle's activations), so the target model's GEMMs multiply both tiles into the same accumulator.
+// Layout: [k tile][row tile][hi|lo][lane][8].
+// 4 consecutive features of row m into the packed operand
 __device__ __forceinline__ void store_packed4(_Float16* __restrict__ xp, int MT_total, int m, int k0, float a, float b, float c, float d) {
   const int kt = k0 >> 5, g = (k0 & 31) >> 3, e = k0 & 7;
   typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-  half4 h = {(_Float16)a, (_Float16)b, (_Float16)c, (_Float16)d};
-  *reinterpret_cast<half4*>(xp + ((size_t)(kt * MT_total + (m >> 4)) * 64 + (g * 16 + (m & 15))) * 8 + e) = h;
+  const half4 h = {(_Float16)a, (_Float16)b, (_Float16)c, (_Float16)d};
+  const half4 l = {(_Float16)(a - (float)h[0]), (_Float16)(b - (float)h[1]), (_Float16)(c - (float)h[2]), (_Float16)(d - (float)h[3])};
+  _Float16* p = xp + ((size_t)(kt * MT_total + (m >> 4)) * 128 + (g * 16 + (m & 15))) * 8 + e;
+  *reinterpret_cast<half4*>(p) = h;
+  *reinterpret_cast<half4*>(p + 512) = l;
 }
 
 // x = E[token]; operand = f16(x * g); ssq slot 0 = sum x^2; the row's accumulators of the other slots are cleared.
@@ -191,9 +199,12 @@ struct GemmArgs {
 // are zeroed in registers.  The second MFMA per step is idle work on an idle unit; the operand traffic
 // is what mattered.
 // 8-wave blocks are held to 128 VGPRs (4 waves per SIMD) so that two blocks fit a CU.
+// TAG 0 = target model: hi and lo operand tiles; TAG 1 = draft / pre-verification layer: hi only
+// (two layers deep, their logits stay at 4e-3 of the RMS without it).
 template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0>
 __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_kernel(const GemmArgs ga) {
   static_assert(!X17 || MT == 2, "the 17-row form uses two row tiles");
+  constexpr int HL = (TAG == 0) ? 2 : 1;             // operand parts multiplied
   __shared__ f32x4 red[WAVES][NT * MT][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nt0 = ga.nt_begin + blockIdx.x * NT;
@@ -209,8 +220,8 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
   const u32x4* wp[NT];
 #pragma unroll
   for (int a = 0; a < NT; ++a) wp[a] = ga.W + (size_t)(nt0 + a) * KT * 64 + lane;
-  const u32x4* xp = ga.X + (size_t)ga.mt0 * 64 + lane;
-  const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 64 + (lane & 48);   // column 0 of row tile mt0+1
+  const u32x4* xp = ga.X + (size_t)ga.mt0 * 128 + lane;
+  const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 128 + (lane & 48);  // column 0 of row tile mt0+1
   const bool col0 = (lane & 15) == 0;
   const int mtt = ga.mt_total;
   // operand columns beyond the last row are never fetched (their accumulator columns are discarded):
@@ -219,9 +230,10 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
 #pragma unroll
   for (int b = 0; b < MT; ++b) col_live[b] = (ga.mt0 + b) * 16 + (lane & 15) < ga.R;
 
-  u32x4 A0[U][NT], A1[U][NT], B0[U][MT], B1[U][MT];
+  constexpr int BW = MT * HL;                          // operand tiles per K step: [row tile][part]
+  u32x4 A0[U][NT], A1[U][NT], B0[U][BW], B1[U][BW];
   const u32x4 zero = {0u, 0u, 0u, 0u};
-  auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][MT], int k0) {
+  auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][BW], int k0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int kt = k0 + u;
@@ -229,34 +241,41 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
 #pragma unroll
         for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + (size_t)kt * 64);
         if (X17) {
-          B[u][0] = xp[(size_t)kt * mtt * 64];
-          B[u][1] = xp17[(size_t)kt * mtt * 64];
+#pragma unroll
+          for (int h = 0; h < HL; ++h) {
+            B[u][h] = xp[((size_t)kt * mtt * 2 + h) * 64];
+            B[u][HL + h] = xp17[((size_t)kt * mtt * 2 + h) * 64];
+          }
         } else {
 #pragma unroll
-          for (int b = 0; b < MT; ++b) {
-            B[u][b] = zero;
-            if (col_live[b]) B[u][b] = xp[((size_t)kt * mtt + b) * 64];
-          }
+          for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int h = 0; h < HL; ++h) {
+              B[u][b * HL + h] = zero;
+              if (col_live[b]) B[u][b * HL + h] = xp[(((size_t)kt * mtt + b) * 2 + h) * 64];
+            }
         }
       } else {
 #pragma unroll
         for (int a = 0; a < NT; ++a) A[u][a] = zero;
 #pragma unroll
-        for (int b = 0; b < MT; ++b) B[u][b] = zero;
+        for (int b = 0; b < BW; ++b) B[u][b] = zero;
       }
     }
   };
-  auto compute = [&](u32x4(&A)[U][NT], u32x4(&B)[U][MT]) {
+  auto compute = [&](u32x4(&A)[U][NT], u32x4(&B)[U][BW]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      half8 bh[MT];
+      half8 bh[BW];
 #pragma unroll
-      for (int b = 0; b < MT; ++b) bh[b] = __builtin_bit_cast(half8, (X17 && b == 1 && !col0) ? zero : B[u][b]);
+      for (int b = 0; b < BW; ++b) bh[b] = __builtin_bit_cast(half8, (X17 && b >= HL && !col0) ? zero : B[u][b]);
 #pragma unroll
       for (int a = 0; a < NT; ++a) {
         const half8 ah = bf16x8_to_f16x8(A[u][a]);
 #pragma unroll
-        for (int b = 0; b < MT; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+          for (int h = 0; h < HL; ++h) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[b * HL + h], acc[a][b], 0, 0, 0);
       }
     }
   };
@@ -386,13 +405,17 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
             const half4 ha = {(_Float16)va[0], (_Float16)va[1], (_Float16)va[2], (_Float16)va[3]};
             const half4 hb = {(_Float16)vb[0], (_Float16)vb[1], (_Float16)vb[2], (_Float16)vb[3]};
             if (part == 0) {
-              // attention operand: [slot][head][kt][2 row tiles][lane][8], lane = 16*(dim%32/8) + row%16
+              // attention operand: [slot][head][kt][2 row tiles][hi|lo][lane][8], lane = 16*(dim%32/8) + row%16
               const int kts = hd >> 5;
               auto qidx = [&](int dim) {
-                return ((((size_t)si * ga.H + h) * kts + (dim >> 5)) * 2 + (rl >> 4)) * 512 + (((dim & 31) >> 3) * 16 + (rl & 15)) * 8 + (dim & 7);
+                return ((((size_t)si * ga.H + h) * kts + (dim >> 5)) * 2 + (rl >> 4)) * 1024 + (((dim & 31) >> 3) * 16 + (rl & 15)) * 8 + (dim & 7);
               };
+              const half4 la = {(_Float16)(va[0] - (float)ha[0]), (_Float16)(va[1] - (float)ha[1]), (_Float16)(va[2] - (float)ha[2]), (_Float16)(va[3] - (float)ha[3])};
+              const half4 lb = {(_Float16)(vb[0] - (float)hb[0]), (_Float16)(vb[1] - (float)hb[1]), (_Float16)(vb[2] - (float)hb[2]), (_Float16)(vb[3] - (float)hb[3])};
               *reinterpret_cast<half4*>(ga.qp + qidx(j0)) = ha;
+              *reinterpret_cast<half4*>(ga.qp + qidx(j0) + 512) = la;
               *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half)) = hb;
+              *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half) + 512) = lb;
             } else {
               _Float16* kr = Kc + (size_t)pos * d + h * hd;
               *reinterpret_cast<half4*>(kr + j0) = ha;
@@ -426,7 +449,8 @@ __device__ __forceinline__ void merge_w(float m1, float m2, float& M, float& w1,
   w2 = (m2 == -INFINITY) ? 0.f : expf(m2 - M);
 }
 
-template <int HD, int MT>
+// QL = 2: the query operand is used as hi + lo (target model), 1: hi only.
+template <int HD, int MT, int QL>
 __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restrict__ qp, const _Float16* __restrict__ kv, int layer,
                                                         int n_layers, int max_seq, int d, SeqRows sr, int kps, int S, int H,
                                                         float* __restrict__ part, int* __restrict__ counters,
@@ -447,12 +471,14 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
   const float scale = 1.0f / sqrtf((float)HD);
   typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
-  half8 q[KTS][MT];
+  half8 q[KTS][MT][QL];
 #pragma unroll
   for (int kt = 0; kt < KTS; ++kt)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-      q[kt][mt] = *reinterpret_cast<const half8*>(qp + ((((size_t)si * H + h) * KTS + kt) * 2 + mt) * 512 + lane * 8);
+#pragma unroll
+      for (int pq = 0; pq < QL; ++pq)
+        q[kt][mt][pq] = *reinterpret_cast<const half8*>(qp + (((((size_t)si * H + h) * KTS + kt) * 2 + mt) * 2 + pq) * 512 + lane * 8);
   f32x4 acc[DTS][MT];
   float mrun[MT], lrun[MT];
 #pragma unroll
@@ -495,7 +521,9 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
       for (int t = 0; t < 2; ++t) {
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kt = 0; kt < KTS; ++kt) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][kt], q[kt][mt], s, 0, 0, 0);
+        for (int kt = 0; kt < KTS; ++kt)
+#pragma unroll
+          for (int pq = 0; pq < QL; ++pq) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][kt], q[kt][mt][pq], s, 0, 0, 0);
         st[t] = s;
       }
       const int pos = pos0 + mt * 16 + j;                // this lane's query row

@@ -133,9 +133,9 @@ size_t carve(pacer_ctx* c, void* base) {
   c->gu = k.take<float>((size_t)c->rcap * 2 * c->fmax);
   c->rope = k.take<float>((size_t)c->rcap * c->hdmax);
   c->part = k.take<float>((size_t)c->rcap * c->hmax * kMaxChunks * (c->hdmax + 2));
-  c->xpA = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
-  c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8);
-  c->qp = k.take<_Float16>((size_t)c->max_batch * (c->dmax / 32) * 2 * 512);
+  c->xpA = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);      // hi and lo tiles
+  c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);
+  c->qp = k.take<_Float16>((size_t)c->max_batch * (c->dmax / 32) * 2 * 1024);
   c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * SSQ_SUB * c->rcap);
   c->att_cnt = k.take<int>((size_t)c->max_batch * c->hmax);
   c->pick_val = k.take<float>((size_t)c->max_batch * (V / 16 + 1));
@@ -211,16 +211,19 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
     const int mt = std::min(2, mt_total - mt0);
     ga.mt0 = mt0;
     if (TAG == 0) prof_begin(c);
+    // K steps in flight per wave: the target model multiplies hi and lo operand tiles, which doubles
+    // the operand registers, so its two-row-tile shapes prefetch less deep
+    constexpr int U1 = TAG == 0 ? 6 : 8, U2 = TAG == 0 ? 2 : 4;
     if (mt == 1) {
-      if (many) launch_w16<EPI, TAG, 1, 1, 4, 8>(c, ga, n_tiles);
+      if (many) launch_w16<EPI, TAG, 1, 1, 4, U1>(c, ga, n_tiles);
       else launch_w16<EPI, TAG, 1, 1, 8, 4>(c, ga, n_tiles);
     } else if (ga.R - 16 * mt0 == 17) {               // 17 rows: second row tile reduced to its one column
-      if (many && even && n_tiles >= 1024) launch_w16<EPI, TAG, 2, 2, 4, 4, 1>(c, ga, n_tiles);
-      else if (many) launch_w16<EPI, TAG, 2, 1, 4, 4, 1>(c, ga, n_tiles);
-      else launch_w16<EPI, TAG, 2, 1, 8, 4, 1>(c, ga, n_tiles);
+      if (many && even && n_tiles >= 1024) launch_w16<EPI, TAG, 2, 2, 4, U2, 1>(c, ga, n_tiles);
+      else if (many) launch_w16<EPI, TAG, 2, 1, 4, U2 + 1, 1>(c, ga, n_tiles);
+      else launch_w16<EPI, TAG, 2, 1, 8, U2, 1>(c, ga, n_tiles);
     } else {
-      if (many && even) launch_w16<EPI, TAG, 2, 2, 4, 4>(c, ga, n_tiles);
-      else launch_w16<EPI, TAG, 2, 1, 8, 4>(c, ga, n_tiles);
+      if (many && even) launch_w16<EPI, TAG, 2, 2, 4, U2>(c, ga, n_tiles);
+      else launch_w16<EPI, TAG, 2, 1, 8, U2>(c, ga, n_tiles);
     }
     if (TAG == 0) prof_end(c, (double)n_tiles * 16.0 * K * 2.0);
   }
@@ -279,9 +282,14 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
     {
       const dim3 grid(S, H, sr.n_seqs);
       const _Float16* kv = static_cast<const _Float16*>(m.kv);
-#define PACER_ATT(HD_, MT_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_>), grid, dim3(512), 0, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->att_cnt, c->xpB, mt_total)
-      if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2); else PACER_ATT(128, 1); }
-      else           { if (max_rows > 16) PACER_ATT(64, 2); else PACER_ATT(64, 1); }
+#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), 0, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->att_cnt, c->xpB, mt_total)
+      if (tag == 0) {
+        if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2, 2); else PACER_ATT(128, 1, 2); }
+        else           { if (max_rows > 16) PACER_ATT(64, 2, 2); else PACER_ATT(64, 1, 2); }
+      } else {
+        if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2, 1); else PACER_ATT(128, 1, 1); }
+        else           { if (max_rows > 16) PACER_ATT(64, 2, 1); else PACER_ATT(64, 1, 1); }
+      }
 #undef PACER_ATT
     }
     {

@@ -139,3 +139,89 @@ def test_batch_mid_bf16_ragged():
     """BASELINE config 5 in miniature: ragged batch, per-sequence beta in [1, 5], prompt lengths
     spread over several attention tiles; 4 sequences x up to 13 verify rows = two 32-row GEMM chunks."""
     _run_batch("mid", [40, 75, 150, 260], [1.0, 2.3, 3.7, 5.0], 6, 2e-2, 2e-2)
+
+
+def _host_copy(x):
+    if isinstance(x, dict):
+        return {k: _host_copy(v) for k, v in x.items()}
+    if isinstance(x, list):
+        return [_host_copy(v) for v in x]
+    return x.cpu()
+
+
+def test_7b_full_depth_against_oracle_and_losslessness():
+    """BASELINE config 3 at full size (32 layers, d 4096, FFN 11008, V 32000; 68M-shaped draft), in
+    the launch configuration bench.py times (weights generated on the device, gamma_max 16, b 4,
+    beta 3).  (i) Two Pacer steps after a short prompt are compared with the oracle row by row
+    (every logit of every verify row).  (ii) Property that holds at any size: greedy speculative
+    decoding emits the tokens of target-only greedy decoding run through the same kernels; a
+    mismatch must sit at a near-tie of the GPU's own deciding logits."""
+    w = synth.workload("7b")
+    w["mode"] = "greedy"
+    tgt, drf, mb = synth.make_pair(w, seed=0, device="cuda")
+    s = _session(w, tgt, drf, mb, 1024)
+    host = (_host_copy(tgt), _host_copy(drf), _host_copy(mb))
+    del tgt, drf, mb
+    torch.cuda.empty_cache()
+    prompt = synth.make_prompt(32000, 12, 1).tolist()
+    o = helpers.build_oracle(w, host[0], host[1], host[2], mode=po.GREEDY, max_seq=64)
+    s.prefill(prompt)
+    o.prefill(prompt)
+    ck = StepChecker(s, o, 2e-2, 2e-2)
+    for _ in range(2):
+        ck.step()
+    print(f"\n[7b full depth] max_err={ck.max_err} flips={ck.flips}")
+    assert s.tokens() == o.tokens
+    # (ii) losslessness on the GPU itself, longer run, 300-token prompt
+    prompt = synth.make_prompt(32000, 300, 2).tolist()
+    s.prefill(prompt)
+    spec, recs = s.generate(40, record=True)
+    s.prefill(prompt)
+    ar, recs_ar = s.generate(40, fixed_gamma=0, record=True)
+    if spec != ar:
+        k = next(i for i in range(40) if spec[i] != ar[i])
+        # the autoregressive run's logits at that token: gap between its top two effective logits
+        r = recs_ar[k]
+        eff = (r["target_logits"][0] + w["beta"] * r["draft_logits"][0]).double().cpu().numpy()
+        top = np.sort(eff)[-2:]
+        print(f"speculative and autoregressive runs part at token {k}: top-2 gap {top[1] - top[0]:.2e}")
+        assert top[1] - top[0] < 2e-2 * np.sqrt(np.mean(eff ** 2))
+    assert any(r["n"] > 0 for r in recs) and any(r["n"] < r["gamma"] for r in recs)
+    s.close()
+
+
+def test_capacity_errors_are_reported_not_faulted():
+    """KV capacity and window limits are host-checked: the calls fail with PACER_EOVERFLOW /
+    PACER_ESTATE and leave the sequence usable."""
+    from paper_2602_01274_amd import binding as B
+    w = synth.workload("tiny")
+    tgt, drf, mb = synth.make_pair(w, seed=0)
+    s = _session(w, tgt, drf, mb, 64)                      # room for 64 positions only
+    with pytest.raises(B.PacerError) as e:
+        s.prefill(list(range(60)))                          # leaves no room for a step
+    assert e.value.code == B.EOVERFLOW
+    s.prefill(list(range(40)))
+    B.pacer_begin_step(s.ctx, 0)
+    for _ in range(w["gamma_max"]):
+        B.pacer_draft_step(s.ctx, [0], B.GREEDY, 0, 0)
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_draft_step(s.ctx, [0], B.GREEDY, 0, 0)      # beyond gamma_max
+    assert e.value.code == B.EOVERFLOW
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_accept_rollback(s.ctx, [0], B.GREEDY, [1.0], 0, 0, s.logits, s.n_acc, s.next_tok)   # not verified yet
+    assert e.value.code == B.ESTATE
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_preverify_block(s.ctx, [0], s.alpha, s.stop)   # 8 new drafts, block is 2
+    assert e.value.code == B.ESTATE
+    B.pacer_verify(s.ctx, [0], None, s.logits)
+    B.pacer_accept_rollback(s.ctx, [0], B.GREEDY, [4.0], 0, 0, s.logits, s.n_acc, s.next_tok)
+    st = B.pacer_get_state(s.ctx, 0)
+    assert st["len"] == 40 + st["n_accepted"] + 1 and 0 <= st["n_accepted"] <= w["gamma_max"]
+    while True:                                             # run into the end of the cache
+        try:
+            s.step()
+        except B.PacerError as e2:
+            assert e2.code == B.EOVERFLOW
+            break
+    assert B.pacer_get_state(s.ctx, 0)["len"] + w["gamma_max"] + 2 > 64
+    s.close()
