@@ -199,19 +199,21 @@ struct GemmArgs {
 // are zeroed in registers.  The second MFMA per step is idle work on an idle unit; the operand traffic
 // is what mattered.
 // 8-wave blocks are held to 128 VGPRs (4 waves per SIMD) so that two blocks fit a CU.
-// TAG 0 = target model: hi and lo operand tiles; TAG 1 = draft / pre-verification layer: hi only
-// (two layers deep, their logits stay at 4e-3 of the RMS without it).
-template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0>
+// HL = operand parts multiplied: 2 = hi and lo tiles (the target model's QKV, gate/up and down GEMMs),
+// 1 = hi only (draft and pre-verification layer: two layers deep, their logits stay at 4e-3 of the RMS).
+template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0, int HL = 1>
 __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_kernel(const GemmArgs ga) {
   static_assert(!X17 || MT == 2, "the 17-row form uses two row tiles");
-  constexpr int HL = (TAG == 0) ? 2 : 1;             // operand parts multiplied
   __shared__ f32x4 red[WAVES][NT * MT][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nt0 = ga.nt_begin + blockIdx.x * NT;
   const int KT = ga.KT;
-  const int per = (KT + WAVES - 1) / WAVES;
-  const int kb = wave * per;
-  const int ke = min(KT, kb + per);
+  // K steps are dealt to the block's waves round-robin (wave w takes w, w+WAVES, ...): at any moment
+  // the waves of a block, and the blocks sharing a CU, read neighbouring operand tiles, which keeps the
+  // operand in the CU's L1 instead of fetching it once per wave from L2
+  const int per = (KT + WAVES - 1) / WAVES;           // steps of this wave: index i -> kt = i*WAVES + wave
+  const int kb = 0;
+  const int ke = (KT - wave + WAVES - 1) / WAVES;
   f32x4 acc[NT][MT];
 #pragma unroll
   for (int a = 0; a < NT; ++a)
@@ -236,8 +238,8 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
   auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][BW], int k0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int kt = k0 + u;
-      if (kt < ke) {
+      const int kt = (k0 + u) * WAVES + wave;
+      if (k0 + u < ke) {
 #pragma unroll
         for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + (size_t)kt * 64);
         if (X17) {

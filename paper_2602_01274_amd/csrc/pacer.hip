@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -189,18 +190,21 @@ u64* slot(pacer_ctx* c, int s) { return c->ssq + (size_t)s * SSQ_SUB * c->rcap; 
 
 // ===== bf16-weight path: fused GEMM epilogues, MFMA attention ================================
 
-template <int EPI, int TAG, int MT, int NT, int WAVES, int U, int X17 = 0>
+template <int EPI, int TAG, int HL, int MT, int NT, int WAVES, int U, int X17 = 0>
 void launch_w16(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
-  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17>), dim3(n_tiles / NT), dim3(WAVES * 64), 0, c->stream, ga);
+  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17, HL>), dim3(n_tiles / NT), dim3(WAVES * 64), 0, c->stream, ga);
 }
 
 // Launches the GEMM over `n_tiles` output tiles starting at ga.nt_begin, in chunks of <= 32 rows.
-// Shape of a launch (measured on MI355X): few output tiles -> 8 waves per block split K so that the
-// chip is covered; many tiles -> 4 waves with a deeper prefetch, which keeps 4 blocks resident per CU so
-// one block's epilogue overlaps the others' streaming; rows beyond 16 -> two output tiles per wave so
-// that the activation operand is fetched once for both.
-// TAG only gives the target model's launches their own kernel symbol; the GEMM profile counts those.
-template <int EPI, int TAG>
+// HL = 2: multiply the operand's hi and lo tiles (target model, all GEMMs but the O projection and the
+// LM head, whose inputs' f16 rounding hardly shows in the logits); HL = 1: hi only.
+// Launch shapes, all measured on MI355X.  HL = 1: >= 512 output tiles -> 4 waves per block, 8 K steps
+// in flight; fewer tiles (O and down projections) -> 8 waves split K, held to 128 VGPRs so two blocks
+// fit a CU.  HL = 2 doubles the operand traffic from L2, which becomes the limiter as rows grow, so wide
+// GEMMs give each wave two output tiles that share the operand registers.  17 rows exactly (full window
+// + committed token): the second row tile is reduced to its one live column (X17).
+// TAG gives the target model's launches their own kernel symbols; the GEMM profile counts those.
+template <int EPI, int TAG, int HL>
 void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
   const int mt_total = (ga.R + 15) / 16;
   ga.mt_total = mt_total;
@@ -209,29 +213,44 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
   const bool even = n_tiles % 2 == 0;
   for (int mt0 = 0; mt0 < mt_total; mt0 += 2) {
     const int mt = std::min(2, mt_total - mt0);
+    const int rows = ga.R - 16 * mt0;
     ga.mt0 = mt0;
     if (TAG == 0) prof_begin(c);
-    // K steps in flight per wave: the target model multiplies hi and lo operand tiles, which doubles
-    // the operand registers, so its two-row-tile shapes prefetch less deep
-    constexpr int U1 = TAG == 0 ? 6 : 8, U2 = TAG == 0 ? 2 : 4;
-    if (mt == 1) {
-      if (many) launch_w16<EPI, TAG, 1, 1, 4, U1>(c, ga, n_tiles);
-      else launch_w16<EPI, TAG, 1, 1, 8, 4>(c, ga, n_tiles);
-    } else if (ga.R - 16 * mt0 == 17) {               // 17 rows: second row tile reduced to its one column
-      if (many && even && n_tiles >= 1024) launch_w16<EPI, TAG, 2, 2, 4, U2, 1>(c, ga, n_tiles);
-      else if (many) launch_w16<EPI, TAG, 2, 1, 4, U2 + 1, 1>(c, ga, n_tiles);
-      else launch_w16<EPI, TAG, 2, 1, 8, U2, 1>(c, ga, n_tiles);
+    if (HL == 1) {
+      if (mt == 1) {
+        if (many) launch_w16<EPI, TAG, 1, 1, 1, 4, 8>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 1, 1, 1, 8, 4>(c, ga, n_tiles);
+      } else if (rows == 17) {
+        if (many && even && n_tiles >= 1024) launch_w16<EPI, TAG, 1, 2, 2, 4, 4, 1>(c, ga, n_tiles);
+        else if (many) launch_w16<EPI, TAG, 1, 2, 1, 4, 4, 1>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 1, 2, 1, 8, 4, 1>(c, ga, n_tiles);
+      } else {
+        if (many && even) launch_w16<EPI, TAG, 1, 2, 2, 4, 4>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 1, 2, 1, 8, 4>(c, ga, n_tiles);
+      }
     } else {
-      if (many && even) launch_w16<EPI, TAG, 2, 2, 4, U2>(c, ga, n_tiles);
-      else launch_w16<EPI, TAG, 2, 1, 8, U2>(c, ga, n_tiles);
+      if (mt == 1) {
+        if (many && even && (n_tiles >= 1024 || rows > 8)) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 2, 1, 1, 8, 4>(c, ga, n_tiles);
+      } else if (rows == 17) {
+        if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2, 1>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 2, 2, 1, 8, 2, 1>(c, ga, n_tiles);
+      } else {
+        if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 2, 2, 1, 8, 2>(c, ga, n_tiles);
+      }
     }
     if (TAG == 0) prof_end(c, (double)n_tiles * 16.0 * K * 2.0);
   }
 }
 template <int EPI>
-void gemm_w16(pacer_ctx* c, int tag, const GemmArgs& ga, int n_tiles, int K) {
-  if (tag == 0) gemm_w16_tag<EPI, 0>(c, ga, n_tiles, K);
-  else gemm_w16_tag<EPI, 1>(c, ga, n_tiles, K);
+void gemm_w16(pacer_ctx* c, int tag, bool hilo, const GemmArgs& ga, int n_tiles, int K) {
+  if (tag == 0) {
+    if (hilo) gemm_w16_tag<EPI, 0, 2>(c, ga, n_tiles, K);
+    else gemm_w16_tag<EPI, 0, 1>(c, ga, n_tiles, K);
+  } else {
+    gemm_w16_tag<EPI, 1, 1>(c, ga, n_tiles, K);
+  }
 }
 
 void rope_table(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
@@ -276,7 +295,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       ga.rope = c->rope;
       ga.layer = l;
       ga.nt_begin = kv_only ? d / 16 : 0;
-      gemm_w16<EPI_QKV>(c, tag, ga, (kv_only ? 2 : 3) * d / 16, d);
+      gemm_w16<EPI_QKV>(c, tag, true, ga, (kv_only ? 2 : 3) * d / 16, d);
     }
     if (kv_only) continue;
     {
@@ -300,7 +319,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       ga.g_next = m.ffn_norm[l];
       ga.xp_out = c->xpA;
       ga.ssq_out = slot(c, 2 * l + 1);
-      gemm_w16<EPI_RESID>(c, tag, ga, d / 16, d);
+      gemm_w16<EPI_RESID>(c, tag, false, ga, d / 16, d);
     }
     {
       GemmArgs ga = base;
@@ -309,7 +328,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       ga.ssq_in = slot(c, 2 * l + 1);
       ga.inv_dim = 1.0f / d;
       ga.xp_out = c->xpB;
-      gemm_w16<EPI_SWIGLU>(c, tag, ga, 2 * F / 16, d);
+      gemm_w16<EPI_SWIGLU>(c, tag, true, ga, 2 * F / 16, d);
     }
     {
       GemmArgs ga = base;
@@ -319,7 +338,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       ga.g_next = (l + 1 < L) ? m.attn_norm[l + 1] : m.final_norm;
       ga.xp_out = c->xpA;
       ga.ssq_out = slot(c, 2 * l + 2);
-      gemm_w16<EPI_RESID>(c, tag, ga, d / 16, F);
+      gemm_w16<EPI_RESID>(c, tag, true, ga, d / 16, F);
     }
   }
 }
@@ -349,7 +368,7 @@ void lm_head_w16(pacer_ctx* c, const Model& m, int tag, int R, float* out, const
   ga.ssq_stride = c->rcap;
   ga.inv_dim = 1.0f / m.cfg.d_model;
   ga.out = out; ga.ldo = m.cfg.vocab;
-  gemm_w16<EPI_STORE>(c, tag, ga, m.cfg.vocab / 16, m.cfg.d_model);
+  gemm_w16<EPI_STORE>(c, tag, false, ga, m.cfg.vocab / 16, m.cfg.d_model);
 }
 
 // ===== f32 path (tiny pair): plain kernels, one per operation ================================
