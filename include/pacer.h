@@ -117,8 +117,10 @@ int32_t pacer_bind(pacer_ctx* ctx, int32_t which, int32_t tensor_id, int32_t lay
 
 /* KV cache of one model for all max_batch sequences, max_batch * n_layers * 2 * max_seq *
  * d_model elements: f32 for a PACER_F32 model ([seq][layer][K|V][position][d_model]), 2-byte
- * IEEE half floats for a PACER_BF16 model ([seq][layer] x { K as [position][d_model], then V
- * transposed as [d_model][max_seq] }; max_seq must be a multiple of 32).  The layout is the
+ * IEEE half floats for a PACER_BF16 model ([seq][layer] x { K, then V }, each stored per head in
+ * the 1 KiB tile order the attention kernel's matrix instructions read: K as
+ * [head][position/16][feature/32][64 lanes][8], V as [head][position/32][feature/16][64 lanes][8];
+ * max_seq must be a multiple of 32).  The layout is the
  * library's own; contents need not be initialised.  pacer_kv_bytes returns the exact size
  * pacer_bind_kv expects. */
 uint64_t pacer_kv_bytes(const pacer_ctx* ctx, int32_t which);

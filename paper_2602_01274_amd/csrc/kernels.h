@@ -9,9 +9,10 @@
 //   packed weights ..... bf16, same tiling: tile (nt, kt) holds outputs nt*16..+15 and inputs
 //                        kt*32..+31, tiles ordered [nt][kt], so a wave that walks along K for
 //                        one output tile reads one contiguous stream.
-//   KV cache ........... [seq][layer][K|V][position][d_model]; f32 for f32 models, IEEE f16 for bf16
-//                        models (same bytes as bf16, 3 more mantissa bits: K after RoPE and V are
-//                        O(1) quantities, so range is no concern and rounding is what matters)
+//   KV cache ........... f32 models: [seq][layer][K|V][position][d_model].  bf16 models: IEEE f16
+//                        (same bytes as bf16, 3 more mantissa bits: K after RoPE and V are O(1)
+//                        quantities, so range is no concern and rounding is what matters), in the
+//                        per-head tile order given in kernels_w16.h
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>

@@ -18,8 +18,13 @@
 //   QKV     Q and K parts: a tile holds 8 rotation pairs of one head: row i<8 <- dim 8t+i, row i+8 <-
 //           dim 8t+i+hd/2 (t = tile within the head); V part plain.  RoPE then stays inside a tile.
 //   GATEUP  tile nt: rows 0..7 <- gate rows 8nt..8nt+7, rows 8..15 <- up rows 8nt..8nt+7.
-// KV cache of a bf16 model, per (sequence, layer): K as [position][d] f16, then V transposed as
-// [d][max_seq] f16, so that both MFMA operands of attention are contiguous 8/16-byte loads.
+// KV cache of a bf16 model, per (sequence, layer): K then V, both f16, both stored per head in the
+// order the attention MFMAs read them, so that every operand load of a wave is one contiguous 1 KiB:
+//   K  [head][position/16][feature/32][lane][8]   lane = 16*((feature%32)/8) + position%16
+//   V  [head][position/32][feature/16][lane][8]   lane = 16*((position%16)/4) + feature%16,
+//                                                 element = position%4 + 4*((position%32)/16)
+// (A row-major [position][d] cache makes a wave's 16 rows of one load sit a power of two apart, which
+// serialises them on one memory channel: measured 4x slower at 550 keys.)
 #pragma once
 #include "kernels.h"
 
@@ -167,6 +172,15 @@ __global__ void hidden_rows_kernel(const float* __restrict__ x, int ldx, const f
 }
 
 // ------------------------------------------------------------------ weight-streaming small-M GEMM, fused epilogues
+// element offsets inside one (sequence, layer) K or V block of the f16 cache (layout in the file header)
+__device__ __forceinline__ size_t kcache_index(int h, int hd, int max_seq, int pos, int f) {
+  return (((size_t)h * (max_seq >> 4) + (pos >> 4)) * (hd >> 5) + (f >> 5)) * 512 + ((((f & 31) >> 3) << 4) + (pos & 15)) * 8 + (f & 7);
+}
+__device__ __forceinline__ size_t vcache_index(int h, int hd, int max_seq, int pos, int f) {
+  const int p = pos & 31;
+  return (((size_t)h * (max_seq >> 5) + (pos >> 5)) * (hd >> 4) + (f >> 4)) * 512 + ((((p & 15) >> 2) << 4) + (f & 15)) * 8 + (p & 3) + ((p >> 4) << 2);
+}
+
 struct GemmArgs {
   const u32x4* W;        // packed weights
   const u32x4* X;        // packed f16 operand [kt][mt_total][lane]
@@ -419,15 +433,15 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
               *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half)) = hb;
               *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half) + 512) = lb;
             } else {
-              _Float16* kr = Kc + (size_t)pos * d + h * hd;
-              *reinterpret_cast<half4*>(kr + j0) = ha;
-              *reinterpret_cast<half4*>(kr + j0 + half) = hb;
+              *reinterpret_cast<half4*>(Kc + kcache_index(h, hd, ga.max_seq, pos, j0)) = ha;
+              *reinterpret_cast<half4*>(Kc + kcache_index(h, hd, ga.max_seq, pos, j0 + half)) = hb;
             }
           }
         } else {
           const int c0 = (nt - 2 * tiles_d) * 16 + g4 * 4;       // V feature index
+          const int h = c0 / hd, f0 = c0 - h * hd;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) Vt[(size_t)(c0 + r) * ga.max_seq + pos] = (_Float16)(s[r] * rs);
+          for (int r = 0; r < 4; ++r) Vt[vcache_index(h, hd, ga.max_seq, pos, f0 + r)] = (_Float16)(s[r] * rs);
         }
       }
     }
@@ -468,8 +482,8 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
   const int n_split = (n_keys + kps - 1) / kps;
   if (split >= n_split) return;
   const int ks_begin = split * kps, ks_end = min(n_keys, ks_begin + kps);
-  const _Float16* Kc = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2) * (size_t)max_seq * d + h * HD;
-  const _Float16* Vt = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2 + 1) * (size_t)max_seq * d + (size_t)h * HD * max_seq;
+  const _Float16* Kc = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2) * (size_t)max_seq * d + (size_t)h * HD * max_seq;
+  const _Float16* Vt = Kc + (size_t)max_seq * d;
   const float scale = 1.0f / sqrtf((float)HD);
   typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
@@ -493,26 +507,24 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
 
   // K tiles (two 16-key tiles x KTS feature groups) and V^T fragments of one 32-key group
   auto load_kv = [&](int kk, half8(&ka)[2][KTS], half8(&va)[DTS]) {
+    const _Float16* kt0 = Kc + (size_t)(kk >> 4) * (KTS * 512) + lane * 8;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int key = min(kk + 16 * t + j, n_keys - 1);
-      const _Float16* kr = Kc + (size_t)key * d + 8 * g;
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int kt = 0; kt < KTS; ++kt) ka[t][kt] = *reinterpret_cast<const half8*>(kr + kt * 32);
-    }
+      for (int kt = 0; kt < KTS; ++kt) ka[t][kt] = *reinterpret_cast<const half8*>(kt0 + (t * KTS + kt) * 512);
+    const _Float16* vg = Vt + (size_t)(kk >> 5) * (DTS * 512) + lane * 8;
     const bool tail = kk + 32 > n_keys;
 #pragma unroll
     for (int dt = 0; dt < DTS; ++dt) {
-      const _Float16* vr = Vt + (size_t)(dt * 16 + j) * max_seq + kk + 4 * g;
-      half4 lo = *reinterpret_cast<const half4*>(vr), hi = *reinterpret_cast<const half4*>(vr + 16);
-      if (tail) {
+      half8 v = *reinterpret_cast<const half8*>(vg + dt * 512);
+      if (tail) {   // slots of positions not written yet may hold anything, NaN included
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          if (kk + 4 * g + e >= n_keys) lo[e] = (_Float16)0.f;
-          if (kk + 16 + 4 * g + e >= n_keys) hi[e] = (_Float16)0.f;
+          if (kk + 4 * g + e >= n_keys) v[e] = (_Float16)0.f;
+          if (kk + 16 + 4 * g + e >= n_keys) v[4 + e] = (_Float16)0.f;
         }
       }
-      va[dt] = half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      va[dt] = v;
     }
   };
   auto step = [&](int kk, half8(&ka)[2][KTS], half8(&va)[DTS]) {
