@@ -2,13 +2,15 @@
 //
 // Data layout conventions used by every kernel in this file
 //   activations ........ f32 [rows][width], row major
-//   packed activations . f16 operand tiles for the MFMA GEMM: tile (kt, mt) holds rows
-//                        mt*16..+15 and features kt*32..+31; inside a tile lane l = 16*g + j
-//                        owns row j and the 8 features 8*g..8*g+7 (16 bytes), so one wave
-//                        loads a tile with a single fully coalesced 1 KiB read.
-//   packed weights ..... bf16, same tiling: tile (nt, kt) holds outputs nt*16..+15 and inputs
-//                        kt*32..+31, tiles ordered [nt][kt], so a wave that walks along K for
-//                        one output tile reads one contiguous stream.
+//   packed activations . (bf16 models) f16 operand tiles for the MFMA GEMM: tile (kt, mt) holds rows
+//                        mt*16..+15 and features kt*32..+31 as 16 columns of 64 bytes: row j's 32
+//                        features are contiguous, MFMA lane 16*g + j reads bytes 64*j + 16*g..+15.
+//                        Rows are what a launch has few of, so a GEMM wave fetches only the 64-byte
+//                        columns of live rows: operand traffic is proportional to the row count.
+//   packed weights ..... bf16, tile (nt, kt) holds outputs nt*16..+15 and inputs kt*32..+31 in MFMA
+//                        lane order (lane 16*g + i = output i, inputs 8*g..+7), tiles ordered
+//                        [nt][kt], so a wave that walks along K for one output tile reads one
+//                        contiguous stream with one 1 KiB load per step.
 //   KV cache ........... f32 models: [seq][layer][K|V][position][d_model].  bf16 models: IEEE f16
 //                        (same bytes as bf16, 3 more mantissa bits: K after RoPE and V are O(1)
 //                        quantities, so range is no concern and rounding is what matters), in the
@@ -156,31 +158,15 @@ __global__ void mb_input_kernel(const float* __restrict__ src, int lds, const fl
   for (int k = threadIdx.x; k < d; k += blockDim.x) x[(size_t)r * ldx + k] = h[k] + e[k];
 }
 
-// ------------------------------------------------------------------ packing helpers
-// store 8 consecutive features k0..k0+7 of row m into the packed f16 operand
-__device__ __forceinline__ void store_packed8(_Float16* __restrict__ xp, int MT_total, int m, int k0, const float* v) {
-  const int kt = k0 >> 5, g = (k0 & 31) >> 3;
-  const int mt = m >> 4, j = m & 15;
-  half8 h;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) h[i] = (_Float16)v[i];
-  *reinterpret_cast<half8*>(xp + ((size_t)(kt * MT_total + mt) * 64 + (g * 16 + j)) * 8) = h;
-}
-
-// RMSNorm of R rows; writes the normalised rows as f32 (xn), optionally scattered copies for the
-// draft's hidden-state ring (hid_out row = seq*G1 + draft index), optionally the packed f16 operand
-// (then the grid covers MT_total*16 rows and rows >= R are zero filled).
+// ------------------------------------------------------------------ f32 path: norm and activation
+// RMSNorm of R rows (one block each); writes the normalised rows as f32 (xn) and optionally scattered
+// copies for the draft's hidden-state ring (hid_out row = seq*G1 + draft index).
 __global__ void rmsnorm_pack_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, float eps, int R, int d,
-                                    float* __restrict__ xn, int ldxn, _Float16* __restrict__ xp, int MT_total,
-                                    float* __restrict__ hid_out, int G1, SeqRows sr) {
+                                    float* __restrict__ xn, int ldxn, float* __restrict__ hid_out, int G1, SeqRows sr) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   const int ng = d >> 3;
-  if (r >= R) {
-    const float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int kg = threadIdx.x; kg < ng; kg += blockDim.x) store_packed8(xp, MT_total, r, kg * 8, z);
-    return;
-  }
+  if (r >= R) return;
   const float* xr = x + (size_t)r * ldx;
   float ss = 0.f;
   for (int k = threadIdx.x; k < d; k += blockDim.x) { const float v = xr[k]; ss += v * v; }
@@ -202,31 +188,19 @@ __global__ void rmsnorm_pack_kernel(const float* __restrict__ x, int ldx, const 
 #pragma unroll
       for (int i = 0; i < 8; ++i) ho[kg * 8 + i] = v[i];
     }
-    if (xp) store_packed8(xp, MT_total, r, kg * 8, v);
   }
 }
 
-// SwiGLU: act = silu(gate) * up for gu = [gate | up] rows; f32 out + optional packed operand
-__global__ void swiglu_pack_kernel(const float* __restrict__ gu, int ldg, int R, int F, float* __restrict__ act, int lda,
-                                   _Float16* __restrict__ xp, int MT_total) {
+// SwiGLU: act = silu(gate) * up for gu = [gate | up] rows, f32
+__global__ void swiglu_pack_kernel(const float* __restrict__ gu, int ldg, int R, int F, float* __restrict__ act, int lda) {
   const int r = blockIdx.y;
   const int kg = blockIdx.x * blockDim.x + threadIdx.x;
-  if (kg >= (F >> 3)) return;
-  float v[8];
+  if (kg >= (F >> 3) || r >= R) return;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    if (r < R) {
-      const float gt = gu[(size_t)r * ldg + kg * 8 + i], up = gu[(size_t)r * ldg + F + kg * 8 + i];
-      v[i] = gt / (1.0f + expf(-gt)) * up;
-    } else {
-      v[i] = 0.f;
-    }
+    const float gt = gu[(size_t)r * ldg + kg * 8 + i], up = gu[(size_t)r * ldg + F + kg * 8 + i];
+    act[(size_t)r * lda + kg * 8 + i] = gt / (1.0f + expf(-gt)) * up;
   }
-  if (r < R) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) act[(size_t)r * lda + kg * 8 + i] = v[i];
-  }
-  if (xp) store_packed8(xp, MT_total, r, kg * 8, v);
 }
 
 // ------------------------------------------------------------------ output row mapping of a GEMM

@@ -89,14 +89,17 @@ __global__ void pack_weight_kind_kernel(uint4* __restrict__ dst, const uint16_t*
 // lo = f16(v - hi).  hi alone carries 11 significant bits; 32 layers of a 4096-wide model turn that
 // rounding into 1.5e-2 of the logit RMS (measured against the float64 oracle and reproduced by rounding
 // the oracle's activations), so the target model's GEMMs multiply both tiles into the same accumulator.
-// Layout: [k tile][row tile][hi|lo][lane][8].
+// Layout: [k tile][row tile][hi|lo][row in tile][32 features]: inside a 1 KiB tile a row is 64
+// contiguous bytes, and MFMA lane 16*g + j reads bytes 64*j + 16*g..+15 of it.  (Storing the tile in
+// lane order instead makes a launch with 9..16 rows touch all eight 128-byte lines of every tile and
+// measured 5 to 10 % slower GEMMs; this way the lines touched follow the row count.)
 // 4 consecutive features of row m into the packed operand
 __device__ __forceinline__ void store_packed4(_Float16* __restrict__ xp, int MT_total, int m, int k0, float a, float b, float c, float d) {
   const int kt = k0 >> 5, g = (k0 & 31) >> 3, e = k0 & 7;
   typedef _Float16 half4 __attribute__((ext_vector_type(4)));
   const half4 h = {(_Float16)a, (_Float16)b, (_Float16)c, (_Float16)d};
   const half4 l = {(_Float16)(a - (float)h[0]), (_Float16)(b - (float)h[1]), (_Float16)(c - (float)h[2]), (_Float16)(d - (float)h[3])};
-  _Float16* p = xp + ((size_t)(kt * MT_total + (m >> 4)) * 128 + (g * 16 + (m & 15))) * 8 + e;
+  _Float16* p = xp + ((size_t)(kt * MT_total + (m >> 4)) * 128 + ((m & 15) * 4 + g)) * 8 + e;
   *reinterpret_cast<half4*>(p) = h;
   *reinterpret_cast<half4*>(p + 512) = l;
 }
@@ -236,8 +239,8 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
   const u32x4* wp[NT];
 #pragma unroll
   for (int a = 0; a < NT; ++a) wp[a] = ga.W + (size_t)(nt0 + a) * KT * 64 + lane;
-  const u32x4* xp = ga.X + (size_t)ga.mt0 * 128 + lane;
-  const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 128 + (lane & 48);  // column 0 of row tile mt0+1
+  const u32x4* xp = ga.X + (size_t)ga.mt0 * 128 + (lane & 15) * 4 + (lane >> 4);
+  const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 128 + (lane >> 4);  // column 0 of row tile mt0+1
   const bool col0 = (lane & 15) == 0;
   const int mtt = ga.mt_total;
   // operand columns beyond the last row are never fetched (their accumulator columns are discarded):

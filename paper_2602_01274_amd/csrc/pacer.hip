@@ -218,7 +218,10 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
     if (TAG == 0) prof_begin(c);
     if (HL == 1) {
       if (mt == 1) {
-        if (many) launch_w16<EPI, TAG, 1, 1, 1, 4, 8>(c, ga, n_tiles);
+        // K <= 1024: 4 waves with at most 8 K steps each, all in flight at once (a prefetch depth above
+        // the wave's step count measured slower than one that matches it)
+        if (ga.KT <= 24) launch_w16<EPI, TAG, 1, 1, 1, 4, 6>(c, ga, n_tiles);
+        else if (many) launch_w16<EPI, TAG, 1, 1, 1, 4, 8>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 1, 1, 1, 8, 4>(c, ga, n_tiles);
       } else if (rows == 17) {
         if (many && even && n_tiles >= 1024) launch_w16<EPI, TAG, 1, 2, 2, 4, 4, 1>(c, ga, n_tiles);
@@ -230,7 +233,9 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
       }
     } else {
       if (mt == 1) {
-        if (many && even && (n_tiles >= 1024 || rows > 8)) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
+        // QKV (768 tiles at d 4096): four output tiles per wave share one fetch of the operand
+        if (EPI == EPI_QKV && many && n_tiles % 4 == 0 && n_tiles < 1024 && rows > 8) launch_w16<EPI, TAG, 2, 1, 4, 8, 1>(c, ga, n_tiles);
+        else if (many && even && (n_tiles >= 1024 || rows > 8)) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 1, 1, 8, 3>(c, ga, n_tiles);
       } else if (rows == 17) {
         if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2, 1>(c, ga, n_tiles);
@@ -381,7 +386,7 @@ void gemm_f32(pacer_ctx* c, const void* W, const float* act, int lda, float* out
 
 void rmsnorm_f32(pacer_ctx* c, const Model& m, const float* g, int R, float* hid_out, const SeqRows& sr) {
   hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(R), dim3(256), 0, c->stream, c->x, c->dmax, g, m.cfg.rms_eps, R, m.cfg.d_model, c->xn,
-                     c->kmax, (_Float16*)nullptr, 0, hid_out, c->G1, sr);
+                     c->kmax, hid_out, c->G1, sr);
 }
 
 void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool kv_only, float* hid_out) {
@@ -407,8 +412,7 @@ void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool
     gemm_f32(c, m.wo[l], c->ao, c->dmax, c->x, c->dmax, R, d, d, 1, none, ROWMAP_ID);
     rmsnorm_f32(c, m, m.ffn_norm[l], R, nullptr, sr);
     gemm_f32(c, m.wgu[l], c->xn, c->kmax, c->gu, 2 * c->fmax, R, 2 * F, d, 0, none, ROWMAP_ID);
-    hipLaunchKernelGGL(swiglu_pack_kernel, dim3((F / 8 + 255) / 256, R), dim3(256), 0, c->stream, c->gu, 2 * c->fmax, R, F, c->xn, c->kmax,
-                       (_Float16*)nullptr, 0);
+    hipLaunchKernelGGL(swiglu_pack_kernel, dim3((F / 8 + 255) / 256, R), dim3(256), 0, c->stream, c->gu, 2 * c->fmax, R, F, c->xn, c->kmax);
     gemm_f32(c, m.wd[l], c->xn, c->kmax, c->x, c->dmax, R, d, F, 1, none, ROWMAP_ID);
   }
   if (!kv_only) rmsnorm_f32(c, m, m.final_norm, R, hid_out, sr);
