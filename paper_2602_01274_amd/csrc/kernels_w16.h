@@ -211,10 +211,10 @@ struct GemmArgs {
 };
 
 // X17 = 1 (with MT = 2): the launch covers exactly 17 rows (a full draft window plus the committed
-// token).  Only column 0 of the second row tile exists, so instead of fetching that whole 1 KiB operand
-// tile each lane reads the 16 bytes of column 0 (a 64-byte broadcast per K step) and the other columns
-// are zeroed in registers.  The second MFMA per step is idle work on an idle unit; the operand traffic
-// is what mattered.
+// token).  Only row 16 of the second row tile exists, so its hi and lo parts share ONE extra MFMA: operand
+// column 0 = hi of row 16, column 1 = lo of row 16, the other columns zero in registers, and the epilogue
+// adds accumulator columns 0 and 1.  That is three MFMAs and 17 fetched operand rows per K step instead
+// of four and 32.
 // 8-wave blocks are held to 128 VGPRs (4 waves per SIMD) so that two blocks fit a CU.
 // HL = operand parts multiplied: 2 = hi and lo tiles (the target model's QKV, gate/up and down GEMMs),
 // 1 = hi only (draft and pre-verification layer: two layers deep, their logits stay at 4e-3 of the RMS).
@@ -240,8 +240,9 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
 #pragma unroll
   for (int a = 0; a < NT; ++a) wp[a] = ga.W + (size_t)(nt0 + a) * KT * 64 + lane;
   const u32x4* xp = ga.X + (size_t)ga.mt0 * 128 + (lane & 15) * 4 + (lane >> 4);
-  const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 128 + (lane >> 4);  // column 0 of row tile mt0+1
-  const bool col0 = (lane & 15) == 0;
+  // row 0 of row tile mt0+1: its hi part for even operand columns, its lo part for odd ones
+  const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 128 + (lane >> 4) + (HL == 2 ? (lane & 1) * 64 : 0);
+  const bool x17_live = (lane & 15) < HL;
   const int mtt = ga.mt_total;
   // operand columns beyond the last row are never fetched (their accumulator columns are discarded):
   // the operand traffic scales with the number of rows instead of with whole 16-row tiles
@@ -249,7 +250,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
 #pragma unroll
   for (int b = 0; b < MT; ++b) col_live[b] = (ga.mt0 + b) * 16 + (lane & 15) < ga.R;
 
-  constexpr int BW = MT * HL;                          // operand tiles per K step: [row tile][part]
+  constexpr int BW = X17 ? HL + 1 : MT * HL;           // operand tiles per K step: [row tile][part]
   u32x4 A0[U][NT], A1[U][NT], B0[U][BW], B1[U][BW];
   const u32x4 zero = {0u, 0u, 0u, 0u};
   auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][BW], int k0) {
@@ -261,10 +262,8 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
         for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + (size_t)kt * 64);
         if (X17) {
 #pragma unroll
-          for (int h = 0; h < HL; ++h) {
-            B[u][h] = xp[((size_t)kt * mtt * 2 + h) * 64];
-            B[u][HL + h] = xp17[((size_t)kt * mtt * 2 + h) * 64];
-          }
+          for (int h = 0; h < HL; ++h) B[u][h] = xp[((size_t)kt * mtt * 2 + h) * 64];
+          B[u][HL] = xp17[(size_t)kt * mtt * 2 * 64];
         } else {
 #pragma unroll
           for (int b = 0; b < MT; ++b)
@@ -287,14 +286,17 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
     for (int u = 0; u < U; ++u) {
       half8 bh[BW];
 #pragma unroll
-      for (int b = 0; b < BW; ++b) bh[b] = __builtin_bit_cast(half8, (X17 && b >= HL && !col0) ? zero : B[u][b]);
+      for (int b = 0; b < BW; ++b) bh[b] = __builtin_bit_cast(half8, (X17 && b == HL && !x17_live) ? zero : B[u][b]);
 #pragma unroll
       for (int a = 0; a < NT; ++a) {
         const half8 ah = bf16x8_to_f16x8(A[u][a]);
 #pragma unroll
         for (int b = 0; b < MT; ++b)
 #pragma unroll
-          for (int h = 0; h < HL; ++h) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[b * HL + h], acc[a][b], 0, 0, 0);
+          for (int h = 0; h < HL; ++h) {
+            if (X17 && b == 1 && h > 0) continue;
+            acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[(X17 && b == 1) ? HL : b * HL + h], acc[a][b], 0, 0, 0);
+          }
       }
     }
   };
@@ -328,6 +330,14 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
       s2 = red[0][ab][l + 32];
 #pragma unroll
       for (int w = 1; w < WAVES; ++w) s2 += red[w][ab][l + 32];
+    }
+    if (X17 && HL == 2 && b == 1 && (l & 15) == 0) {   // row 16: hi product in column 0, lo product in column 1
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) s += red[w][ab][l + 1];
+      if (paired && g4 < 2) {
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) s2 += red[w][ab][l + 33];
+      }
     }
     const bool live = m < ga.R;
     float rs = 1.f;

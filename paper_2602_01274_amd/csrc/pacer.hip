@@ -238,7 +238,8 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
         else if (many && even && (n_tiles >= 1024 || rows > 8)) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 1, 1, 8, 3>(c, ga, n_tiles);
       } else if (rows == 17) {
-        if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2, 1>(c, ga, n_tiles);
+        if (EPI == EPI_QKV && many && n_tiles % 4 == 0 && n_tiles < 1024) launch_w16<EPI, TAG, 2, 2, 4, 8, 1, 1>(c, ga, n_tiles);
+        else if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2, 1>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 2, 1, 8, 2, 1>(c, ga, n_tiles);
       } else {
         if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2>(c, ga, n_tiles);
