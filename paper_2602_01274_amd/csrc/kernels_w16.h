@@ -210,6 +210,134 @@ struct GemmArgs {
   SeqRows sr;
 };
 
+// Epilogue of one accumulator lane, shared by the GEMM kernels.  Lane l of a 16x16 result tile holds
+// tile rows (outputs) 4*(l/16)..+3 of activation row m; s2 holds the same for the partner outputs i+8
+// (paired weight layouts: rotation pairs of QKV, gate/up of SwiGLU; lanes with l/16 < 2).  All 64 lanes
+// of the tile call this together (the row reductions use wave shuffles).
+template <int EPI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& ga, int nt, int m, int l, f32x4 s, f32x4 s2) {
+  const int g4 = l >> 4;
+  const bool live = m < ga.R;
+  float rs = 1.f;
+  if (ga.ssq_in && live) rs = row_scale(ga.ssq_in, ga.ssq_stride, m, ga.inv_dim, ga.eps);
+
+  if (EPI == EPI_STORE) {
+    const int n = nt * 16 + g4 * 4;
+    const f32x4 lg = s * rs;
+    if (live) {
+      float* o = ga.out + (size_t)map_row(ga.sr, ga.rowmap, ga.G1, m) * ga.ldo + n;
+      *reinterpret_cast<f32x4*>(o) = lg;
+    }
+    if (ga.pick_val) {
+      // token choice, first stage: best of this tile's 16 vocabulary entries for row m
+      // (argmax of the logits, or of logits + Gumbel noise; lowest id wins ties)
+      float best = -INFINITY;
+      int bi = 0x7fffffff;
+      if (live) {
+        float g4n[4] = {0.f, 0.f, 0.f, 0.f};
+        if (ga.pick_mode) {
+          const int si = find_seq(ga.sr, m);
+          const int jrow = ga.sr.pos0[si] + (m - ga.sr.row_off[si]) - (ga.sr.len[si] - 1);
+          const uint4 bits = vocab_bits(ga.pick_seed, ga.sr.seq[si], ga.pick_step, (uint32_t)(jrow + 1), PURPOSE_DRAFT, (uint32_t)(n >> 2));
+          g4n[0] = gumbel(u01(bits.x)); g4n[1] = gumbel(u01(bits.y)); g4n[2] = gumbel(u01(bits.z)); g4n[3] = gumbel(u01(bits.w));
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float v = lg[r] + g4n[r];
+          if (v > best) { best = v; bi = n + r; }
+        }
+      }
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const float ov = __shfl_xor(best, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+      }
+      if (live && g4 == 0) {
+        ga.pick_val[(size_t)m * ga.pick_tiles + nt] = best;
+        ga.pick_idx[(size_t)m * ga.pick_tiles + nt] = bi;
+      }
+    }
+  } else if (EPI == EPI_RESID) {
+    float sq = 0.f;
+    if (live) {
+      const int n = nt * 16 + g4 * 4;
+      float* o = ga.out + (size_t)m * ga.ldo + n;
+      const f32x4 xn = *reinterpret_cast<const f32x4*>(o) + s;
+      *reinterpret_cast<f32x4*>(o) = xn;
+      const float4 gn = *reinterpret_cast<const float4*>(ga.g_next + n);
+      store_packed4(ga.xp_out, ga.mt_total_out, m, n, xn[0] * gn.x, xn[1] * gn.y, xn[2] * gn.z, xn[3] * gn.w);
+      sq = xn[0] * xn[0] + xn[1] * xn[1] + xn[2] * xn[2] + xn[3] * xn[3];
+    }
+    sq += __shfl_xor(sq, 16, 64);
+    sq += __shfl_xor(sq, 32, 64);
+    if (live && g4 == 0) atomicAdd(ga.ssq_out + (size_t)(blockIdx.x % SSQ_SUB) * ga.ssq_stride + m, (u64)(sq * SSQ_SCALE + 0.5f));
+  } else if (EPI == EPI_SWIGLU) {
+    if (live && g4 < 2) {
+      const int f = nt * 8 + g4 * 4;
+      float v[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float gt = s[r] * rs, up = s2[r] * rs;
+        v[r] = gt / (1.0f + expf(-gt)) * up;
+      }
+      store_packed4(ga.xp_out, ga.mt_total_out, m, f, v[0], v[1], v[2], v[3]);
+    }
+  } else {  // EPI_QKV
+    if (live) {
+      const int d = ga.d, hd = ga.hd, half = hd >> 1;
+      const int si = find_seq(ga.sr, m);
+      const int rl = m - ga.sr.row_off[si];
+      const int pos = ga.sr.pos0[si] + rl;
+      _Float16* Kc = ga.kv + (((size_t)ga.sr.seq[si] * ga.n_layers + ga.layer) * 2) * (size_t)ga.max_seq * d;
+      _Float16* Vt = Kc + (size_t)ga.max_seq * d;
+      const int tiles_d = d >> 4;
+      typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+      if (nt < 2 * tiles_d) {
+        if (g4 < 2) {
+          const int part = nt / tiles_d;
+          const int tq = nt - part * tiles_d;
+          const int tph = hd >> 4;
+          const int h = tq / tph, tt = tq % tph;
+          const int j0 = 8 * tt + 4 * g4;                   // rotation pairs j0..j0+3
+          const float* tb = ga.rope + ((size_t)m * half + j0) * 2;
+          float va[4], vb[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float cs = tb[2 * r], sn = tb[2 * r + 1];
+            const float x0 = s[r] * rs, x1 = s2[r] * rs;
+            va[r] = x0 * cs - x1 * sn;
+            vb[r] = x1 * cs + x0 * sn;
+          }
+          const half4 ha = {(_Float16)va[0], (_Float16)va[1], (_Float16)va[2], (_Float16)va[3]};
+          const half4 hb = {(_Float16)vb[0], (_Float16)vb[1], (_Float16)vb[2], (_Float16)vb[3]};
+          if (part == 0) {
+            // attention operand: [slot][head][kt][2 row tiles][hi|lo][lane][8], lane = 16*(dim%32/8) + row%16
+            const int kts = hd >> 5;
+            auto qidx = [&](int dim) {
+              return ((((size_t)si * ga.H + h) * kts + (dim >> 5)) * 2 + (rl >> 4)) * 1024 + (((dim & 31) >> 3) * 16 + (rl & 15)) * 8 + (dim & 7);
+            };
+            const half4 la = {(_Float16)(va[0] - (float)ha[0]), (_Float16)(va[1] - (float)ha[1]), (_Float16)(va[2] - (float)ha[2]), (_Float16)(va[3] - (float)ha[3])};
+            const half4 lb = {(_Float16)(vb[0] - (float)hb[0]), (_Float16)(vb[1] - (float)hb[1]), (_Float16)(vb[2] - (float)hb[2]), (_Float16)(vb[3] - (float)hb[3])};
+            *reinterpret_cast<half4*>(ga.qp + qidx(j0)) = ha;
+            *reinterpret_cast<half4*>(ga.qp + qidx(j0) + 512) = la;
+            *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half)) = hb;
+            *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half) + 512) = lb;
+          } else {
+            *reinterpret_cast<half4*>(Kc + kcache_index(h, hd, ga.max_seq, pos, j0)) = ha;
+            *reinterpret_cast<half4*>(Kc + kcache_index(h, hd, ga.max_seq, pos, j0 + half)) = hb;
+          }
+        }
+      } else {
+        const int c0 = (nt - 2 * tiles_d) * 16 + g4 * 4;       // V feature index
+        const int h = c0 / hd, f0 = c0 - h * hd;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Vt[vcache_index(h, hd, ga.max_seq, pos, f0 + r)] = (_Float16)(s[r] * rs);
+      }
+    }
+  }
+}
+
 // X17 = 1 (with MT = 2): the launch covers exactly 17 rows (a full draft window plus the committed
 // token).  Only row 16 of the second row tile exists, so its hi and lo parts share ONE extra MFMA: operand
 // column 0 = hi of row 16, column 1 = lo of row 16, the other columns zero in registers, and the epilogue
@@ -339,124 +467,116 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
         for (int w = 0; w < WAVES; ++w) s2 += red[w][ab][l + 33];
       }
     }
-    const bool live = m < ga.R;
-    float rs = 1.f;
-    if (ga.ssq_in && live) rs = row_scale(ga.ssq_in, ga.ssq_stride, m, ga.inv_dim, ga.eps);
+    gemm_epilogue<EPI>(ga, nt, m, l, s, s2);
+  }
+}
 
-    if (EPI == EPI_STORE) {
-      const int n = nt * 16 + g4 * 4;
-      const f32x4 lg = s * rs;
-      if (live) {
-        float* o = ga.out + (size_t)map_row(ga.sr, ga.rowmap, ga.G1, m) * ga.ldo + n;
-        *reinterpret_cast<f32x4*>(o) = lg;
-      }
-      if (ga.pick_val) {
-        // token choice, first stage: best of this tile's 16 vocabulary entries for row m
-        // (argmax of the logits, or of logits + Gumbel noise; lowest id wins ties)
-        float best = -INFINITY;
-        int bi = 0x7fffffff;
-        if (live) {
-          float g4n[4] = {0.f, 0.f, 0.f, 0.f};
-          if (ga.pick_mode) {
-            const int si = find_seq(ga.sr, m);
-            const int jrow = ga.sr.pos0[si] + (m - ga.sr.row_off[si]) - (ga.sr.len[si] - 1);
-            const uint4 bits = vocab_bits(ga.pick_seed, ga.sr.seq[si], ga.pick_step, (uint32_t)(jrow + 1), PURPOSE_DRAFT, (uint32_t)(n >> 2));
-            g4n[0] = gumbel(u01(bits.x)); g4n[1] = gumbel(u01(bits.y)); g4n[2] = gumbel(u01(bits.z)); g4n[3] = gumbel(u01(bits.w));
-          }
+// ------------------------------------------------------------------ wide GEMM: more than 32 rows
+// Batched verification puts up to 16 x 17 rows through the target model; at that width the product is
+// bound by the matrix units and by operand delivery, not by the weight stream, so the roles change:
+//   block  = 4 waves = 4*NTW output tiles x MTB row tiles, full K, walked in super-steps of 4 K steps
+//   weights: each wave streams its own NTW tiles from HBM into registers, one super-step ahead
+//   operand: the block's MTB*HL tiles of a super-step are fetched once (two super-steps ahead), written
+//            to LDS in MFMA lane order (double buffered, ONE barrier per super-step) and read by all four
+//            waves, so each operand byte feeds 4*NTW tiles and each weight byte MTB*HL MFMAs
+// Blocks that share weights (same output tiles, different rows) get consecutive slots on one XCD
+// (block id mod 8 picks the XCD), so the weight stream of the later ones comes from that XCD's L2.
+// The K loop has no branches and no conditional loads (a branch makes the compiler wait for every
+// outstanding load at the join, which serialises the pipeline on memory latency): tiles or K steps that
+// do not exist are replaced by the nearest one that does, and their products are never stored.
+// Requires KT % 4 == 0.
+template <int EPI, int NTW, int MTB, int HL, int TAG>
+__global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const GemmArgs ga, int n_tiles, int n_groups, int row_groups) {
+  constexpr int KC = 4, BT = MTB * HL, BI = (BT + 3) / 4;
+  __shared__ u32x4 Bs[2][KC][BI * 4][64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int rg = slot % row_groups, ng = (slot / row_groups) * 8 + xcd;
+  if (ng >= n_groups) return;
+  const int mtt = ga.mt_total;
+  const int mt_lo = mtt * rg / row_groups;
+  const int mtb = mtt * (rg + 1) / row_groups - mt_lo;       // row tiles of this block, 1..MTB
+  const int nt0 = ga.nt_begin + (ng * 4 + wave) * NTW;
+  const int nt_end = ga.nt_begin + n_tiles;
+  const int KT = ga.KT;
+
+  f32x4 acc[NTW][MTB];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float v = lg[r] + g4n[r];
-            if (v > best) { best = v; bi = n + r; }
-          }
-        }
+  for (int a = 0; a < NTW; ++a)
 #pragma unroll
-        for (int o = 16; o <= 32; o <<= 1) {
-          const float ov = __shfl_xor(best, o, 64);
-          const int oi = __shfl_xor(bi, o, 64);
-          if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
-        }
-        if (live && g4 == 0) {
-          ga.pick_val[(size_t)m * ga.pick_tiles + nt] = best;
-          ga.pick_idx[(size_t)m * ga.pick_tiles + nt] = bi;
-        }
-      }
-    } else if (EPI == EPI_RESID) {
-      float sq = 0.f;
-      if (live) {
-        const int n = nt * 16 + g4 * 4;
-        float* o = ga.out + (size_t)m * ga.ldo + n;
-        const f32x4 xn = *reinterpret_cast<const f32x4*>(o) + s;
-        *reinterpret_cast<f32x4*>(o) = xn;
-        const float4 gn = *reinterpret_cast<const float4*>(ga.g_next + n);
-        store_packed4(ga.xp_out, ga.mt_total_out, m, n, xn[0] * gn.x, xn[1] * gn.y, xn[2] * gn.z, xn[3] * gn.w);
-        sq = xn[0] * xn[0] + xn[1] * xn[1] + xn[2] * xn[2] + xn[3] * xn[3];
-      }
-      sq += __shfl_xor(sq, 16, 64);
-      sq += __shfl_xor(sq, 32, 64);
-      if (live && g4 == 0) atomicAdd(ga.ssq_out + (size_t)(blockIdx.x % SSQ_SUB) * ga.ssq_stride + m, (u64)(sq * SSQ_SCALE + 0.5f));
-    } else if (EPI == EPI_SWIGLU) {
-      if (live && g4 < 2) {
-        const int f = nt * 8 + g4 * 4;
-        float v[4];
+    for (int b = 0; b < MTB; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const u32x4* wp[NTW];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float gt = s[r] * rs, up = s2[r] * rs;
-          v[r] = gt / (1.0f + expf(-gt)) * up;
-        }
-        store_packed4(ga.xp_out, ga.mt_total_out, m, f, v[0], v[1], v[2], v[3]);
-      }
-    } else {  // EPI_QKV
-      if (live) {
-        const int d = ga.d, hd = ga.hd, half = hd >> 1;
-        const int si = find_seq(ga.sr, m);
-        const int rl = m - ga.sr.row_off[si];
-        const int pos = ga.sr.pos0[si] + rl;
-        _Float16* Kc = ga.kv + (((size_t)ga.sr.seq[si] * ga.n_layers + ga.layer) * 2) * (size_t)ga.max_seq * d;
-        _Float16* Vt = Kc + (size_t)ga.max_seq * d;
-        const int tiles_d = d >> 4;
-        typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-        if (nt < 2 * tiles_d) {
-          if (g4 < 2) {
-            const int part = nt / tiles_d;
-            const int tq = nt - part * tiles_d;
-            const int tph = hd >> 4;
-            const int h = tq / tph, tt = tq % tph;
-            const int j0 = 8 * tt + 4 * g4;                   // rotation pairs j0..j0+3
-            const float* tb = ga.rope + ((size_t)m * half + j0) * 2;
-            float va[4], vb[4];
+  for (int a = 0; a < NTW; ++a) wp[a] = ga.W + (size_t)min(nt0 + a, nt_end - 1) * KT * 64 + lane;
+  // operand staging: wave w copies tile-parts w, w+4, ...; lane 16g+j reads row j's bytes 16g..16g+15
+  const u32x4* xsrc[BI];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float cs = tb[2 * r], sn = tb[2 * r + 1];
-              const float x0 = s[r] * rs, x1 = s2[r] * rs;
-              va[r] = x0 * cs - x1 * sn;
-              vb[r] = x1 * cs + x0 * sn;
-            }
-            const half4 ha = {(_Float16)va[0], (_Float16)va[1], (_Float16)va[2], (_Float16)va[3]};
-            const half4 hb = {(_Float16)vb[0], (_Float16)vb[1], (_Float16)vb[2], (_Float16)vb[3]};
-            if (part == 0) {
-              // attention operand: [slot][head][kt][2 row tiles][hi|lo][lane][8], lane = 16*(dim%32/8) + row%16
-              const int kts = hd >> 5;
-              auto qidx = [&](int dim) {
-                return ((((size_t)si * ga.H + h) * kts + (dim >> 5)) * 2 + (rl >> 4)) * 1024 + (((dim & 31) >> 3) * 16 + (rl & 15)) * 8 + (dim & 7);
-              };
-              const half4 la = {(_Float16)(va[0] - (float)ha[0]), (_Float16)(va[1] - (float)ha[1]), (_Float16)(va[2] - (float)ha[2]), (_Float16)(va[3] - (float)ha[3])};
-              const half4 lb = {(_Float16)(vb[0] - (float)hb[0]), (_Float16)(vb[1] - (float)hb[1]), (_Float16)(vb[2] - (float)hb[2]), (_Float16)(vb[3] - (float)hb[3])};
-              *reinterpret_cast<half4*>(ga.qp + qidx(j0)) = ha;
-              *reinterpret_cast<half4*>(ga.qp + qidx(j0) + 512) = la;
-              *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half)) = hb;
-              *reinterpret_cast<half4*>(ga.qp + qidx(j0 + half) + 512) = lb;
-            } else {
-              *reinterpret_cast<half4*>(Kc + kcache_index(h, hd, ga.max_seq, pos, j0)) = ha;
-              *reinterpret_cast<half4*>(Kc + kcache_index(h, hd, ga.max_seq, pos, j0 + half)) = hb;
-            }
-          }
-        } else {
-          const int c0 = (nt - 2 * tiles_d) * 16 + g4 * 4;       // V feature index
-          const int h = c0 / hd, f0 = c0 - h * hd;
+  for (int it = 0; it < BI; ++it) {
+    const int tp = min(it * 4 + wave, BT - 1), b = min(tp / HL, mtb - 1), h = tp % HL;
+    xsrc[it] = ga.X + ((size_t)(mt_lo + b) * 2 + h) * 64 + (lane & 15) * 4 + (lane >> 4);
+  }
+  const size_t xstep = (size_t)mtt * 128;                      // operand elements (16 B) per K step
+  u32x4 Areg[KC][NTW], Breg[KC][BI];
+  auto loadA = [&](u32x4(&A)[NTW], int k) {                    // plain loads: row groups sharing these tiles find them in L2
+    const size_t o = (size_t)min(k, KT - 1) * 64;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) Vt[vcache_index(h, hd, ga.max_seq, pos, f0 + r)] = (_Float16)(s[r] * rs);
-        }
+    for (int a = 0; a < NTW; ++a) A[a] = wp[a][o];
+  };
+  auto loadB = [&](u32x4(&B)[BI], int k) {
+    const size_t o = (size_t)min(k, KT - 1) * xstep;
+#pragma unroll
+    for (int it = 0; it < BI; ++it) B[it] = xsrc[it][o];
+  };
+  auto storeB = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < KC; ++u)
+#pragma unroll
+      for (int it = 0; it < BI; ++it) Bs[buf][u][it * 4 + wave][lane] = Breg[u][it];
+  };
+  // prologue: operand of super-step 0 into LDS, of super-step 1 into registers; weights of super-step 0
+#pragma unroll
+  for (int u = 0; u < KC; ++u) loadB(Breg[u], u);
+#pragma unroll
+  for (int u = 0; u < KC; ++u) loadA(Areg[u], u);
+  storeB(0);
+#pragma unroll
+  for (int u = 0; u < KC; ++u) loadB(Breg[u], KC + u);
+  __syncthreads();
+  for (int k0 = 0, buf = 0; k0 < KT; k0 += KC, buf ^= 1) {
+    storeB(buf ^ 1);                                           // operand of super-step k0/KC + 1
+#pragma unroll
+    for (int u = 0; u < KC; ++u) loadB(Breg[u], k0 + 2 * KC + u);
+#pragma unroll
+    for (int u = 0; u < KC; ++u) {
+      half8 af[NTW];
+#pragma unroll
+      for (int a = 0; a < NTW; ++a) af[a] = bf16x8_to_f16x8(Areg[u][a]);
+      loadA(Areg[u], k0 + KC + u);
+      half8 bf[BT];
+#pragma unroll
+      for (int t = 0; t < BT; ++t) bf[t] = __builtin_bit_cast(half8, Bs[buf][u][t][lane]);
+#pragma unroll
+      for (int t = 0; t < BT; ++t)
+#pragma unroll
+        for (int a = 0; a < NTW; ++a) acc[a][t / HL] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[a], bf[t], acc[a][t / HL], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  constexpr bool paired = (EPI == EPI_SWIGLU) || (EPI == EPI_QKV);
+#pragma unroll
+  for (int a = 0; a < NTW; ++a) {
+    if (nt0 + a >= nt_end) continue;
+#pragma unroll
+    for (int b = 0; b < MTB; ++b) {
+      if (b >= mtb) continue;
+      const f32x4 s = acc[a][b];
+      f32x4 s2 = {0.f, 0.f, 0.f, 0.f};
+      if (paired) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s2[r] = __shfl(s[r], (lane + 32) & 63, 64);
       }
+      gemm_epilogue<EPI>(ga, nt0 + a, (mt_lo + b) * 16 + (lane & 15), lane, s, s2);
     }
   }
 }

@@ -195,7 +195,30 @@ void launch_w16(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
   hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17, HL>), dim3(n_tiles / NT), dim3(WAVES * 64), 0, c->stream, ga);
 }
 
-// Launches the GEMM over `n_tiles` output tiles starting at ga.nt_begin, in chunks of <= 32 rows.
+// More than 32 rows: one launch of the wide kernel (operand shared through LDS, weights read once).
+template <int EPI, int TAG, int HL, int MTB>
+void launch_wide_mtb(pacer_ctx* c, GemmArgs ga, int n_tiles) {
+  const int row_groups = (ga.mt_total + MTB - 1) / MTB;
+  ga.mt0 = 0;
+  // 16 output tiles per block; 8 when that leaves CUs without a block
+  int n_groups = (n_tiles + 15) / 16;
+  const bool narrow = n_groups * row_groups < 256;
+  if (narrow) n_groups = (n_tiles + 7) / 8;
+  const dim3 grid((unsigned)((n_groups + 7) / 8 * 8 * row_groups));
+  if (narrow) hipLaunchKernelGGL((gemm_wide_kernel<EPI, 2, MTB, HL, TAG>), grid, dim3(256), 0, c->stream, ga, n_tiles, n_groups, row_groups);
+  else hipLaunchKernelGGL((gemm_wide_kernel<EPI, 4, MTB, HL, TAG>), grid, dim3(256), 0, c->stream, ga, n_tiles, n_groups, row_groups);
+}
+template <int EPI, int TAG, int HL>
+void launch_wide(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
+  // row tiles per block: a block always multiplies MTB row tiles (a short group repeats its last tile), so
+  // the target model picks 3 or 4, whichever wastes fewer; equal waste -> 4 (fewer readers per weight tile)
+  const int mt = ga.mt_total;
+  if (TAG == 0 && (mt + 2) / 3 * 3 < (mt + 3) / 4 * 4) launch_wide_mtb<EPI, TAG, HL, (TAG == 0 ? 3 : 4)>(c, ga, n_tiles);
+  else launch_wide_mtb<EPI, TAG, HL, 4>(c, ga, n_tiles);
+}
+
+// Launches the GEMM over `n_tiles` output tiles starting at ga.nt_begin; up to 32 rows with the
+// weight-streaming kernel, more with the wide one.
 // HL = 2: multiply the operand's hi and lo tiles (target model, all GEMMs but the O projection and the
 // LM head, whose inputs' f16 rounding hardly shows in the logits); HL = 1: hi only.
 // Launch shapes, all measured on MI355X.  HL = 1: >= 512 output tiles -> 4 waves per block, 8 K steps
@@ -211,6 +234,12 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
   ga.KT = K / 32;
   const bool many = n_tiles >= 512;
   const bool even = n_tiles % 2 == 0;
+  if (mt_total > 2 && ga.KT % 4 == 0) {
+    if (TAG == 0) prof_begin(c);
+    launch_wide<EPI, TAG, HL>(c, ga, n_tiles);
+    if (TAG == 0) prof_end(c, (double)n_tiles * 16.0 * K * 2.0);
+    return;
+  }
   for (int mt0 = 0; mt0 < mt_total; mt0 += 2) {
     const int mt = std::min(2, mt_total - mt0);
     const int rows = ga.R - 16 * mt0;
@@ -278,7 +307,8 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
   // keys per block (8 waves): 1024, i.e. one block per head and no global merge up to 1k context
   // (measured: the device-scope fence of the split path costs more than it saves below that), more
   // when that would exceed 16 splits
-  const int kps = std::max(1024, ((max_keys + 15) / 16 + 31) / 32 * 32);
+  // With many (head, sequence) pairs the grid is full without splitting keys, whatever the length.
+  const int kps = (H * sr.n_seqs >= 128) ? (max_keys + 31) / 32 * 32 : std::max(1024, ((max_keys + 15) / 16 + 31) / 32 * 32);
   const int S = (max_keys + kps - 1) / kps;
   GemmArgs base{};
   base.R = R;

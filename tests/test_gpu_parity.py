@@ -141,6 +141,12 @@ def test_batch_mid_bf16_ragged():
     _run_batch("mid", [40, 75, 150, 260], [1.0, 2.3, 3.7, 5.0], 6, 2e-2, 2e-2)
 
 
+def test_batch_mid_bf16_eight_sequences_wide_gemm():
+    """8 sequences x up to 13 verify rows = up to 104 rows: the wide GEMM with several row groups per
+    output-tile group, ragged last row tile, per-sequence attention over different lengths."""
+    _run_batch("mid", [40, 75, 150, 260, 33, 97, 201, 64], [1.0, 2.3, 3.7, 5.0, 4.0, 3.0, 2.0, 4.5], 4, 2e-2, 2e-2)
+
+
 def _host_copy(x):
     if isinstance(x, dict):
         return {k: _host_copy(v) for k, v in x.items()}
