@@ -104,7 +104,9 @@ void pacer_destroy(pacer_ctx* ctx);
 const char* pacer_last_error(const pacer_ctx* ctx);
 
 /* Re-tiles a row-major bf16 matrix [n_out][n_in] (dev_src) into the layout the bf16 kernels
- * stream (dev_dst, same size, must not alias).  The tiling depends on the role of the matrix:
+ * stream (dev_dst, same size, must not alias).  The packed copy holds each bf16 value as an IEEE
+ * half float (what the matrix instructions multiply; exact for |w| >= 2^-17, smaller values round
+ * to the nearest half subnormal).  The tiling depends on the role of the matrix:
  * tensor_id is the PACER_T_* id it will be bound as (WQKV, WO, WGU, WD or HEAD); head_dim is
  * needed for WQKV (rotation pairs of a head share a tile) and ignored otherwise.
  * Enqueued on hip_stream. */

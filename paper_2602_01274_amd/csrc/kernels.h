@@ -7,7 +7,10 @@
 //                        features are contiguous, MFMA lane 16*g + j reads bytes 64*j + 16*g..+15.
 //                        Rows are what a launch has few of, so a GEMM wave fetches only the 64-byte
 //                        columns of live rows: operand traffic is proportional to the row count.
-//   packed weights ..... bf16, tile (nt, kt) holds outputs nt*16..+15 and inputs kt*32..+31 in MFMA
+//   packed weights ..... the model's bf16 values stored as IEEE f16 (same bytes; the matrix units take
+//                        f16 pairs with f16 activations, and converting while packing instead of in
+//                        every GEMM frees three vector instructions per weight pair; bf16 -> f16 is
+//                        exact down to 2^-17): tile (nt, kt) holds outputs nt*16..+15 and inputs kt*32..+31 in MFMA
 //                        lane order (lane 16*g + i = output i, inputs 8*g..+7), tiles ordered
 //                        [nt][kt], so a wave that walks along K for one output tile reads one
 //                        contiguous stream with one 1 KiB load per step.
@@ -215,8 +218,9 @@ __device__ __forceinline__ int map_row(const SeqRows& sr, int mode, int G1, int 
   return sr.seq[si] * G1 + (sr.pos0[si] + rr - (sr.len[si] - 1));
 }
 
-// bf16 -> f16 of one weight tile fragment (exact for normal-range weights)
-__device__ __forceinline__ half8 bf16x8_to_f16x8(u32x4 w) {
+// bf16 -> f16 of 8 weights (exact for |w| >= 2^-17; smaller ones round to the nearest f16 subnormal,
+// absolute error <= 2^-25).  Done once, when a matrix is packed.
+__device__ __forceinline__ u32x4 bf16x8_to_f16x8(u32x4 w) {
   half8 h;
   const uint32_t u[4] = {w[0], w[1], w[2], w[3]};
 #pragma unroll
@@ -225,7 +229,7 @@ __device__ __forceinline__ half8 bf16x8_to_f16x8(u32x4 w) {
     h[2 * i] = (_Float16)lo;
     h[2 * i + 1] = (_Float16)hi;
   }
-  return h;
+  return __builtin_bit_cast(u32x4, h);
 }
 
 // Plain f32 GEMM for f32 models and tiny heads: one wave per output feature, rows in groups of 8.

@@ -13,7 +13,7 @@
 // row sums of squares are accumulated by the producing GEMM's blocks with integer (fixed point,
 // 2^-26) atomics: integer addition is associative, so the result does not depend on block order.
 //
-// Weight tile layouts (written by pack_weight_kernel):
+// Weight tiles hold the bf16 values converted to f16 (see kernels.h).  Tile layouts (written by pack_weight_kind_kernel):
 //   PLAIN   tile nt, row i  <- matrix row 16*nt + i
 //   QKV     Q and K parts: a tile holds 8 rotation pairs of one head: row i<8 <- dim 8t+i, row i+8 <-
 //           dim 8t+i+hd/2 (t = tile within the head); V part plain.  RoPE then stays inside a tile.
@@ -80,7 +80,8 @@ __global__ void pack_weight_kind_kernel(uint4* __restrict__ dst, const uint16_t*
       row = (i < 8) ? (8 * nt + i) : (F + 8 * nt + (i - 8));
     }
     const uint16_t* p = src + (size_t)row * K + kt * 32 + (lane >> 4) * 8;
-    dst[idx] = *reinterpret_cast<const uint4*>(p);
+    const u32x4 h = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(p));
+    dst[idx] = make_uint4(h[0], h[1], h[2], h[3]);
   }
 }
 
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
       for (int b = 0; b < BW; ++b) bh[b] = __builtin_bit_cast(half8, (X17 && b == HL && !x17_live) ? zero : B[u][b]);
 #pragma unroll
       for (int a = 0; a < NT; ++a) {
-        const half8 ah = bf16x8_to_f16x8(A[u][a]);
+        const half8 ah = __builtin_bit_cast(half8, A[u][a]);
 #pragma unroll
         for (int b = 0; b < MT; ++b)
 #pragma unroll
@@ -474,22 +475,29 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
 // ------------------------------------------------------------------ wide GEMM: more than 32 rows
 // Batched verification puts up to 16 x 17 rows through the target model; at that width the product is
 // bound by the matrix units and by operand delivery, not by the weight stream, so the roles change:
-//   block  = 4 waves = 4*NTW output tiles x MTB row tiles, full K, walked in super-steps of 4 K steps
-//   weights: each wave streams its own NTW tiles from HBM into registers, one super-step ahead
-//   operand: the block's MTB*HL tiles of a super-step are fetched once (two super-steps ahead), written
-//            to LDS in MFMA lane order (double buffered, ONE barrier per super-step) and read by all four
-//            waves, so each operand byte feeds 4*NTW tiles and each weight byte MTB*HL MFMAs
+//   block  = KS K-slices x 4 waves; a slice's 4 waves own 4*NTW output tiles x MTB row tiles over
+//            their 1/KS of K, walked in super-steps of KC = 4/KS K steps; the slices' sums meet in LDS
+//   weights: each wave streams its own NTW tiles into registers, 4 K steps ahead
+//   operand: a slice's MTB*HL tiles of a super-step are fetched once (two super-steps ahead), written
+//            to LDS in MFMA lane order (double buffered, one barrier per super-step) and read by the
+//            slice's four waves, so each operand byte feeds 4*NTW tiles and each weight byte MTB*HL MFMAs
+// KS > 1 is for matrices with few output tiles (O and down projections): it is what puts 8 waves on a CU
+// when there are fewer blocks than CUs, and a wave alone on its SIMD cannot hide the weight stream's latency.
 // Blocks that share weights (same output tiles, different rows) get consecutive slots on one XCD
-// (block id mod 8 picks the XCD), so the weight stream of the later ones comes from that XCD's L2.
+// (block id mod 8 picks the XCD), so the weight stream of the later ones comes from that XCD's L2
+// (measured: 1.2 to 1.5 x the weight bytes from HBM with three row groups).
 // The K loop has no branches and no conditional loads (a branch makes the compiler wait for every
 // outstanding load at the join, which serialises the pipeline on memory latency): tiles or K steps that
 // do not exist are replaced by the nearest one that does, and their products are never stored.
-// Requires KT % 4 == 0.
-template <int EPI, int NTW, int MTB, int HL, int TAG>
-__global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const GemmArgs ga, int n_tiles, int n_groups, int row_groups) {
-  constexpr int KC = 4, BT = MTB * HL, BI = (BT + 3) / 4;
-  __shared__ u32x4 Bs[2][KC][BI * 4][64];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+// Requires KT % (4*KS) == 0.
+template <int EPI, int NTW, int MTB, int HL, int TAG, int KS>
+__global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(const GemmArgs ga, int n_tiles, int n_groups, int row_groups) {
+  constexpr int UA = 4, KC = UA / KS, BT = MTB * HL, BI = (BT + 3) / 4;
+  __shared__ u32x4 Bs[KS][2][KC][BI * 4][64];
+  static_assert(KS == 1 || (KS - 1) * 4 * NTW * MTB <= KS * 2 * KC * BI * 4, "slice sums reuse the operand buffers");
+  // wave-uniform ids as scalars, so that tile pointers and K offsets live in scalar registers
+  const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wave = wid & 3, ks = wid >> 2, lane = threadIdx.x & 63;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int rg = slot % row_groups, ng = (slot / row_groups) * 8 + xcd;
   if (ng >= n_groups) return;
@@ -498,7 +506,7 @@ __global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const GemmArgs ga, in
   const int mtb = mtt * (rg + 1) / row_groups - mt_lo;       // row tiles of this block, 1..MTB
   const int nt0 = ga.nt_begin + (ng * 4 + wave) * NTW;
   const int nt_end = ga.nt_begin + n_tiles;
-  const int KT = ga.KT;
+  const int KT = ga.KT, kb = ks * (KT / KS), ke = kb + KT / KS;
 
   f32x4 acc[NTW][MTB];
 #pragma unroll
@@ -516,51 +524,75 @@ __global__ __launch_bounds__(256, 2) void gemm_wide_kernel(const GemmArgs ga, in
     xsrc[it] = ga.X + ((size_t)(mt_lo + b) * 2 + h) * 64 + (lane & 15) * 4 + (lane >> 4);
   }
   const size_t xstep = (size_t)mtt * 128;                      // operand elements (16 B) per K step
-  u32x4 Areg[KC][NTW], Breg[KC][BI];
+  u32x4 Areg[UA][NTW], Breg[KC][BI];
   auto loadA = [&](u32x4(&A)[NTW], int k) {                    // plain loads: row groups sharing these tiles find them in L2
-    const size_t o = (size_t)min(k, KT - 1) * 64;
+    const size_t o = (size_t)min(k, ke - 1) * 64;
 #pragma unroll
     for (int a = 0; a < NTW; ++a) A[a] = wp[a][o];
   };
   auto loadB = [&](u32x4(&B)[BI], int k) {
-    const size_t o = (size_t)min(k, KT - 1) * xstep;
+    const size_t o = (size_t)min(k, ke - 1) * xstep;
 #pragma unroll
     for (int it = 0; it < BI; ++it) B[it] = xsrc[it][o];
   };
   auto storeB = [&](int buf) {
 #pragma unroll
-    for (int u = 0; u < KC; ++u)
+    for (int j = 0; j < KC; ++j)
 #pragma unroll
-      for (int it = 0; it < BI; ++it) Bs[buf][u][it * 4 + wave][lane] = Breg[u][it];
+      for (int it = 0; it < BI; ++it) Bs[ks][buf][j][it * 4 + wave][lane] = Breg[j][it];
   };
-  // prologue: operand of super-step 0 into LDS, of super-step 1 into registers; weights of super-step 0
+  // prologue: operand of super-step 0 into LDS, of super-step 1 into registers; weights of 4 steps
 #pragma unroll
-  for (int u = 0; u < KC; ++u) loadB(Breg[u], u);
+  for (int j = 0; j < KC; ++j) loadB(Breg[j], kb + j);
 #pragma unroll
-  for (int u = 0; u < KC; ++u) loadA(Areg[u], u);
+  for (int u = 0; u < UA; ++u) loadA(Areg[u], kb + u);
   storeB(0);
 #pragma unroll
-  for (int u = 0; u < KC; ++u) loadB(Breg[u], KC + u);
+  for (int j = 0; j < KC; ++j) loadB(Breg[j], kb + KC + j);
   __syncthreads();
-  for (int k0 = 0, buf = 0; k0 < KT; k0 += KC, buf ^= 1) {
-    storeB(buf ^ 1);                                           // operand of super-step k0/KC + 1
+  int buf = 0;
+  for (int k0 = kb; k0 < ke; k0 += UA) {
 #pragma unroll
-    for (int u = 0; u < KC; ++u) loadB(Breg[u], k0 + 2 * KC + u);
+    for (int ss = 0; ss < UA / KC; ++ss) {
+      storeB(buf ^ 1);                                         // operand of the next super-step
 #pragma unroll
-    for (int u = 0; u < KC; ++u) {
-      half8 af[NTW];
+      for (int j = 0; j < KC; ++j) loadB(Breg[j], k0 + ss * KC + 2 * KC + j);
 #pragma unroll
-      for (int a = 0; a < NTW; ++a) af[a] = bf16x8_to_f16x8(Areg[u][a]);
-      loadA(Areg[u], k0 + KC + u);
-      half8 bf[BT];
+      for (int j = 0; j < KC; ++j) {
+        const int u = ss * KC + j;
+        half8 af[NTW];
 #pragma unroll
-      for (int t = 0; t < BT; ++t) bf[t] = __builtin_bit_cast(half8, Bs[buf][u][t][lane]);
+        for (int a = 0; a < NTW; ++a) af[a] = __builtin_bit_cast(half8, Areg[u][a]);
+        loadA(Areg[u], k0 + UA + u);
+        half8 bf[BT];
 #pragma unroll
-      for (int t = 0; t < BT; ++t)
+        for (int t = 0; t < BT; ++t) bf[t] = __builtin_bit_cast(half8, Bs[ks][buf][j][t][lane]);
 #pragma unroll
-        for (int a = 0; a < NTW; ++a) acc[a][t / HL] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[a], bf[t], acc[a][t / HL], 0, 0, 0);
+        for (int t = 0; t < BT; ++t)
+#pragma unroll
+          for (int a = 0; a < NTW; ++a) acc[a][t / HL] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[a], bf[t], acc[a][t / HL], 0, 0, 0);
+      }
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+  if (KS > 1) {
+    // slices 1.. hand their sums to slice 0 through the (now idle) operand buffers, added in slice order
+    f32x4* red = reinterpret_cast<f32x4*>(&Bs[0][0][0][0][0]);
+    if (ks > 0) {
+#pragma unroll
+      for (int a = 0; a < NTW; ++a)
+#pragma unroll
+        for (int b = 0; b < MTB; ++b) red[((((ks - 1) * 4 + wave) * NTW + a) * MTB + b) * 64 + lane] = acc[a][b];
     }
     __syncthreads();
+    if (ks > 0) return;
+#pragma unroll
+    for (int s = 1; s < KS; ++s)
+#pragma unroll
+      for (int a = 0; a < NTW; ++a)
+#pragma unroll
+        for (int b = 0; b < MTB; ++b) acc[a][b] += red[((((s - 1) * 4 + wave) * NTW + a) * MTB + b) * 64 + lane];
   }
 
   constexpr bool paired = (EPI == EPI_SWIGLU) || (EPI == EPI_QKV);

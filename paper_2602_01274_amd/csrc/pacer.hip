@@ -196,17 +196,29 @@ void launch_w16(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
 }
 
 // More than 32 rows: one launch of the wide kernel (operand shared through LDS, weights read once).
+template <int EPI, int TAG, int HL, int MTB, int NTW, int KS>
+void launch_wide_shape(pacer_ctx* c, const GemmArgs& ga, int n_tiles, int row_groups) {
+  const int n_groups = (n_tiles + 4 * NTW - 1) / (4 * NTW);
+  const dim3 grid((unsigned)((n_groups + 7) / 8 * 8 * row_groups));
+  hipLaunchKernelGGL((gemm_wide_kernel<EPI, NTW, MTB, HL, TAG, KS>), grid, dim3(256 * KS), 0, c->stream, ga, n_tiles, n_groups, row_groups);
+}
 template <int EPI, int TAG, int HL, int MTB>
 void launch_wide_mtb(pacer_ctx* c, GemmArgs ga, int n_tiles) {
   const int row_groups = (ga.mt_total + MTB - 1) / MTB;
   ga.mt0 = 0;
-  // 16 output tiles per block; 8 when that leaves CUs without a block
-  int n_groups = (n_tiles + 15) / 16;
-  const bool narrow = n_groups * row_groups < 256;
-  if (narrow) n_groups = (n_tiles + 7) / 8;
-  const dim3 grid((unsigned)((n_groups + 7) / 8 * 8 * row_groups));
-  if (narrow) hipLaunchKernelGGL((gemm_wide_kernel<EPI, 2, MTB, HL, TAG>), grid, dim3(256), 0, c->stream, ga, n_tiles, n_groups, row_groups);
-  else hipLaunchKernelGGL((gemm_wide_kernel<EPI, 4, MTB, HL, TAG>), grid, dim3(256), 0, c->stream, ga, n_tiles, n_groups, row_groups);
+  if constexpr (TAG != 0) {   // draft and pre-verification layer: small matrices, one shape
+    launch_wide_shape<EPI, TAG, HL, MTB, 2, 1>(c, ga, n_tiles, row_groups);
+  } else {
+  // Output tiles per wave (NTW): blocks run two to a CU, so the launch takes about
+  // ceil(blocks / 256) * NTW units; pick the NTW with the fewest units, the larger one on a tie (it reads
+  // the operand from LDS less often).  Fewer blocks than CUs: split K over two slices of waves instead.
+  auto blocks = [&](int ntw) { return (n_tiles + 4 * ntw - 1) / (4 * ntw) * row_groups; };
+  auto units = [&](int ntw) { return (blocks(ntw) + 255) / 256 * ntw; };
+  if (blocks(2) <= 256 && ga.KT % 8 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 2, 2>(c, ga, n_tiles, row_groups);
+  else if (units(4) <= units(3) && units(4) <= units(2)) launch_wide_shape<EPI, TAG, HL, MTB, 4, 1>(c, ga, n_tiles, row_groups);
+  else if (units(3) <= units(2)) launch_wide_shape<EPI, TAG, HL, MTB, 3, 1>(c, ga, n_tiles, row_groups);
+  else launch_wide_shape<EPI, TAG, HL, MTB, 2, 1>(c, ga, n_tiles, row_groups);
+  }
 }
 template <int EPI, int TAG, int HL>
 void launch_wide(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
@@ -281,7 +293,10 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
 template <int EPI>
 void gemm_w16(pacer_ctx* c, int tag, bool hilo, const GemmArgs& ga, int n_tiles, int K) {
   if (tag == 0) {
-    if (hilo) gemm_w16_tag<EPI, 0, 2>(c, ga, n_tiles, K);
+    // the target's QKV and gate/up GEMMs always take hi+lo, its LM head never does
+    if constexpr (EPI == EPI_QKV || EPI == EPI_SWIGLU) gemm_w16_tag<EPI, 0, 2>(c, ga, n_tiles, K);
+    else if constexpr (EPI == EPI_STORE) gemm_w16_tag<EPI, 0, 1>(c, ga, n_tiles, K);
+    else if (hilo) gemm_w16_tag<EPI, 0, 2>(c, ga, n_tiles, K);
     else gemm_w16_tag<EPI, 0, 1>(c, ga, n_tiles, K);
   } else {
     gemm_w16_tag<EPI, 1, 1>(c, ga, n_tiles, K);
