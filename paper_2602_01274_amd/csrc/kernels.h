@@ -534,52 +534,101 @@ __global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const floa
 // ------------------------------------------------------------------ acceptance (Eq. 5)
 struct AccArgs { int n_seqs; int seq[PK_MAXB]; int gamma[PK_MAXB]; int len[PK_MAXB]; float beta[PK_MAXB]; };
 
-// grid (gamma_max+1, n_seqs): row i of sequence slot si.  Writes cand (token emitted if this row
-// is where drafting is cut) and rej (row's draft rejected).
-__global__ __launch_bounds__(1024) void accept_rows_kernel(const float* __restrict__ tl, const float* __restrict__ ring,
-                                                           const int* __restrict__ draft_tok, AccArgs aa, int G1, int V, int mode,
-                                                           uint64_t seed, uint32_t step, int* __restrict__ cand, int* __restrict__ rej) {
+// One row of logits is split into ACC_CHUNKS vocabulary ranges, one block each (a single block per row
+// spent 53 us walking 32000 entries three times).  Three launches:
+//   accept_stats_kernel   per (row, chunk): running max and sum of exp of the effective target logits and
+//                         of the draft logits over the chunk                                  (sampling only)
+//   accept_rows_kernel    per (row, chunk): log-sum-exp of the row from the chunk statistics (fixed chunk
+//                         order, so every chunk of a row derives the same value), then the chunk's best
+//                         candidates; chunk 0 also takes the row's accept test
+//   accept_finalize_kernel per sequence: best candidate over the chunks of each row, first rejection, tokens
+#define ACC_CHUNKS 8
+#define ACC_PART 8      // floats per (row, chunk): [0..3] = mp, sp, mq, sq ; [4..7] = best, bi, bestp, bip
+
+__device__ __forceinline__ void acc_chunk_range(int V, int chunk, int& v0, int& v1) {
+  const int per = ((V + ACC_CHUNKS - 1) / ACC_CHUNKS + 3) & ~3;   // multiple of 4: a Philox block never straddles chunks
+  v0 = min(V, chunk * per);
+  v1 = min(V, v0 + per);
+}
+
+// grid (gamma_max+1, n_seqs, ACC_CHUNKS)
+__global__ __launch_bounds__(256) void accept_stats_kernel(const float* __restrict__ tl, const float* __restrict__ ring, AccArgs aa, int G1,
+                                                           int V, float* __restrict__ part) {
+  __shared__ float redv[16];
+  const int i = blockIdx.x, si = blockIdx.y, ch = blockIdx.z, s = aa.seq[si];
+  if (i > aa.gamma[si]) return;
+  const float beta = aa.beta[si];
+  const float* t = tl + (size_t)(si * G1 + i) * V;
+  const float* q = ring + (size_t)(s * G1 + i) * V;
+  int v0, v1;
+  acc_chunk_range(V, ch, v0, v1);
+  float mp = -INFINITY, mq = -INFINITY;
+  for (int v = v0 + threadIdx.x; v < v1; v += blockDim.x) { mp = fmaxf(mp, t[v] + beta * q[v]); mq = fmaxf(mq, q[v]); }
+  mp = block_max(mp, redv);
+  mq = block_max(mq, redv);
+  float sp = 0.f, sq = 0.f;
+  for (int v = v0 + threadIdx.x; v < v1; v += blockDim.x) { sp += expf(t[v] + beta * q[v] - mp); sq += expf(q[v] - mq); }
+  sp = block_sum(sp, redv);
+  sq = block_sum(sq, redv);
+  if (threadIdx.x == 0) {
+    float* o = part + ((size_t)(si * G1 + i) * ACC_CHUNKS + ch) * ACC_PART;
+    o[0] = mp; o[1] = sp; o[2] = mq; o[3] = sq;
+  }
+}
+
+// grid (gamma_max+1, n_seqs, ACC_CHUNKS): row i of sequence slot si, vocabulary chunk ch.  Writes the chunk's
+// candidates (token emitted if this row is where drafting is cut) and, from chunk 0, rej (row's draft rejected).
+__global__ __launch_bounds__(256) void accept_rows_kernel(const float* __restrict__ tl, const float* __restrict__ ring,
+                                                          const int* __restrict__ draft_tok, AccArgs aa, int G1, int V, int mode,
+                                                          uint64_t seed, uint32_t step, float* __restrict__ part, int* __restrict__ rej) {
   __shared__ float redv[16];
   __shared__ int redi[16];
-  const int i = blockIdx.x, si = blockIdx.y, s = aa.seq[si];
+  const int i = blockIdx.x, si = blockIdx.y, ch = blockIdx.z, s = aa.seq[si];
   const int gamma = aa.gamma[si];
   if (i > gamma) return;
   const float beta = aa.beta[si];
   const float* t = tl + (size_t)(si * G1 + i) * V;
   const float* q = ring + (size_t)(s * G1 + i) * V;
   const int y = i < gamma ? draft_tok[s * G1 + i] : -1;
+  float* prow = part + (size_t)(si * G1 + i) * ACC_CHUNKS * ACC_PART;
+  float* o = prow + ch * ACC_PART;
+  int v0, v1;
+  acc_chunk_range(V, ch, v0, v1);
   if (mode == 0) {
     float best = -INFINITY;
     int bi = 0x7fffffff;
-    for (int v = threadIdx.x; v < V; v += blockDim.x) {
+    for (int v = v0 + threadIdx.x; v < v1; v += blockDim.x) {
       const float e = t[v] + beta * q[v];
       if (e > best) { best = e; bi = v; }
     }
     block_argmax(best, bi, redv, redi);
-    if (threadIdx.x == 0) { cand[si * G1 + i] = bi; rej[si * G1 + i] = (i < gamma && bi != y) ? 1 : 0; }
+    if (threadIdx.x == 0) {
+      o[4] = -INFINITY; o[5] = __int_as_float(0x7fffffff);
+      o[6] = best; o[7] = __int_as_float(bi);
+    }
     return;
   }
-  // log-sum-exp of effective target and of draft logits
+  // log-sum-exp of effective target and of draft logits from the chunk statistics
   float mp = -INFINITY, mq = -INFINITY;
-  for (int v = threadIdx.x; v < V; v += blockDim.x) { mp = fmaxf(mp, t[v] + beta * q[v]); mq = fmaxf(mq, q[v]); }
-  mp = block_max(mp, redv);
-  mq = block_max(mq, redv);
+  for (int c = 0; c < ACC_CHUNKS; ++c) { mp = fmaxf(mp, prow[c * ACC_PART]); mq = fmaxf(mq, prow[c * ACC_PART + 2]); }
   float sp = 0.f, sq = 0.f;
-  for (int v = threadIdx.x; v < V; v += blockDim.x) { sp += expf(t[v] + beta * q[v] - mp); sq += expf(q[v] - mq); }
-  sp = block_sum(sp, redv);
-  sq = block_sum(sq, redv);
+  for (int c = 0; c < ACC_CHUNKS; ++c) {
+    const float m1 = prow[c * ACC_PART], m2 = prow[c * ACC_PART + 2];
+    if (m1 > -INFINITY) sp += prow[c * ACC_PART + 1] * expf(m1 - mp);
+    if (m2 > -INFINITY) sq += prow[c * ACC_PART + 3] * expf(m2 - mq);
+  }
   const float lsp = mp + logf(sp), lsq = mq + logf(sq);
   // candidate token: Gumbel-max over log max(0, p - q) (rows < gamma) or log p (bonus row);
   // if no residual mass exists the row falls back to log p with the same noise
   float best = -INFINITY, bestp = -INFINITY;
   int bi = 0x7fffffff, bip = 0x7fffffff;
-  for (int blk = threadIdx.x; blk * 4 < V; blk += blockDim.x) {
+  for (int blk = (v0 >> 2) + threadIdx.x; blk * 4 < v1; blk += blockDim.x) {
     const uint4 b = vocab_bits(seed, s, step, (uint32_t)(i + 1), PURPOSE_NEXT, (uint32_t)blk);
     const float g4[4] = {gumbel(u01(b.x)), gumbel(u01(b.y)), gumbel(u01(b.z)), gumbel(u01(b.w))};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int v = blk * 4 + e;
-      if (v < V) {
+      if (v < v1) {
         const float lp = t[v] + beta * q[v] - lsp;
         const float kp = lp + g4[e];
         if (kp > bestp) { bestp = kp; bip = v; }
@@ -594,33 +643,57 @@ __global__ __launch_bounds__(1024) void accept_rows_kernel(const float* __restri
     }
   }
   block_argmax(bestp, bip, redv, redi);
-  int c = bip;
-  if (i < gamma) {
-    block_argmax(best, bi, redv, redi);
-    if (best > -INFINITY) c = bi;
-  }
+  if (i < gamma) block_argmax(best, bi, redv, redi);
   if (threadIdx.x == 0) {
-    cand[si * G1 + i] = c;
-    int rj = 0;
-    if (i < gamma) {
-      const float ratio = expf((t[y] + beta * q[y] - lsp) - (q[y] - lsq));
-      const uint4 b = vocab_bits(seed, s, step, (uint32_t)(i + 1), PURPOSE_ACCEPT, 0u);
-      rj = (u01(b.x) > ratio) ? 1 : 0;
+    o[4] = best; o[5] = __int_as_float(bi);
+    o[6] = bestp; o[7] = __int_as_float(bip);
+    if (ch == 0) {
+      int rj = 0;
+      if (i < gamma) {
+        const float ratio = expf((t[y] + beta * q[y] - lsp) - (q[y] - lsq));
+        const uint4 b = vocab_bits(seed, s, step, (uint32_t)(i + 1), PURPOSE_ACCEPT, 0u);
+        rj = (u01(b.x) > ratio) ? 1 : 0;
+      }
+      rej[si * G1 + i] = rj;
     }
-    rej[si * G1 + i] = rj;
   }
 }
 
 // n = first rejected row (or gamma); next token = that row's candidate; append to committed tokens
-__global__ void accept_finalize_kernel(const int* __restrict__ cand, const int* __restrict__ rej, const int* __restrict__ draft_tok,
-                                       AccArgs aa, int G1, int max_seq, int* __restrict__ tokens, int* __restrict__ out_n,
+__global__ void accept_finalize_kernel(const float* __restrict__ part, const int* __restrict__ rej, const int* __restrict__ draft_tok,
+                                       AccArgs aa, int G1, int mode, int max_seq, int* __restrict__ tokens, int* __restrict__ out_n,
                                        int* __restrict__ out_z, int* __restrict__ host_res) {
   const int si = blockIdx.x, s = aa.seq[si];
   const int gamma = aa.gamma[si];
   int n = gamma;
-  for (int i = gamma - 1; i >= 0; --i)
-    if (rej[si * G1 + i]) n = i;
-  const int z = cand[si * G1 + n];
+  if (mode == 0) {
+    // greedy: row i's draft is rejected when it differs from the row's argmax
+    for (int i = gamma - 1; i >= 0; --i) {
+      const float* pr = part + (size_t)(si * G1 + i) * ACC_CHUNKS * ACC_PART;
+      float best = -INFINITY;
+      int bi = 0x7fffffff;
+      for (int c = 0; c < ACC_CHUNKS; ++c) {
+        const float v = pr[c * ACC_PART + 6];
+        const int id = __float_as_int(pr[c * ACC_PART + 7]);
+        if (v > best || (v == best && id < bi)) { best = v; bi = id; }
+      }
+      if (bi != draft_tok[s * G1 + i]) n = i;
+    }
+  } else {
+    for (int i = gamma - 1; i >= 0; --i)
+      if (rej[si * G1 + i]) n = i;
+  }
+  // the emitted token: best residual candidate of row n over the chunks, else best candidate of p
+  const float* pr = part + (size_t)(si * G1 + n) * ACC_CHUNKS * ACC_PART;
+  float best = -INFINITY, bestp = -INFINITY;
+  int bi = 0x7fffffff, bip = 0x7fffffff;
+  for (int c = 0; c < ACC_CHUNKS; ++c) {
+    const float v = pr[c * ACC_PART + 4], vp = pr[c * ACC_PART + 6];
+    const int id = __float_as_int(pr[c * ACC_PART + 5]), idp = __float_as_int(pr[c * ACC_PART + 7]);
+    if (v > best || (v == best && id < bi)) { best = v; bi = id; }
+    if (vp > bestp || (vp == bestp && idp < bip)) { bestp = vp; bip = idp; }
+  }
+  const int z = (n < gamma && best > -INFINITY) ? bi : bip;
   int* tk = tokens + (size_t)s * max_seq + aa.len[si];
   for (int k = threadIdx.x; k < n; k += blockDim.x) tk[k] = draft_tok[s * G1 + k];
   if (threadIdx.x == 0) {

@@ -54,7 +54,8 @@ struct pacer_ctx {
   // workspace carve-up
   bool ws_bound = false;
   int G1 = 0, rcap = 0, dmax = 0, fmax = 0, kmax = 0, hmax = 0, hdmax = 0, max_seq = 0;
-  int *tokens = nullptr, *draft_tok = nullptr, *cand = nullptr, *rej = nullptr;
+  int *tokens = nullptr, *draft_tok = nullptr, *rej = nullptr;
+  float* acc_part = nullptr;   // acceptance: per (slot, row, vocabulary chunk) statistics and candidates
   float *ring = nullptr, *hidden = nullptr, *x = nullptr, *xn = nullptr, *qkv = nullptr, *ao = nullptr, *gu = nullptr,
         *rope = nullptr, *part = nullptr;
   _Float16 *xpA = nullptr, *xpB = nullptr, *qp = nullptr;   // bf16 path: ping-pong f16 operands, attention Q operand
@@ -123,7 +124,7 @@ size_t carve(pacer_ctx* c, void* base) {
   const int mtcap = (c->rcap + 15) / 16;
   c->tokens = k.take<int>((size_t)B * c->max_seq);
   c->draft_tok = k.take<int>((size_t)B * G1);
-  c->cand = k.take<int>((size_t)B * G1);
+  c->acc_part = k.take<float>((size_t)B * G1 * ACC_CHUNKS * ACC_PART);
   c->rej = k.take<int>((size_t)B * G1);
   c->ring = k.take<float>((size_t)B * G1 * V);
   c->hidden = k.take<float>((size_t)B * G1 * dD);
@@ -920,10 +921,13 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
     aa.beta[i] = beta[i];
   }
   const int V = c->m[PACER_TARGET].cfg.vocab;
-  hipLaunchKernelGGL(accept_rows_kernel, dim3(c->G1, n), dim3(1024), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode,
-                     seed, (uint32_t)ctr, c->cand, c->rej);
-  hipLaunchKernelGGL(accept_finalize_kernel, dim3(n), dim3(64), 0, c->stream, c->cand, c->rej, c->draft_tok, aa, c->G1, c->max_seq,
-                     c->tokens, dev_n, dev_z, c->host_res_dev);
+  const dim3 grid(c->G1, n, ACC_CHUNKS);
+  if (mode != PACER_GREEDY)
+    hipLaunchKernelGGL(accept_stats_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, aa, c->G1, V, c->acc_part);
+  hipLaunchKernelGGL(accept_rows_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode, seed,
+                     (uint32_t)ctr, c->acc_part, c->rej);
+  hipLaunchKernelGGL(accept_finalize_kernel, dim3(n), dim3(64), 0, c->stream, c->acc_part, c->rej, c->draft_tok, aa, c->G1, mode,
+                     c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev);
   for (int i = 0; i < n; ++i) {
     Seq& q = c->seq[seqs[i]];
     q.pending = true;
