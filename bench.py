@@ -17,6 +17,7 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
         sys.path.insert(0, p)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0   # dense f16/bf16 matrix peak of MI355X
 
 
 def weight_bytes(shape, n_layers=None):
@@ -155,11 +156,23 @@ def main():
     calls = {}
     for name, ts in tm.items():
         ms = sum(ts) / len(ts)
-        calls[name] = {"mean_ms": round(ms, 4), "n": len(ts)}
+        q = sorted(ts)
+        pct = lambda f: q[min(len(q) - 1, int(f * len(q)))]
+        calls[name] = {"mean_ms": round(ms, 4), "median_ms": round(pct(0.5), 4), "p10_ms": round(pct(0.1), 4),
+                       "p90_ms": round(pct(0.9), 4), "n": len(ts)}
         if name in alg:
             calls[name]["algorithmic_GB"] = round(alg[name] / 1e9, 4)
             calls[name]["GBps"] = round(alg[name] / 1e6 / ms, 1)
             calls[name]["hbm_frac"] = round(alg[name] / 1e6 / ms / HBM_PEAK_GBS, 4)
+
+    # matrix-unit view of the verify pass (what matters once a batch puts hundreds of rows through it):
+    # algorithmic FLOPs = 2 x target parameters x verified rows, against the dense f16 MFMA peak
+    if "verify" in calls:
+        rows = nb * (main_run["mean_gamma"] + 1.0)
+        flops = weight_bytes(w["target"], L) * rows          # 2 FLOPs per weight per row = bytes x rows for 2-byte weights
+        tf = flops / 1e9 / calls["verify"]["mean_ms"]
+        calls["verify"].update({"rows": round(rows, 1), "algorithmic_TFLOP": round(flops / 1e12, 4), "TFLOPs": round(tf, 1),
+                                "mfma_frac": round(tf / MFMA_PEAK_TFLOPS, 4)})
 
     context = {}
     if not a.no_context:
@@ -205,7 +218,8 @@ def main():
         "tau": round(main_run["tau"], 3), "mean_gamma": round(main_run["mean_gamma"], 3),
         "forwards": counts, "verify_GBps": calls.get("verify", {}).get("GBps"),
         "calls": calls, "context": context,
-        "roofline": {"bound": "hbm", "kernel": "gemm_w16_kernel, target-model launches (template TAG 0), all shapes",
+        "roofline": {"bound": "hbm", "kernel": ("gemm_w16_kernel" if nb == 1 else "gemm_wide_kernel / gemm_w16_kernel")
+                               + ", target-model launches (template TAG 0), all shapes",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "launches": int(n_launch), "avg_launch_us": round(1e3 * gemm_ms / max(1, n_launch), 3),

@@ -2,8 +2,8 @@
 //
 // One decoder layer is five launches:
 //   QKV GEMM   (epilogue: row scale of the RMSNorm, RoPE, Q -> f16 attention operand, K/V -> cache)
-//   attention  (MFMA scores and weighted values, one wave per key range, no LDS; the wave that
-//               finishes last for a head merges the ranges into the f16 operand of the O projection)
+//   attention  (MFMA scores and weighted values, 8 waves per key range merged through LDS, output = the
+//               f16 operand of the O projection; long contexts: several key ranges + a merge launch)
 //   O GEMM     (epilogue: residual add, next norm's operand x*g as f16, row sum of squares)
 //   gate/up GEMM (epilogue: row scale, SwiGLU, f16 operand of the down projection)
 //   down GEMM  (epilogue: residual add, next norm's operand, row sum of squares)
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(
 //           holds), and V^T rows are contiguous along keys.
 // The 8 wave states are merged pairwise through LDS (same lane layout on both sides, so no transposition).
 // With one split the block writes the f16 operand of the O projection directly; with several, each block
-// writes a partial and the block that arrives last (device-scope ticket) merges them.
+// writes a partial and attn_merge_kernel combines them.
 struct AttnState { float m, l; };
 __device__ __forceinline__ void merge_w(float m1, float m2, float& M, float& w1, float& w2) {
   M = fmaxf(m1, m2);
@@ -634,12 +634,10 @@ __device__ __forceinline__ void merge_w(float m1, float m2, float& M, float& w1,
 template <int HD, int MT, int QL>
 __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restrict__ qp, const _Float16* __restrict__ kv, int layer,
                                                         int n_layers, int max_seq, int d, SeqRows sr, int kps, int S, int H,
-                                                        float* __restrict__ part, int* __restrict__ counters,
-                                                        _Float16* __restrict__ xp_out, int MT_total_out) {
+                                                        float* __restrict__ part, _Float16* __restrict__ xp_out, int MT_total_out) {
   constexpr int KTS = HD / 32, DTS = HD / 16, NW = 8;
   __shared__ f32x4 sacc[NW / 2][DTS][64];
   __shared__ float sm[NW / 2][64], sl[NW / 2][64];
-  __shared__ int s_last;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
   const int split = blockIdx.x, h = blockIdx.y, si = blockIdx.z;
   const int r0 = sr.row_off[si], Rs = sr.row_off[si + 1] - r0, pos0 = sr.pos0[si];
@@ -807,7 +805,7 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
     }
     return;
   }
-  // several splits: partial to global, last block merges
+  // several splits: un-normalised partial (values, running max, running sum) for attn_merge_kernel
   if (wave == 0) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -819,34 +817,38 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
         if (g == 0) { o[HD] = mrun[mt]; o[HD + 1] = lrun[mt]; }
       }
     }
-    __threadfence();
-    if (lane == 0) s_last = (atomicAdd(counters + si * H + h, 1) == n_split - 1) ? 1 : 0;
   }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  // all 512 threads: outputs are (row, 4 consecutive dims)
-  for (int o4 = threadIdx.x; o4 < Rs * (HD / 4); o4 += 512) {
+}
+
+// Merge of the key splits of attn_mfma_kernel (its own launch: a merge by the block that arrives last
+// needs device-scope fences, which cost more than a launch on this part).  grid (heads, sequences);
+// a thread owns 4 consecutive dims of one row; output = the f16 operand of the O projection.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, SeqRows sr, int kps, int S, int H,
+                                                         _Float16* __restrict__ xp_out, int MT_total_out) {
+  const int h = blockIdx.x, si = blockIdx.y;
+  const int r0 = sr.row_off[si], Rs = sr.row_off[si + 1] - r0;
+  const int n_split = (sr.pos0[si] + Rs + kps - 1) / kps;
+  if (n_split <= 1) return;                                   // that sequence's block wrote its output itself
+  for (int o4 = threadIdx.x; o4 < Rs * (HD / 4); o4 += blockDim.x) {
     const int rl = o4 / (HD / 4), d4 = (o4 % (HD / 4)) * 4;
     const float* p = part + ((size_t)(r0 + rl) * H + h) * S * (HD + 2);
     float M = -INFINITY;
-    for (int c = 0; c < n_split; ++c) M = fmaxf(M, __builtin_nontemporal_load(p + (size_t)c * (HD + 2) + HD));
+    for (int c = 0; c < n_split; ++c) M = fmaxf(M, p[(size_t)c * (HD + 2) + HD]);
     float L = 0.f;
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < n_split; ++c) {
       const float* pc = p + (size_t)c * (HD + 2);
-      const float m = __builtin_nontemporal_load(pc + HD);
+      const float m = pc[HD];
       const float w = (m == -INFINITY) ? 0.f : expf(m - M);
-      L += __builtin_nontemporal_load(pc + HD + 1) * w;
+      L += pc[HD + 1] * w;
       typedef float f32x2 __attribute__((ext_vector_type(2)));
-      const f32x2 a01 = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(pc + d4));
-      const f32x2 a23 = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(pc + d4 + 2));
+      const f32x2 a01 = *reinterpret_cast<const f32x2*>(pc + d4), a23 = *reinterpret_cast<const f32x2*>(pc + d4 + 2);
       a[0] += a01[0] * w; a[1] += a01[1] * w; a[2] += a23[0] * w; a[3] += a23[1] * w;
     }
     const float inv = 1.0f / L;
     store_packed4(xp_out, MT_total_out, r0 + rl, h * HD + d4, a[0] * inv, a[1] * inv, a[2] * inv, a[3] * inv);
   }
-  if (threadIdx.x == 0) counters[si * H + h] = 0;
 }
 
 // ------------------------------------------------------------------ tail of a draft forward

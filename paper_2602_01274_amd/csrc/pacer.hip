@@ -60,7 +60,6 @@ struct pacer_ctx {
         *rope = nullptr, *part = nullptr;
   _Float16 *xpA = nullptr, *xpB = nullptr, *qp = nullptr;   // bf16 path: ping-pong f16 operands, attention Q operand
   u64* ssq = nullptr;                                         // bf16 path: row sums of squares, [2*Lmax+1][rcap]
-  int* att_cnt = nullptr;                                     // bf16 path: arrival tickets per (sequence slot, head)
   float* pick_val = nullptr;                                  // bf16 path: per (row, vocab tile) token candidates
   int* pick_idx = nullptr;
   int lmax = 0;
@@ -139,7 +138,6 @@ size_t carve(pacer_ctx* c, void* base) {
   c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);
   c->qp = k.take<_Float16>((size_t)c->max_batch * (c->dmax / 32) * 2 * 1024);
   c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * SSQ_SUB * c->rcap);
-  c->att_cnt = k.take<int>((size_t)c->max_batch * c->hmax);
   c->pick_val = k.take<float>((size_t)c->max_batch * (V / 16 + 1));
   c->pick_idx = k.take<int>((size_t)c->max_batch * (V / 16 + 1));
   return k.off;
@@ -320,11 +318,17 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
     max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
     max_rows = std::max(max_rows, sr.row_off[i + 1] - sr.row_off[i]);
   }
-  // keys per block (8 waves): 1024, i.e. one block per head and no global merge up to 1k context
-  // (measured: the device-scope fence of the split path costs more than it saves below that), more
-  // when that would exceed 16 splits
-  // With many (head, sequence) pairs the grid is full without splitting keys, whatever the length.
-  const int kps = (H * sr.n_seqs >= 128) ? (max_keys + 31) / 32 * 32 : std::max(1024, ((max_keys + 15) / 16 + 31) / 32 * 32);
+  // Keys per block (8 waves).  One block per (head, sequence) writes its output itself; splitting the keys
+  // over several blocks costs a merge launch.  Measured (32 heads, one sequence): no split wins up to 2k
+  // keys; beyond, blocks of 1024 keys or more, and never more blocks than CUs (544 blocks of 256 keys take
+  // twice as long as 160 blocks of 1024).
+  int kps = (max_keys + 31) / 32 * 32;
+  {
+    const int pairs = H * sr.n_seqs;
+    const int most = 256 / pairs;                               // splits that still leave one block per CU
+    if (most >= 2 && max_keys >= 2048) kps = std::max(1024, ((max_keys + most - 1) / most + 31) / 32 * 32);
+    kps = std::max(kps, ((max_keys + kMaxChunks - 1) / kMaxChunks + 31) / 32 * 32);   // the partial buffer holds kMaxChunks splits
+  }
   const int S = (max_keys + kps - 1) / kps;
   GemmArgs base{};
   base.R = R;
@@ -353,7 +357,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
     {
       const dim3 grid(S, H, sr.n_seqs);
       const _Float16* kv = static_cast<const _Float16*>(m.kv);
-#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), 0, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->att_cnt, c->xpB, mt_total)
+#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), 0, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total)
       if (tag == 0) {
         if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2, 2); else PACER_ATT(128, 1, 2); }
         else           { if (max_rows > 16) PACER_ATT(64, 2, 2); else PACER_ATT(64, 1, 2); }
@@ -362,6 +366,10 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
         else           { if (max_rows > 16) PACER_ATT(64, 2, 1); else PACER_ATT(64, 1, 1); }
       }
 #undef PACER_ATT
+      if (S > 1) {
+        if (hd == 128) hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(H, sr.n_seqs), dim3(256), 0, c->stream, c->part, sr, kps, S, H, c->xpB, mt_total);
+        else hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(H, sr.n_seqs), dim3(256), 0, c->stream, c->part, sr, kps, S, H, c->xpB, mt_total);
+      }
     }
     {
       GemmArgs ga = base;
@@ -711,7 +719,6 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
   void* dp = nullptr;
   HIPCHK(c, hipHostGetDevicePointer(&dp, hp, 0));
   c->host_res_dev = static_cast<int*>(dp);
-  HIPCHK(c, hipMemsetAsync(c->att_cnt, 0, sizeof(int) * c->max_batch * c->hmax, c->stream));   // tickets reset themselves afterwards
   c->ws_bound = true;
   return PACER_OK;
 }

@@ -44,6 +44,13 @@ _SHAPES = {
         draft=dict(n_layers=2, d_model=768, n_heads=12, head_dim=64, d_ffn=3072, vocab=32000),
         share_embed_head=False, dtype="bf16", block=4, gamma_max=16, beta=None,
         prompt=(256, 2048), new=256, mode="greedy", batch=16),
+    # a pair at the scale of the paper's larger experiments (Sec. 4.1: 1.3B draft, 33B target), where the
+    # draft step itself streams gigabytes: Llama-shaped, multi-head attention, 33.6 B and 1.35 B parameters
+    "33b": dict(
+        target=dict(n_layers=54, d_model=7168, n_heads=56, head_dim=128, d_ffn=19200, vocab=32256),
+        draft=dict(n_layers=24, d_model=2048, n_heads=16, head_dim=128, d_ffn=5504, vocab=32256),
+        share_embed_head=False, dtype="bf16", block=4, gamma_max=16, beta=3.0,
+        prompt=512, new=256, mode="sample"),
 }
 T0_DEFAULT = 0.5
 RHO_DEFAULT = 1.05
