@@ -15,7 +15,8 @@
 
 namespace {
 
-constexpr int kChunkRows = 32;       // rows per prefill chunk and per MFMA GEMM launch
+constexpr int kChunkRows = 32;       // rows of one sequence slot in a launch (two MFMA row tiles: what attention takes)
+constexpr int kPrefillRows = PK_MAXB * kChunkRows;   // a prompt goes through the models 512 rows at a time
 constexpr int kMaxChunks = 64;       // attention: key chunks per (head, sequence)
 constexpr int kProfEvents = 8192;
 
@@ -53,7 +54,7 @@ struct pacer_ctx {
   char err[256] = {0};
   // workspace carve-up
   bool ws_bound = false;
-  int G1 = 0, rcap = 0, dmax = 0, fmax = 0, kmax = 0, hmax = 0, hdmax = 0, max_seq = 0;
+  int G1 = 0, rcap = 0, prows = 0, dmax = 0, fmax = 0, kmax = 0, hmax = 0, hdmax = 0, max_seq = 0;   // prows: rows the attention partials hold
   int *tokens = nullptr, *draft_tok = nullptr, *rej = nullptr;
   float* acc_part = nullptr;   // acceptance: per (slot, row, vocabulary chunk) statistics and candidates
   float *ring = nullptr, *hidden = nullptr, *x = nullptr, *xn = nullptr, *qkv = nullptr, *ao = nullptr, *gu = nullptr,
@@ -133,10 +134,10 @@ size_t carve(pacer_ctx* c, void* base) {
   c->ao = k.take<float>((size_t)c->rcap * c->dmax);
   c->gu = k.take<float>((size_t)c->rcap * 2 * c->fmax);
   c->rope = k.take<float>((size_t)c->rcap * c->hdmax);
-  c->part = k.take<float>((size_t)c->rcap * c->hmax * kMaxChunks * (c->hdmax + 2));
+  c->part = k.take<float>((size_t)c->prows * c->hmax * kMaxChunks * (c->hdmax + 2));
   c->xpA = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);      // hi and lo tiles
   c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);
-  c->qp = k.take<_Float16>((size_t)c->max_batch * (c->dmax / 32) * 2 * 1024);
+  c->qp = k.take<_Float16>((size_t)PK_MAXB * (c->dmax / 32) * 2 * 1024);           // one slot per sequence slot of a launch
   c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * SSQ_SUB * c->rcap);
   c->pick_val = k.take<float>((size_t)c->max_batch * (V / 16 + 1));
   c->pick_idx = k.take<int>((size_t)c->max_batch * (V / 16 + 1));
@@ -326,7 +327,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
   {
     const int pairs = H * sr.n_seqs;
     const int most = 256 / pairs;                               // splits that still leave one block per CU
-    if (most >= 2 && max_keys >= 2048) kps = std::max(1024, ((max_keys + most - 1) / most + 31) / 32 * 32);
+    if (most >= 2 && max_keys >= 2048 && R <= c->prows) kps = std::max(1024, ((max_keys + most - 1) / most + 31) / 32 * 32);
     kps = std::max(kps, ((max_keys + kMaxChunks - 1) / kMaxChunks + 31) / 32 * 32);   // the partial buffer holds kMaxChunks splits
   }
   const int S = (max_keys + kps - 1) / kps;
@@ -598,7 +599,10 @@ int32_t pacer_create(pacer_ctx** out, const pacer_model_cfg* target, const pacer
   c->max_batch = max_batch;
   c->stream = static_cast<hipStream_t>(hip_stream);
   c->G1 = pv->gamma_max + 1;
-  c->rcap = std::max(kChunkRows, max_batch * c->G1);
+  c->rcap = std::max(kPrefillRows, max_batch * c->G1);
+  // attention partials: f32 models always go through them (all rows); bf16 models only when a decode
+  // launch splits its keys, never in the wide prefill chunks
+  c->prows = (target->dtype == PACER_F32 || draft->dtype == PACER_F32) ? c->rcap : std::max(kChunkRows, max_batch * c->G1);
   c->dmax = std::max(target->d_model, draft->d_model);
   c->fmax = std::max(target->d_ffn, draft->d_ffn);
   c->kmax = std::max(c->dmax, c->fmax);
@@ -732,15 +736,21 @@ int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_
   q = Seq();
   q.len = n;
   hipLaunchKernelGGL(copy_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->tokens + (size_t)s * c->max_seq, dev_tokens, n);
-  for (int p0 = 0; p0 < n - 1; p0 += kChunkRows) {
-    const int R = std::min(kChunkRows, n - 1 - p0);
+  // up to 16 slots of 32 consecutive positions per pass: one trip through the weights per 512 prompt tokens
+  for (int p0 = 0; p0 < n - 1; p0 += kPrefillRows) {
+    const int R = std::min(kPrefillRows, n - 1 - p0);
     SeqRows sr{};
-    sr.n_seqs = 1;
-    sr.seq[0] = s;
-    sr.row_off[0] = 0;
-    sr.row_off[1] = R;
-    sr.pos0[0] = p0;
-    sr.len[0] = n;
+    MbRows mr{};
+    sr.n_seqs = (R + kChunkRows - 1) / kChunkRows;
+    for (int i = 0; i < sr.n_seqs; ++i) {
+      sr.seq[i] = s;
+      sr.row_off[i] = i * kChunkRows;
+      sr.pos0[i] = p0 + i * kChunkRows;
+      sr.len[i] = n;
+      mr.src_row0[i] = i * kChunkRows;
+      mr.e0[i] = -1;
+    }
+    sr.row_off[sr.n_seqs] = R;
     forward_lm(c, c->m[PACER_TARGET], 0, R, sr);
     const Model& md = c->m[PACER_DRAFT];
     forward_lm(c, md, 1, R, sr);
@@ -751,9 +761,6 @@ int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_
     else
       (void)hipMemcpy2DAsync(c->ao, (size_t)c->dmax * 4, c->xn, (size_t)c->kmax * 4, (size_t)md.cfg.d_model * 4, R, hipMemcpyDeviceToDevice,
                              c->stream);
-    MbRows mr{};
-    mr.src_row0[0] = 0;
-    mr.e0[0] = -1;
     run_preverify_rows(c, R, sr, mr, c->ao, c->dmax, true);
   }
   HIPCHK(c, hipGetLastError());
