@@ -620,24 +620,16 @@ __global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(
 //   values  O^T[dim][row] += V^T[dim][keys] P^T[keys][row]; the probabilities leave the first MFMA in
 //           exactly the lane layout the second one wants for B (contraction index = the 8 keys a lane
 //           holds), and V^T rows are contiguous along keys.
-// The 8 wave states are merged pairwise through LDS (same lane layout on both sides, so no transposition).
+// The 8 wave states meet in LDS (dynamic, 8 x live rows x (HD + 4) floats) and are combined in one pass.
 // With one split the block writes the f16 operand of the O projection directly; with several, each block
 // writes a partial and attn_merge_kernel combines them.
-struct AttnState { float m, l; };
-__device__ __forceinline__ void merge_w(float m1, float m2, float& M, float& w1, float& w2) {
-  M = fmaxf(m1, m2);
-  w1 = (m1 == -INFINITY) ? 0.f : expf(m1 - M);
-  w2 = (m2 == -INFINITY) ? 0.f : expf(m2 - M);
-}
-
 // QL = 2: the query operand is used as hi + lo (target model), 1: hi only.
 template <int HD, int MT, int QL>
 __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restrict__ qp, const _Float16* __restrict__ kv, int layer,
                                                         int n_layers, int max_seq, int d, SeqRows sr, int kps, int S, int H,
                                                         float* __restrict__ part, _Float16* __restrict__ xp_out, int MT_total_out) {
   constexpr int KTS = HD / 32, DTS = HD / 16, NW = 8;
-  __shared__ f32x4 sacc[NW / 2][DTS][64];
-  __shared__ float sm[NW / 2][64], sl[NW / 2][64];
+  extern __shared__ __align__(16) float att_state[];   // [8 waves][live rows][HD + 4]: values, running max, running sum
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
   const int split = blockIdx.x, h = blockIdx.y, si = blockIdx.z;
   const int r0 = sr.row_off[si], Rs = sr.row_off[si + 1] - r0, pos0 = sr.pos0[si];
@@ -763,59 +755,46 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
     }
   }
 
-  // pairwise merge of the 8 wave states (waves s..2s-1 hand theirs to waves 0..s-1)
+  // Merge of the 8 wave states: every wave writes its live rows (values, running max, running sum) to LDS
+  // once, then each thread combines the 8 states of one (row, 4 dims) group and writes the result.  One
+  // barrier (a pairwise tree over the MFMA tiles took six per row tile and 1.4 to 4 us).
+  const int rcap = min(Rs, MT * 16);
+  float* st = att_state;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
+    const int rl = mt * 16 + j;
+    if (rl < rcap) {
+      float* o = st + (size_t)(wave * rcap + rl) * (HD + 4);
 #pragma unroll
-    for (int stride = NW / 2; stride >= 1; stride >>= 1) {
-      if (wave >= stride && wave < 2 * stride) {
-        const int w = wave - stride;
-        sm[w][lane] = mrun[mt];
-        sl[w][lane] = lrun[mt];
-#pragma unroll
-        for (int dt = 0; dt < DTS; ++dt) sacc[w][dt][lane] = acc[dt][mt];
-      }
-      __syncthreads();
-      if (wave < stride) {
-        float M, w1, w2;
-        merge_w(mrun[mt], sm[wave][lane], M, w1, w2);
-        lrun[mt] = lrun[mt] * w1 + sl[wave][lane] * w2;
-        mrun[mt] = M;
-#pragma unroll
-        for (int dt = 0; dt < DTS; ++dt) acc[dt][mt] = acc[dt][mt] * w1 + sacc[wave][dt][lane] * w2;
-      }
-      __syncthreads();
+      for (int dt = 0; dt < DTS; ++dt) *reinterpret_cast<f32x4*>(o + dt * 16 + 4 * g) = acc[dt][mt];
+      if (g == 0) { o[HD] = mrun[mt]; o[HD + 1] = lrun[mt]; }
     }
   }
-
-  if (n_split == 1) {
-    if (wave == 0) {
+  __syncthreads();
+  for (int o4 = threadIdx.x; o4 < rcap * (HD / 4); o4 += NW * 64) {
+    const int rl = o4 / (HD / 4), d4 = (o4 % (HD / 4)) * 4;
+    const float* p = st + (size_t)rl * (HD + 4);
+    float M = -INFINITY;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int rl = mt * 16 + j;
-        if (rl < Rs) {
-          const float inv = 1.0f / lrun[mt];
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, p[(size_t)w * rcap * (HD + 4) + HD]);
+    float L = 0.f;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int dt = 0; dt < DTS; ++dt) {
-            const f32x4 o = acc[dt][mt] * inv;
-            store_packed4(xp_out, MT_total_out, r0 + rl, h * HD + dt * 16 + 4 * g, o[0], o[1], o[2], o[3]);
-          }
-        }
-      }
+    for (int w = 0; w < NW; ++w) {
+      const float* pw = p + (size_t)w * rcap * (HD + 4);
+      const float m = pw[HD];
+      const float wt = (m == -INFINITY) ? 0.f : expf(m - M);
+      L += pw[HD + 1] * wt;
+      a += *reinterpret_cast<const f32x4*>(pw + d4) * wt;
     }
-    return;
-  }
-  // several splits: un-normalised partial (values, running max, running sum) for attn_merge_kernel
-  if (wave == 0) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int rl = mt * 16 + j;
-      if (rl < Rs) {
-        float* o = part + (((size_t)(r0 + rl) * H + h) * S + split) * (HD + 2);
-#pragma unroll
-        for (int dt = 0; dt < DTS; ++dt) *reinterpret_cast<f32x4*>(o + dt * 16 + 4 * g) = acc[dt][mt];
-        if (g == 0) { o[HD] = mrun[mt]; o[HD + 1] = lrun[mt]; }
-      }
+    if (n_split == 1) {
+      const float inv = 1.0f / L;
+      store_packed4(xp_out, MT_total_out, r0 + rl, h * HD + d4, a[0] * inv, a[1] * inv, a[2] * inv, a[3] * inv);
+    } else {
+      // several splits: un-normalised partial (values, running max, running sum) for attn_merge_kernel
+      float* o = part + (((size_t)(r0 + rl) * H + h) * S + split) * (HD + 2);
+      o[d4] = a[0]; o[d4 + 1] = a[1]; o[d4 + 2] = a[2]; o[d4 + 3] = a[3];
+      if (d4 == 0) { o[HD] = M; o[HD + 1] = L; }
     }
   }
 }

@@ -358,7 +358,8 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
     {
       const dim3 grid(S, H, sr.n_seqs);
       const _Float16* kv = static_cast<const _Float16*>(m.kv);
-#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), 0, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total)
+      // LDS for the wave states: 8 waves x live rows x (hd + 4) floats
+#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), (size_t)8 * std::min(max_rows, MT_ * 16) * (HD_ + 4) * 4, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total)
       if (tag == 0) {
         if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2, 2); else PACER_ATT(128, 1, 2); }
         else           { if (max_rows > 16) PACER_ATT(64, 2, 2); else PACER_ATT(64, 1, 2); }
@@ -723,6 +724,14 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
   void* dp = nullptr;
   HIPCHK(c, hipHostGetDevicePointer(&dp, hp, 0));
   c->host_res_dev = static_cast<int*>(dp);
+  // attention keeps its 8 wave states in dynamic LDS: up to 8 x 32 rows x 132 floats = 132 KiB of the CU's 160
+  {
+    const int lds_max = 8 * 32 * (128 + 4) * 4;
+#define PACER_ATT_LDS(HD_, MT_, QL_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<HD_, MT_, QL_>), hipFuncAttributeMaxDynamicSharedMemorySize, lds_max))
+    PACER_ATT_LDS(128, 2, 2); PACER_ATT_LDS(128, 1, 2); PACER_ATT_LDS(64, 2, 2); PACER_ATT_LDS(64, 1, 2);
+    PACER_ATT_LDS(128, 2, 1); PACER_ATT_LDS(128, 1, 1); PACER_ATT_LDS(64, 2, 1); PACER_ATT_LDS(64, 1, 1);
+#undef PACER_ATT_LDS
+  }
   c->ws_bound = true;
   return PACER_OK;
 }
