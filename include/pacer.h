@@ -137,7 +137,8 @@ int32_t pacer_bind_workspace(pacer_ctx* ctx, void* dev_ptr, uint64_t nbytes);
 
 /* Prompt ingestion (support; Alg. 1 takes the prefix as given).  Resets sequence `seq` to the
  * committed tokens dev_tokens[0..n-1], n >= 1, and fills the three caches for positions
- * 0..n-2 (M_B with prefix rows). */
+ * 0..n-2 (M_B with prefix rows), 512 positions per pass through the weights.  The workspace
+ * is sized for such a pass whatever max_batch is. */
 int32_t pacer_prefill(pacer_ctx* ctx, int32_t seq, const int32_t* dev_tokens, int32_t n);
 
 /* Debug / teacher forcing: replace the committed tokens of `seq` from position `from` on with
