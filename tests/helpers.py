@@ -28,6 +28,8 @@ class LazyF64:
 
 def to_oracle(w, cache=False):
     """cache=True keeps the float64 copies (8 bytes per weight): small and mid models only."""
+    if isinstance(w, LazyF64):          # already converted (several oracles sharing one set of float64 copies)
+        return w
     if isinstance(w, dict):
         return {k: to_oracle(v, cache) for k, v in w.items()}
     if isinstance(w, list):

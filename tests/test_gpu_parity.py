@@ -108,9 +108,10 @@ def _run_batch(name, prompt_lens, betas, n_steps, tol_logits, tol_alpha, mode=po
     nb = len(prompt_lens)
     s = _session(w, tgt, drf, mb, max_seq, max_batch=nb)
     cks = []
+    ow = [helpers.to_oracle(m, cache=True) for m in (tgt, drf, mb)]      # one set of float64 copies for all oracles
     for i, (pl, beta) in enumerate(zip(prompt_lens, betas)):
         prompt = synth.make_prompt(w["target"]["vocab"], pl, 10 + i).tolist()
-        o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=seed, max_seq=max_seq, cache=True, seq=i, beta=beta)
+        o = helpers.build_oracle(w, ow[0], ow[1], ow[2], mode=mode, seed=seed, max_seq=max_seq, cache=True, seq=i, beta=beta)
         s.prefill(prompt, seq=i)
         o.prefill(prompt)
         cks.append(StepChecker(s, o, tol_logits, tol_alpha, mode=mode, seed=seed, seq=i))
@@ -146,6 +147,72 @@ def test_batch_mid_bf16_eight_sequences_wide_gemm():
     """8 sequences x up to 13 verify rows = up to 104 rows: the wide GEMM with several row groups per
     output-tile group, ragged last row tile, per-sequence attention over different lengths."""
     _run_batch("mid", [40, 75, 150, 260, 33, 97, 201, 64], [1.0, 2.3, 3.7, 5.0, 4.0, 3.0, 2.0, 4.5], 4, 2e-2, 2e-2)
+
+
+def test_13b_width_four_layers_batch_against_oracle():
+    """BASELINE config 5's shapes (d 5120, 40 heads of 128, FFN 13824, V 32000) at a depth the oracle can
+    afford, 6 sequences, ragged prompts and windows, per-sequence beta: up to 102 verify rows through the
+    wide GEMM at the widths bench.py times (K 5120 and 13824, 960 / 320 / 1728 / 2000 output tiles)."""
+    _run_batch("13b_batch", [18, 33, 47, 25, 60, 39], [1.0, 2.0, 3.0, 4.0, 5.0, 2.5], 2, 2e-2, 2e-2, max_seq=160,
+               n_layers_target=4)
+
+
+def test_33b_width_two_layers_bf16():
+    """Shapes of the large pair (target d 7168, 56 heads of 128, FFN 19200, V 32256; 24-layer d 2048
+    draft with 128-wide heads): tile counts and K lengths none of the other tests has."""
+    _run("33b", 40, 10, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2, max_seq=128, w_over=dict(mode="greedy"))
+
+
+def test_13b_batch_full_depth_batch_invariance():
+    """BASELINE config 5 at full size (40 layers, 16 sequences) in the launch configuration bench.py
+    times.  Property that holds at any size: a sequence verified inside the ragged batch (wide GEMM,
+    rows of 16 sequences) gets the logits and decisions it gets when stepped alone (weight-streaming
+    GEMM) from the same state."""
+    w = synth.workload("13b_batch")
+    tgt, drf, mb = synth.make_pair(w, seed=0, device="cuda")
+    nb = 16
+    s = _session(w, tgt, drf, mb, 256, max_batch=nb)
+    del tgt, drf, mb
+    torch.cuda.empty_cache()
+    lens = synth.make_lengths(20, 150, nb, 4)
+    betas = synth.make_betas(1.0, 5.0, nb, 5)
+    prompts = [synth.make_prompt(32000, n, 30 + i).tolist() for i, n in enumerate(lens)]
+
+    def fresh():
+        for i, p in enumerate(prompts):
+            s.prefill(p, seq=i)
+        s.step_idx = [0] * nb
+
+    fresh()
+    batched = s.step_batch(list(range(nb)), betas=betas, record=True)
+    rows = sum(r["gamma"] + 1 for r in batched)
+    assert rows > 32                                            # the wide kernel really ran
+    fresh()
+    worst = 0.0
+    for i in (0, 5, 10, 15):
+        solo = s.step_batch([i], betas=[betas[i]], record=True)[0]
+        b = batched[i]
+        g = min(solo["gamma"], b["gamma"])
+        assert solo["draft_tokens"][:g] == b["draft_tokens"][:g]
+        if solo["gamma"] != b["gamma"]:
+            # the pre-verification layer ran 64 rows through the wide GEMM in the batch and 4 rows through the
+            # streaming one alone: a different window is allowed only at a near-tie of the block mean
+            k = g // w["block"] - 1
+            mean = float(np.mean(b["alpha"][k * w["block"]:(k + 1) * w["block"]]))
+            assert abs(mean - w["t0"] * w["rho"] ** k) < 2e-3, (i, solo["gamma"], b["gamma"], mean)
+            continue
+        ls, lb = solo["target_logits"].double(), b["target_logits"].double()
+        err = ((ls - lb).abs().amax(dim=1) / lb.pow(2).mean(dim=1).sqrt()).max().item()
+        worst = max(worst, err)
+        if (solo["n"], solo["z"]) != (b["n"], b["z"]):
+            # allowed only at a near-tie of the deciding row's top two effective logits
+            k = min(solo["n"], b["n"])
+            eff = (lb[k] + betas[i] * b["draft_logits"][k].double()).cpu().numpy()
+            top = np.sort(eff)[-2:]
+            assert top[1] - top[0] < 2e-2 * np.sqrt(np.mean(eff ** 2)), (i, solo["n"], b["n"], top)
+    print(f"\n[13b_batch full depth] rows={rows} batched vs solo logits max err {worst:.2e}")
+    assert worst < 5e-3
+    s.close()
 
 
 def _host_copy(x):
