@@ -44,7 +44,7 @@ def _run(name, n_prompt, n_new, tol_logits, tol_alpha, mode=po.GREEDY, seed=0, g
 
 
 def test_tiny_f32_greedy_steps_match_oracle():
-    """BASELINE config 1: tiny f32 pair, 32-token prompt, 64 new tokens, greedy, gamma_max 8, b 2."""
+    """Workload `tiny`: f32 pair, 32-token prompt, 64 new tokens, greedy, gamma_max 8, b 2."""
     ck, gammas, ns = _run("tiny", 32, 64, tol_logits=1e-4, tol_alpha=1e-4)
     assert len(set(gammas)) > 1          # the window really adapts
     assert 0 < np.mean(ns) < np.mean(gammas)
@@ -75,7 +75,7 @@ def test_halting_variants_any_and_last():
 
 
 def test_mid_bf16_greedy_steps_match_oracle():
-    """BASELINE config 2 shapes (12-layer d768 V32000 target, 2-layer draft, bf16, b 4, gamma_max 12);
+    """Workload `mid` (12-layer d768 V32000 target, 2-layer draft, bf16, b 4, gamma_max 12);
     the context crosses several 64-key attention tiles."""
     _run("mid", 150, 40, tol_logits=2e-2, tol_alpha=2e-2)
 
@@ -138,7 +138,7 @@ def test_batch_tiny_f32_ragged():
 
 
 def test_batch_mid_bf16_ragged():
-    """BASELINE config 5 in miniature: ragged batch, per-sequence beta in [1, 5], prompt lengths
+    """The batched workload in miniature: ragged batch, per-sequence beta in [1, 5], prompt lengths
     spread over several attention tiles; 4 sequences x up to 13 verify rows = two 32-row GEMM chunks."""
     _run_batch("mid", [40, 75, 150, 260], [1.0, 2.3, 3.7, 5.0], 6, 2e-2, 2e-2)
 
@@ -150,7 +150,7 @@ def test_batch_mid_bf16_eight_sequences_wide_gemm():
 
 
 def test_13b_width_four_layers_batch_against_oracle():
-    """BASELINE config 5's shapes (d 5120, 40 heads of 128, FFN 13824, V 32000) at a depth the oracle can
+    """The shapes of workload `13b_batch` (d 5120, 40 heads of 128, FFN 13824, V 32000) at a depth the oracle can
     afford, 6 sequences, ragged prompts and windows, per-sequence beta: up to 102 verify rows through the
     wide GEMM at the widths bench.py times (K 5120 and 13824, 960 / 320 / 1728 / 2000 output tiles)."""
     _run_batch("13b_batch", [18, 33, 47, 25, 60, 39], [1.0, 2.0, 3.0, 4.0, 5.0, 2.5], 2, 2e-2, 2e-2, max_seq=160,
@@ -164,7 +164,7 @@ def test_33b_width_two_layers_bf16():
 
 
 def test_13b_batch_full_depth_batch_invariance():
-    """BASELINE config 5 at full size (40 layers, 16 sequences) in the launch configuration bench.py
+    """Workload `13b_batch` at full size (40 layers, 16 sequences) in the launch configuration bench.py
     times.  Property that holds at any size: a sequence verified inside the ragged batch (wide GEMM,
     rows of 16 sequences) gets the logits and decisions it gets when stepped alone (weight-streaming
     GEMM) from the same state."""
@@ -224,7 +224,7 @@ def _host_copy(x):
 
 
 def test_7b_full_depth_against_oracle_and_losslessness():
-    """BASELINE config 3 at full size (32 layers, d 4096, FFN 11008, V 32000; 68M-shaped draft), in
+    """Workload `7b` (the headline configuration) at full size (32 layers, d 4096, FFN 11008, V 32000; 68M-shaped draft), in
     the launch configuration bench.py times (weights generated on the device, gamma_max 16, b 4,
     beta 3).  (i) Two Pacer steps after a short prompt are compared with the oracle row by row
     (every logit of every verify row).  (ii) Property that holds at any size: greedy speculative
