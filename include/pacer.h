@@ -173,6 +173,15 @@ int32_t pacer_draft_step(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, in
 int32_t pacer_preverify_block(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs,
                               float* dev_alpha, int32_t* dev_stop);
 
+/* The stop flags of the last pacer_preverify_block of each listed sequence, as host values:
+ * host_stop[n_seqs] (host array).  The kernel also writes each flag, tagged with the number of
+ * the call, to pinned host memory; this call polls those words, which takes a few microseconds
+ * after the kernel has finished where a stream synchronisation plus a device-to-host copy takes
+ * tens.  It waits for that kernel only, not for the stream.  This is what decides whether
+ * drafting goes on (Alg. 1, the stop test of the inner loop).  PACER_ESTATE if a listed sequence
+ * has had no pre-verification call since its prefill. */
+int32_t pacer_wait_stop(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, int32_t* host_stop);
+
 /* Eq. 4: one target pass over [last committed token, y_1..y_gamma] of each listed sequence
  * against its KV cache (appending those rows).  gamma = number of drafts since
  * pacer_begin_step, or gamma_override[s] if gamma_override != NULL and >= 0 (host array; must
@@ -197,8 +206,9 @@ int32_t pacer_accept_rollback(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seq
                               const float* dev_logits, int32_t* dev_n_accepted,
                               int32_t* dev_next_token);
 
-/* Synchronises the stream, folds a pending accept result into the host-side state and
- * reports: gamma (drafts of the current/last step), len (committed tokens), t (current
+/* Waits for the sequence's pending pacer_accept_rollback, if any (by polling the pinned host
+ * words its last kernel writes; it does not synchronise the stream), folds the result into the
+ * host-side state and reports: gamma (drafts of the current/last step), len (committed tokens), t (current
  * threshold), n_accepted / next_token of the last finished step (-1 if none).  Any output
  * pointer may be NULL. */
 int32_t pacer_get_state(pacer_ctx* ctx, int32_t seq, int32_t* gamma, int32_t* len, float* t,

@@ -26,7 +26,7 @@ EXPORTS = [
     "pacer_create", "pacer_destroy", "pacer_last_error", "pacer_pack_weight", "pacer_bind",
     "pacer_kv_bytes", "pacer_bind_kv", "pacer_workspace_bytes", "pacer_bind_workspace",
     "pacer_prefill", "pacer_force_commit", "pacer_begin_step", "pacer_draft_step",
-    "pacer_preverify_block", "pacer_verify", "pacer_accept_rollback", "pacer_get_state",
+    "pacer_preverify_block", "pacer_wait_stop", "pacer_verify", "pacer_accept_rollback", "pacer_get_state",
     "pacer_peek", "pacer_profile_enable", "pacer_profile_read",
 ]
 
@@ -69,6 +69,7 @@ def _load():
         "pacer_begin_step": (i32, [vp, i32]),
         "pacer_draft_step": (i32, [vp, C.POINTER(i32), i32, i32, u64, u64]),
         "pacer_preverify_block": (i32, [vp, C.POINTER(i32), i32, vp, vp]),
+        "pacer_wait_stop": (i32, [vp, C.POINTER(i32), i32, C.POINTER(i32)]),
         "pacer_verify": (i32, [vp, C.POINTER(i32), i32, C.POINTER(i32), vp]),
         "pacer_accept_rollback": (i32, [vp, C.POINTER(i32), i32, i32, C.POINTER(C.c_float), u64, u64, vp, vp, vp]),
         "pacer_get_state": (i32, [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(i32), C.POINTER(i32)]),
@@ -163,6 +164,12 @@ def pacer_draft_step(ctx, seqs, mode, rng_seed, rng_ctr):
 
 def pacer_preverify_block(ctx, seqs, dev_alpha, dev_stop):
     _chk(ctx, _lib.pacer_preverify_block(ctx, _i32s(seqs), len(seqs), _ptr(dev_alpha), _ptr(dev_stop)))
+
+
+def pacer_wait_stop(ctx, seqs):
+    out = (C.c_int32 * len(seqs))()
+    _chk(ctx, _lib.pacer_wait_stop(ctx, _i32s(seqs), len(seqs), out))
+    return list(out)
 
 
 def pacer_verify(ctx, seqs, gamma_override, dev_logits):

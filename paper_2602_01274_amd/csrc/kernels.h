@@ -500,7 +500,9 @@ __global__ __launch_bounds__(1024) void pick_token_kernel(const float* __restric
 // ------------------------------------------------------------------ pre-verification head + halting test
 // xn: final-norm output of M_B, rows grouped per sequence (b rows each).  alpha_j = softmax(z)[1]
 // = 1/(1+exp(z0-z1)); stop = (mean alpha <= t) with the mean summed in index order in f32.
-struct HaltArgs { int n_seqs; int rule; float t[PK_MAXB]; };   // rule: 0 mean, 1 any, 2 last
+// rule: 0 mean, 1 any, 2 last.  seq/ticket: the stop flag also goes to pinned host memory as
+// host_stop[seq] = ticket*2 + stop, which the host polls instead of synchronising the stream.
+struct HaltArgs { int n_seqs; int rule; float t[PK_MAXB]; int seq[PK_MAXB]; int ticket[PK_MAXB]; };
 // the halting test of one block, decided in f32 (al: the block's alpha values in index order)
 __device__ __forceinline__ int halt_decision(const float* al, int b, float t, int rule) {
   if (rule == 1) {
@@ -514,7 +516,7 @@ __device__ __forceinline__ int halt_decision(const float* al, int b, float t, in
   return (s / (float)b <= t) ? 1 : 0;
 }
 __global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const float* __restrict__ cls, int d, int b, HaltArgs ha,
-                               float* __restrict__ alpha, int* __restrict__ stop) {
+                               float* __restrict__ alpha, int* __restrict__ stop, int* __restrict__ host_stop) {
   __shared__ float al[32];
   const int si = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
   for (int j = wv; j < b; j += nw) {
@@ -527,7 +529,9 @@ __global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const floa
   __syncthreads();
   if (threadIdx.x == 0) {
     for (int j = 0; j < b; ++j) alpha[si * b + j] = al[j];
-    stop[si] = halt_decision(al, b, ha.t[si], ha.rule);
+    const int st = halt_decision(al, b, ha.t[si], ha.rule);
+    stop[si] = st;
+    host_stop[ha.seq[si]] = ha.ticket[si] * 2 + st;
   }
 }
 
@@ -662,7 +666,7 @@ __global__ __launch_bounds__(256) void accept_rows_kernel(const float* __restric
 // n = first rejected row (or gamma); next token = that row's candidate; append to committed tokens
 __global__ void accept_finalize_kernel(const float* __restrict__ part, const int* __restrict__ rej, const int* __restrict__ draft_tok,
                                        AccArgs aa, int G1, int mode, int max_seq, int* __restrict__ tokens, int* __restrict__ out_n,
-                                       int* __restrict__ out_z, int* __restrict__ host_res) {
+                                       int* __restrict__ out_z, int* __restrict__ host_res, int* __restrict__ host_tick, int ticket) {
   const int si = blockIdx.x, s = aa.seq[si];
   const int gamma = aa.gamma[si];
   int n = gamma;
@@ -702,6 +706,8 @@ __global__ void accept_finalize_kernel(const float* __restrict__ part, const int
     out_z[si] = z;
     host_res[2 * s] = n;
     host_res[2 * s + 1] = z;
+    __threadfence_system();            // the results first, then the ticket the host polls for
+    host_tick[s] = ticket;
   }
 }
 

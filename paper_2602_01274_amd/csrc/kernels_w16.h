@@ -856,7 +856,7 @@ __global__ void draft_tail_kernel(const float* __restrict__ x, int ldx, const fl
 // pre-verification head on the un-normalised residual rows: z = (x*g*rs) . cls
 __global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
                                    int ssq_stride, float inv_dim, float eps, const float* __restrict__ cls, int d, int b, HaltArgs ha,
-                                   float* __restrict__ alpha, int* __restrict__ stop) {
+                                   float* __restrict__ alpha, int* __restrict__ stop, int* __restrict__ host_stop) {
   __shared__ float al[32];
   const int si = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
   for (int jj = wv; jj < b; jj += nw) {
@@ -876,6 +876,8 @@ __global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const f
   __syncthreads();
   if (threadIdx.x == 0) {
     for (int jj = 0; jj < b; ++jj) alpha[si * b + jj] = al[jj];
-    stop[si] = halt_decision(al, b, ha.t[si], ha.rule);
+    const int st = halt_decision(al, b, ha.t[si], ha.rule);
+    stop[si] = st;
+    host_stop[ha.seq[si]] = ha.ticket[si] * 2 + st;
   }
 }

@@ -6,6 +6,7 @@
 #include "kernels_w16.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -41,6 +42,8 @@ struct Seq {
   bool pending = false;
   bool in_step = false;
   int last_n = -1, last_z = -1;
+  int pv_ticket = 0;   // number of the last pre-verification call that covered this sequence (the kernel echoes it next to the stop flag)
+  int acc_ticket = 0;  // number of the last accept call that covered it
 };
 
 }  // namespace
@@ -64,8 +67,11 @@ struct pacer_ctx {
   float* pick_val = nullptr;                                  // bf16 path: per (row, vocab tile) token candidates
   int* pick_idx = nullptr;
   int lmax = 0;
-  int* host_res = nullptr;      // pinned host memory [max_batch][2]
+  // pinned host memory the kernels write and the host polls: [0..31] (n, z) per sequence, [32..47] accept
+  // tickets, [48..63] stop flags with their tickets
+  int* host_res = nullptr;
   int* host_res_dev = nullptr;  // its device alias
+  int pv_calls = 0, acc_calls = 0;
   // profiling of the GEMM kernel
   bool prof = false;
   std::vector<hipEvent_t> ev;
@@ -512,9 +518,10 @@ void preverify_head(pacer_ctx* c, int n, int b, const HaltArgs& ha, float* dev_a
   const Model& mb = c->m[PACER_PREVERIFY];
   if (is_w16(mb))
     hipLaunchKernelGGL(mb_head_w16_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, mb.final_norm, slot(c, 2), c->rcap, 1.0f / mb.cfg.d_model,
-                       mb.cfg.rms_eps, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop);
+                       mb.cfg.rms_eps, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop, c->host_res_dev + 3 * PACER_MAX_BATCH);
   else
-    hipLaunchKernelGGL(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop);
+    hipLaunchKernelGGL(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop,
+                       c->host_res_dev + 3 * PACER_MAX_BATCH);
 }
 
 // one draft forward at draft index j[s] (0-based) for each listed sequence; logits and hidden
@@ -550,13 +557,29 @@ void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int m
   }
 }
 
+// Waits until the kernel-written word *p (pinned host memory) carries `ticket` (in its bits above `shift`).
+// Polling costs a few microseconds where hipStreamSynchronize costs twenty to thirty; if the word does not
+// arrive within the spin budget the stream is synchronised and the word checked once more.
+int wait_ticket(pacer_ctx* c, const int* p, int ticket, int shift) {
+  const volatile int* v = p;
+  for (long spin = 0; spin < 200000000L; ++spin) {
+    if ((*v >> shift) == ticket) { std::atomic_thread_fence(std::memory_order_acquire); return PACER_OK; }
+    if ((spin & 1023) == 1023 && hipStreamQuery(c->stream) == hipSuccess) break;   // stream drained: the word is final
+  }
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if ((*v >> shift) == ticket) return PACER_OK;
+  return fail(c, PACER_EHIP, "a kernel's result did not reach host memory (ticket %d, found %d)", ticket, *v >> shift);
+}
+
 int fold(pacer_ctx* c, int s) {
   Seq& q = c->seq[s];
   if (!q.pending) return PACER_OK;
-  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (int rc = wait_ticket(c, c->host_res + 2 * PACER_MAX_BATCH + s, q.acc_ticket, 0)) return rc;
   for (int i = 0; i < c->max_batch; ++i) {
     Seq& o = c->seq[i];
     if (!o.pending) continue;
+    // sequences of the same accept call carry the same ticket and were written by the same launch
+    if (int rc = wait_ticket(c, c->host_res + 2 * PACER_MAX_BATCH + i, o.acc_ticket, 0)) return rc;
     o.last_n = c->host_res[2 * i];
     o.last_z = c->host_res[2 * i + 1];
     o.len += o.last_n + 1;
@@ -719,8 +742,9 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
   if (c->ws_bound) return fail(c, PACER_ESTATE, "workspace already bound");
   carve(c, p);
   void* hp = nullptr;
-  HIPCHK(c, hipHostMalloc(&hp, sizeof(int) * 2 * PACER_MAX_BATCH, hipHostMallocMapped));
+  HIPCHK(c, hipHostMalloc(&hp, sizeof(int) * 4 * PACER_MAX_BATCH, hipHostMallocMapped));
   c->host_res = static_cast<int*>(hp);
+  for (int i = 0; i < 4 * PACER_MAX_BATCH; ++i) c->host_res[i] = 0;
   void* dp = nullptr;
   HIPCHK(c, hipHostGetDevicePointer(&dp, hp, 0));
   c->host_res_dev = static_cast<int*>(dp);
@@ -850,7 +874,10 @@ int32_t pacer_preverify_block(pacer_ctx* c, const int32_t* seqs, int32_t n, floa
     mr.src_row0[i] = seqs[i] * c->G1 + q.mb_done;
     mr.e0[i] = q.mb_done + 1;                 // draft positions i, i+1, ... (1-based)
     ha.t[i] = q.t;
+    ha.seq[i] = seqs[i];
+    ha.ticket[i] = q.pv_ticket = c->pv_calls + 1;   // per context, never reused: a re-prefilled sequence cannot match a stale word
   }
+  ++c->pv_calls;
   sr.row_off[n] = n * b;
   const Model& mb = c->m[PACER_PREVERIFY];
   run_preverify_rows(c, n * b, sr, mr, c->hidden, mb.cfg.d_model, false);
@@ -861,6 +888,21 @@ int32_t pacer_preverify_block(pacer_ctx* c, const int32_t* seqs, int32_t n, floa
     q.t = q.t * c->pv.rho;
   }
   HIPCHK(c, hipGetLastError());
+  return PACER_OK;
+}
+
+int32_t pacer_wait_stop(pacer_ctx* c, const int32_t* seqs, int32_t n, int32_t* host_stop) {
+  if (!c) return PACER_EINVAL;
+  if (int rc = ready(c)) return rc;
+  if (int rc = check_seqs(c, seqs, n)) return rc;
+  if (!host_stop) return fail(c, PACER_EINVAL, "wait_stop: null output");
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = c->seq[seqs[i]];
+    if (q.pv_ticket == 0) return fail(c, PACER_ESTATE, "wait_stop: sequence %d has had no pre-verification call", seqs[i]);
+    const int* p = c->host_res + 3 * PACER_MAX_BATCH + seqs[i];
+    if (int rc = wait_ticket(c, p, q.pv_ticket, 1)) return rc;
+    host_stop[i] = *p & 1;
+  }
   return PACER_OK;
 }
 
@@ -950,9 +992,10 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
   hipLaunchKernelGGL(accept_rows_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode, seed,
                      (uint32_t)ctr, c->acc_part, c->rej);
   hipLaunchKernelGGL(accept_finalize_kernel, dim3(n), dim3(64), 0, c->stream, c->acc_part, c->rej, c->draft_tok, aa, c->G1, mode,
-                     c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev);
+                     c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev, c->host_res_dev + 2 * PACER_MAX_BATCH, ++c->acc_calls);
   for (int i = 0; i < n; ++i) {
     Seq& q = c->seq[seqs[i]];
+    q.acc_ticket = c->acc_calls;
     q.pending = true;
     q.in_step = false;
   }
@@ -965,7 +1008,6 @@ int32_t pacer_get_state(pacer_ctx* c, int32_t s, int32_t* gamma, int32_t* len, f
   if (s < 0 || s >= c->max_batch) return fail(c, PACER_EINVAL, "get_state: sequence id %d out of range", s);
   if (c->ws_bound) {
     if (int rc = fold(c, s)) return rc;
-    HIPCHK(c, hipStreamSynchronize(c->stream));
   }
   const Seq& q = c->seq[s];
   if (gamma) *gamma = q.gamma;

