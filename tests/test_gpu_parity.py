@@ -137,6 +137,12 @@ def test_batch_tiny_f32_ragged():
     _run_batch("tiny", [9, 64], [4.0, 3.0], 8, 1e-4, 1e-4, mode=po.SAMPLE)
 
 
+def test_batch_tiny_f32_sixteen_sequences():
+    """The largest batch the library takes (16 sequences), f32 path, ragged prompts from 1 token up."""
+    _run_batch("tiny", [1, 2, 3, 5, 8, 13, 21, 34, 55, 89, 4, 6, 10, 16, 26, 42],
+               [4.0, 1.0, 2.5, 3.0, 0.0, 4.5, 2.0, 3.5, 1.5, 5.0, 4.0, 0.5, 2.5, 3.0, 1.0, 4.0], 4, 1e-4, 1e-4, max_seq=256)
+
+
 def test_batch_mid_bf16_ragged():
     """The batched workload in miniature: ragged batch, per-sequence beta in [1, 5], prompt lengths
     spread over several attention tiles; 4 sequences x up to 13 verify rows = two 32-row GEMM chunks."""
