@@ -494,7 +494,7 @@ template <int EPI, int NTW, int MTB, int HL, int TAG, int KS>
 __global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(const GemmArgs ga, int n_tiles, int n_groups, int row_groups) {
   constexpr int UA = 4, KC = UA / KS, BT = MTB * HL, BI = (BT + 3) / 4;
   __shared__ u32x4 Bs[KS][2][KC][BI * 4][64];
-  static_assert(KS == 1 || (KS - 1) * 4 * NTW * MTB <= KS * 2 * KC * BI * 4, "slice sums reuse the operand buffers");
+  static_assert(KS == 1 || 4 * NTW * MTB <= KS * 2 * KC * BI * 4, "slice sums reuse the operand buffers");
   // wave-uniform ids as scalars, so that tile pointers and K offsets live in scalar registers
   const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wave = wid & 3, ks = wid >> 2, lane = threadIdx.x & 63;
@@ -577,22 +577,26 @@ __global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(
     }
   }
   if (KS > 1) {
-    // slices 1.. hand their sums to slice 0 through the (now idle) operand buffers, added in slice order
+    // slices 1.. hand their sums to slice 0 through the (now idle) operand buffers, one slice at a time, in slice order
     f32x4* red = reinterpret_cast<f32x4*>(&Bs[0][0][0][0][0]);
-    if (ks > 0) {
 #pragma unroll
-      for (int a = 0; a < NTW; ++a)
+    for (int s = 1; s < KS; ++s) {
+      if (ks == s) {
 #pragma unroll
-        for (int b = 0; b < MTB; ++b) red[((((ks - 1) * 4 + wave) * NTW + a) * MTB + b) * 64 + lane] = acc[a][b];
+        for (int a = 0; a < NTW; ++a)
+#pragma unroll
+          for (int b = 0; b < MTB; ++b) red[((wave * NTW + a) * MTB + b) * 64 + lane] = acc[a][b];
+      }
+      __syncthreads();
+      if (ks == 0) {
+#pragma unroll
+        for (int a = 0; a < NTW; ++a)
+#pragma unroll
+          for (int b = 0; b < MTB; ++b) acc[a][b] += red[((wave * NTW + a) * MTB + b) * 64 + lane];
+      }
+      __syncthreads();
     }
-    __syncthreads();
     if (ks > 0) return;
-#pragma unroll
-    for (int s = 1; s < KS; ++s)
-#pragma unroll
-      for (int a = 0; a < NTW; ++a)
-#pragma unroll
-        for (int b = 0; b < MTB; ++b) acc[a][b] += red[((((s - 1) * 4 + wave) * NTW + a) * MTB + b) * 64 + lane];
   }
 
   constexpr bool paired = (EPI == EPI_SWIGLU) || (EPI == EPI_QKV);

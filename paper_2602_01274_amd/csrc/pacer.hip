@@ -220,7 +220,8 @@ void launch_wide_mtb(pacer_ctx* c, GemmArgs ga, int n_tiles) {
   // the operand from LDS less often).  Fewer blocks than CUs: split K over two slices of waves instead.
   auto blocks = [&](int ntw) { return (n_tiles + 4 * ntw - 1) / (4 * ntw) * row_groups; };
   auto units = [&](int ntw) { return (blocks(ntw) + 255) / 256 * ntw; };
-  if (blocks(2) <= 256 && ga.KT % 8 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 2, 2>(c, ga, n_tiles, row_groups);
+  if (blocks(2) <= 128 && ga.KT % 16 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 2, 4>(c, ga, n_tiles, row_groups);
+  else if (blocks(2) <= 256 && ga.KT % 8 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 2, 2>(c, ga, n_tiles, row_groups);
   else if (units(4) <= units(3) && units(4) <= units(2)) launch_wide_shape<EPI, TAG, HL, MTB, 4, 1>(c, ga, n_tiles, row_groups);
   else if (units(3) <= units(2)) launch_wide_shape<EPI, TAG, HL, MTB, 3, 1>(c, ga, n_tiles, row_groups);
   else launch_wide_shape<EPI, TAG, HL, MTB, 2, 1>(c, ga, n_tiles, row_groups);
