@@ -157,10 +157,11 @@ def test_batch_mid_bf16_eight_sequences_wide_gemm():
 
 def test_13b_width_four_layers_batch_against_oracle():
     """The shapes of workload `13b_batch` (d 5120, 40 heads of 128, FFN 13824, V 32000) at a depth the oracle can
-    afford, 6 sequences, ragged prompts and windows, per-sequence beta: up to 102 verify rows through the
-    wide GEMM at the widths bench.py times (K 5120 and 13824, 960 / 320 / 1728 / 2000 output tiles)."""
-    _run_batch("13b_batch", [18, 33, 47, 25, 60, 39], [1.0, 2.0, 3.0, 4.0, 5.0, 2.5], 2, 2e-2, 2e-2, max_seq=160,
-               n_layers_target=4)
+    afford, 12 sequences, ragged prompts and windows, per-sequence beta: up to 204 verify rows through the
+    wide GEMM at the widths bench.py times (K 5120 and 13824, 960 / 320 / 1728 / 2000 output tiles; 3 and 4
+    row tiles per block, K slices for the few-tile matrices)."""
+    _run_batch("13b_batch", [18, 33, 47, 25, 60, 39, 21, 52, 30, 44, 27, 36],
+               [1.0, 2.0, 3.0, 4.0, 5.0, 2.5, 3.5, 1.5, 4.5, 2.0, 3.0, 4.0], 2, 2e-2, 2e-2, max_seq=160, n_layers_target=4)
 
 
 def test_33b_width_two_layers_bf16():
