@@ -194,9 +194,12 @@ int32_t pacer_verify(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs,
  * host array [n_seqs]; 0 gives the paper's plain rule), PACER_GREEDY accepts the leading drafts
  * equal to the effective argmax and emits the argmax at the first mismatch (or of the bonus
  * row); PACER_SAMPLE accepts y_i while r_i <= p_i[y_i]/q_i[y_i], then samples from
- * norm(max(0, p - q)) at the first rejection or from p_{gamma+1}.  Runs the draft forward on
- * y_gamma that the all-accepted case needs (it also yields the draft logits of the bonus row)
- * and extends M_B's cache over positions that no pacer_preverify_block covered.  Appends
+ * norm(max(0, p - q)) at the first rejection or from p_{gamma+1}.  Extends M_B's cache over
+ * positions that no pacer_preverify_block covered.  The call waits (polling pinned host words,
+ * no stream synchronisation) until n is known for every listed sequence; for those that accepted
+ * all gamma drafts it then runs the draft forward on y_gamma (it completes the draft cache and
+ * yields the draft logits of the bonus row) and evaluates the bonus row.  The kernels of that
+ * second part may still be in flight when the call returns.  Appends
  * y_1..y_n and the new token to the committed tokens; all three caches then logically hold
  * committed_length-1 positions (rollback = shorter length, nothing is erased).
  * dev_logits: the buffer pacer_verify wrote.  dev_n_accepted[n_seqs], dev_next_token[n_seqs]

@@ -536,7 +536,10 @@ __global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const floa
 }
 
 // ------------------------------------------------------------------ acceptance (Eq. 5)
-struct AccArgs { int n_seqs; int seq[PK_MAXB]; int gamma[PK_MAXB]; int len[PK_MAXB]; float beta[PK_MAXB]; };
+// slot: the sequence's index in the verify call that wrote the logits (row slot*G1 + i of tl, entry slot of the
+// caller's n / z arrays).  The kernels run in two phases: phase 0 covers rows i < gamma (everything a step needs
+// unless every draft is accepted), phase 1 the bonus row i = gamma of the sequences that accepted all drafts.
+struct AccArgs { int n_seqs; int seq[PK_MAXB]; int slot[PK_MAXB]; int gamma[PK_MAXB]; int len[PK_MAXB]; float beta[PK_MAXB]; };
 
 // One row of logits is split into ACC_CHUNKS vocabulary ranges, one block each (a single block per row
 // spent 53 us walking 32000 entries three times).  Three launches:
@@ -546,6 +549,8 @@ struct AccArgs { int n_seqs; int seq[PK_MAXB]; int gamma[PK_MAXB]; int len[PK_MA
 //                         order, so every chunk of a row derives the same value), then the chunk's best
 //                         candidates; chunk 0 also takes the row's accept test
 //   accept_finalize_kernel per sequence: best candidate over the chunks of each row, first rejection, tokens
+// Rows i < gamma first; the bonus row i = gamma (whose draft logits cost one more draft forward) only for the
+// sequences that turn out to have accepted every draft.
 #define ACC_CHUNKS 8
 #define ACC_PART 8      // floats per (row, chunk): [0..3] = mp, sp, mq, sq ; [4..7] = best, bi, bestp, bip
 
@@ -557,12 +562,13 @@ __device__ __forceinline__ void acc_chunk_range(int V, int chunk, int& v0, int& 
 
 // grid (gamma_max+1, n_seqs, ACC_CHUNKS)
 __global__ __launch_bounds__(256) void accept_stats_kernel(const float* __restrict__ tl, const float* __restrict__ ring, AccArgs aa, int G1,
-                                                           int V, float* __restrict__ part) {
+                                                           int V, int phase, float* __restrict__ part) {
   __shared__ float redv[16];
-  const int i = blockIdx.x, si = blockIdx.y, ch = blockIdx.z, s = aa.seq[si];
-  if (i > aa.gamma[si]) return;
+  const int si = blockIdx.y, ch = blockIdx.z, s = aa.seq[si], sl = aa.slot[si];
+  const int i = phase ? aa.gamma[si] : blockIdx.x;
+  if (!phase && i >= aa.gamma[si]) return;
   const float beta = aa.beta[si];
-  const float* t = tl + (size_t)(si * G1 + i) * V;
+  const float* t = tl + (size_t)(sl * G1 + i) * V;
   const float* q = ring + (size_t)(s * G1 + i) * V;
   int v0, v1;
   acc_chunk_range(V, ch, v0, v1);
@@ -575,7 +581,7 @@ __global__ __launch_bounds__(256) void accept_stats_kernel(const float* __restri
   sp = block_sum(sp, redv);
   sq = block_sum(sq, redv);
   if (threadIdx.x == 0) {
-    float* o = part + ((size_t)(si * G1 + i) * ACC_CHUNKS + ch) * ACC_PART;
+    float* o = part + ((size_t)(sl * G1 + i) * ACC_CHUNKS + ch) * ACC_PART;
     o[0] = mp; o[1] = sp; o[2] = mq; o[3] = sq;
   }
 }
@@ -584,17 +590,19 @@ __global__ __launch_bounds__(256) void accept_stats_kernel(const float* __restri
 // candidates (token emitted if this row is where drafting is cut) and, from chunk 0, rej (row's draft rejected).
 __global__ __launch_bounds__(256) void accept_rows_kernel(const float* __restrict__ tl, const float* __restrict__ ring,
                                                           const int* __restrict__ draft_tok, AccArgs aa, int G1, int V, int mode,
-                                                          uint64_t seed, uint32_t step, float* __restrict__ part, int* __restrict__ rej) {
+                                                          uint64_t seed, uint32_t step, int phase, float* __restrict__ part,
+                                                          int* __restrict__ rej) {
   __shared__ float redv[16];
   __shared__ int redi[16];
-  const int i = blockIdx.x, si = blockIdx.y, ch = blockIdx.z, s = aa.seq[si];
+  const int si = blockIdx.y, ch = blockIdx.z, s = aa.seq[si], sl = aa.slot[si];
   const int gamma = aa.gamma[si];
-  if (i > gamma) return;
+  const int i = phase ? gamma : blockIdx.x;
+  if (!phase && i >= gamma) return;
   const float beta = aa.beta[si];
-  const float* t = tl + (size_t)(si * G1 + i) * V;
+  const float* t = tl + (size_t)(sl * G1 + i) * V;
   const float* q = ring + (size_t)(s * G1 + i) * V;
   const int y = i < gamma ? draft_tok[s * G1 + i] : -1;
-  float* prow = part + (size_t)(si * G1 + i) * ACC_CHUNKS * ACC_PART;
+  float* prow = part + (size_t)(sl * G1 + i) * ACC_CHUNKS * ACC_PART;
   float* o = prow + ch * ACC_PART;
   int v0, v1;
   acc_chunk_range(V, ch, v0, v1);
@@ -658,52 +666,62 @@ __global__ __launch_bounds__(256) void accept_rows_kernel(const float* __restric
         const uint4 b = vocab_bits(seed, s, step, (uint32_t)(i + 1), PURPOSE_ACCEPT, 0u);
         rj = (u01(b.x) > ratio) ? 1 : 0;
       }
-      rej[si * G1 + i] = rj;
+      rej[sl * G1 + i] = rj;
     }
   }
 }
 
-// n = first rejected row (or gamma); next token = that row's candidate; append to committed tokens
+// Phase 0: n = first rejected row (or gamma).  n < gamma: next token = row n's candidate, tokens appended, results
+// (n, z) to the caller's arrays and to pinned host memory.  n = gamma: the bonus row has not been evaluated yet
+// (its draft logits need one more draft forward): the drafts are appended and (gamma, -1) tells the host to run
+// phase 1, which takes the token of row gamma.  The ticket is written last; the host polls for it.
 __global__ void accept_finalize_kernel(const float* __restrict__ part, const int* __restrict__ rej, const int* __restrict__ draft_tok,
-                                       AccArgs aa, int G1, int mode, int max_seq, int* __restrict__ tokens, int* __restrict__ out_n,
-                                       int* __restrict__ out_z, int* __restrict__ host_res, int* __restrict__ host_tick, int ticket) {
-  const int si = blockIdx.x, s = aa.seq[si];
+                                       AccArgs aa, int G1, int mode, int phase, int max_seq, int* __restrict__ tokens,
+                                       int* __restrict__ out_n, int* __restrict__ out_z, int* __restrict__ host_res,
+                                       int* __restrict__ host_tick, int ticket) {
+  const int si = blockIdx.x, s = aa.seq[si], sl = aa.slot[si];
   const int gamma = aa.gamma[si];
   int n = gamma;
-  if (mode == 0) {
-    // greedy: row i's draft is rejected when it differs from the row's argmax
-    for (int i = gamma - 1; i >= 0; --i) {
-      const float* pr = part + (size_t)(si * G1 + i) * ACC_CHUNKS * ACC_PART;
-      float best = -INFINITY;
-      int bi = 0x7fffffff;
-      for (int c = 0; c < ACC_CHUNKS; ++c) {
-        const float v = pr[c * ACC_PART + 6];
-        const int id = __float_as_int(pr[c * ACC_PART + 7]);
-        if (v > best || (v == best && id < bi)) { best = v; bi = id; }
+  if (!phase) {
+    if (mode == 0) {
+      // greedy: row i's draft is rejected when it differs from the row's argmax
+      for (int i = gamma - 1; i >= 0; --i) {
+        const float* pr = part + (size_t)(sl * G1 + i) * ACC_CHUNKS * ACC_PART;
+        float best = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int c = 0; c < ACC_CHUNKS; ++c) {
+          const float v = pr[c * ACC_PART + 6];
+          const int id = __float_as_int(pr[c * ACC_PART + 7]);
+          if (v > best || (v == best && id < bi)) { best = v; bi = id; }
+        }
+        if (bi != draft_tok[s * G1 + i]) n = i;
       }
-      if (bi != draft_tok[s * G1 + i]) n = i;
+    } else {
+      for (int i = gamma - 1; i >= 0; --i)
+        if (rej[sl * G1 + i]) n = i;
     }
-  } else {
-    for (int i = gamma - 1; i >= 0; --i)
-      if (rej[si * G1 + i]) n = i;
   }
-  // the emitted token: best residual candidate of row n over the chunks, else best candidate of p
-  const float* pr = part + (size_t)(si * G1 + n) * ACC_CHUNKS * ACC_PART;
-  float best = -INFINITY, bestp = -INFINITY;
-  int bi = 0x7fffffff, bip = 0x7fffffff;
-  for (int c = 0; c < ACC_CHUNKS; ++c) {
-    const float v = pr[c * ACC_PART + 4], vp = pr[c * ACC_PART + 6];
-    const int id = __float_as_int(pr[c * ACC_PART + 5]), idp = __float_as_int(pr[c * ACC_PART + 7]);
-    if (v > best || (v == best && id < bi)) { best = v; bi = id; }
-    if (vp > bestp || (vp == bestp && idp < bip)) { bestp = vp; bip = idp; }
+  int z = -1;
+  if (phase || n < gamma) {
+    // the emitted token: best residual candidate of row n over the chunks, else best candidate of p
+    const float* pr = part + (size_t)(sl * G1 + n) * ACC_CHUNKS * ACC_PART;
+    float best = -INFINITY, bestp = -INFINITY;
+    int bi = 0x7fffffff, bip = 0x7fffffff;
+    for (int c = 0; c < ACC_CHUNKS; ++c) {
+      const float v = pr[c * ACC_PART + 4], vp = pr[c * ACC_PART + 6];
+      const int id = __float_as_int(pr[c * ACC_PART + 5]), idp = __float_as_int(pr[c * ACC_PART + 7]);
+      if (v > best || (v == best && id < bi)) { best = v; bi = id; }
+      if (vp > bestp || (vp == bestp && idp < bip)) { bestp = vp; bip = idp; }
+    }
+    z = (n < gamma && best > -INFINITY) ? bi : bip;
   }
-  const int z = (n < gamma && best > -INFINITY) ? bi : bip;
   int* tk = tokens + (size_t)s * max_seq + aa.len[si];
-  for (int k = threadIdx.x; k < n; k += blockDim.x) tk[k] = draft_tok[s * G1 + k];
+  if (!phase)
+    for (int k = threadIdx.x; k < n; k += blockDim.x) tk[k] = draft_tok[s * G1 + k];
   if (threadIdx.x == 0) {
-    tk[n] = z;
-    out_n[si] = n;
-    out_z[si] = z;
+    if (z >= 0) tk[n] = z;
+    out_n[sl] = n;
+    out_z[sl] = z;
     host_res[2 * s] = n;
     host_res[2 * s + 1] = z;
     __threadfence_system();            // the results first, then the ticket the host polls for

@@ -949,26 +949,26 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
   for (int i = 0; i < n; ++i)
     if (!c->seq[seqs[i]].in_step || c->seq[seqs[i]].verified < 0)
       return fail(c, PACER_ESTATE, "accept_rollback: sequence %d has not been verified", seqs[i]);
-  // draft forward on y_gamma: completes the draft cache for the all-accepted case and yields the
-  // draft logits of the bonus row
-  int j[PACER_MAX_BATCH];
-  for (int i = 0; i < n; ++i) j[i] = c->seq[seqs[i]].verified;
-  draft_forward(c, seqs, n, j, PACER_GREEDY, 0, 0);
-  // M_B prefix rows for draft positions no pre-verification call covered (incl. the bonus position)
-  {
+  // Phase 0 takes rows i < gamma: M_B prefix rows for the drafts no pre-verification call covered, the accept
+  // tests and the token at the first rejection.  The draft forward on y_gamma (it completes the draft cache
+  // and yields the draft logits of the bonus row) is needed only by a sequence that accepted every draft;
+  // those sequences go through phase 1 once the host has seen phase 0's result.
+  const int V = c->m[PACER_TARGET].cfg.vocab;
+  auto mb_prefix = [&](const int* ids, int m, bool bonus) {
     SeqRows sr{};
     MbRows mr{};
     int R = 0, k = 0;
-    for (int i = 0; i < n; ++i) {
-      const Seq& q = c->seq[seqs[i]];
-      const int first = std::min(q.mb_done, q.verified + 1);
-      const int cnt = q.verified + 1 - first;
+    for (int i = 0; i < m; ++i) {
+      const Seq& q = c->seq[ids[i]];
+      const int end = bonus ? q.verified + 1 : q.verified;       // draft positions [first, end)
+      const int first = bonus ? q.verified : std::min(q.mb_done, q.verified);
+      const int cnt = end - first;
       if (cnt <= 0) continue;
-      sr.seq[k] = seqs[i];
+      sr.seq[k] = ids[i];
       sr.row_off[k] = R;
       sr.pos0[k] = q.len - 1 + first;
       sr.len[k] = q.len;
-      mr.src_row0[k] = seqs[i] * c->G1 + first;
+      mr.src_row0[k] = ids[i] * c->G1 + first;
       mr.e0[k] = -1;
       R += cnt;
       ++k;
@@ -976,27 +976,60 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
     sr.n_seqs = k;
     sr.row_off[k] = R;
     if (R > 0) run_preverify_rows(c, R, sr, mr, c->hidden, c->m[PACER_PREVERIFY].cfg.d_model, true);
-  }
+  };
+  auto accept_rows = [&](const AccArgs& aa, int rows, int phase) {
+    if (rows > 0) {
+      const dim3 grid(rows, aa.n_seqs, ACC_CHUNKS);
+      if (mode != PACER_GREEDY)
+        hipLaunchKernelGGL(accept_stats_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, aa, c->G1, V, phase, c->acc_part);
+      hipLaunchKernelGGL(accept_rows_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode, seed,
+                         (uint32_t)ctr, phase, c->acc_part, c->rej);
+    }
+    hipLaunchKernelGGL(accept_finalize_kernel, dim3(aa.n_seqs), dim3(64), 0, c->stream, c->acc_part, c->rej, c->draft_tok, aa, c->G1,
+                       mode, phase, c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev, c->host_res_dev + 2 * PACER_MAX_BATCH,
+                       ++c->acc_calls);
+    for (int i = 0; i < aa.n_seqs; ++i) c->seq[aa.seq[i]].acc_ticket = c->acc_calls;
+  };
+  mb_prefix(seqs, n, false);
   AccArgs aa{};
   aa.n_seqs = n;
+  int gmax = 0;
   for (int i = 0; i < n; ++i) {
     const Seq& q = c->seq[seqs[i]];
     aa.seq[i] = seqs[i];
+    aa.slot[i] = i;
     aa.gamma[i] = q.verified;
     aa.len[i] = q.len;
     aa.beta[i] = beta[i];
+    gmax = std::max(gmax, q.verified);
   }
-  const int V = c->m[PACER_TARGET].cfg.vocab;
-  const dim3 grid(c->G1, n, ACC_CHUNKS);
-  if (mode != PACER_GREEDY)
-    hipLaunchKernelGGL(accept_stats_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, aa, c->G1, V, c->acc_part);
-  hipLaunchKernelGGL(accept_rows_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode, seed,
-                     (uint32_t)ctr, c->acc_part, c->rej);
-  hipLaunchKernelGGL(accept_finalize_kernel, dim3(n), dim3(64), 0, c->stream, c->acc_part, c->rej, c->draft_tok, aa, c->G1, mode,
-                     c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev, c->host_res_dev + 2 * PACER_MAX_BATCH, ++c->acc_calls);
+  accept_rows(aa, gmax, 0);
+  HIPCHK(c, hipGetLastError());
+  // the sequences whose drafts were all accepted: host_res holds (gamma, -1) for them
+  AccArgs ab{};
+  int32_t sub[PACER_MAX_BATCH];
+  int jb[PACER_MAX_BATCH];
+  int m = 0;
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = c->seq[seqs[i]];
+    if (int rc = wait_ticket(c, c->host_res + 2 * PACER_MAX_BATCH + seqs[i], q.acc_ticket, 0)) return rc;
+    if (c->host_res[2 * seqs[i] + 1] >= 0) continue;
+    sub[m] = ab.seq[m] = seqs[i];
+    jb[m] = q.verified;
+    ab.slot[m] = i;
+    ab.gamma[m] = q.verified;
+    ab.len[m] = q.len;
+    ab.beta[m] = beta[i];
+    ++m;
+  }
+  if (m > 0) {
+    ab.n_seqs = m;
+    draft_forward(c, sub, m, jb, PACER_GREEDY, 0, 0);
+    mb_prefix(sub, m, true);
+    accept_rows(ab, 1, 1);
+  }
   for (int i = 0; i < n; ++i) {
     Seq& q = c->seq[seqs[i]];
-    q.acc_ticket = c->acc_calls;
     q.pending = true;
     q.in_step = false;
   }
