@@ -48,6 +48,8 @@ def test_tiny_f32_greedy_steps_match_oracle():
     ck, gammas, ns = _run("tiny", 32, 64, tol_logits=1e-4, tol_alpha=1e-4)
     assert len(set(gammas)) > 1          # the window really adapts
     assert 0 < np.mean(ns) < np.mean(gammas)
+    both = {n == g for n, g in zip(ns, gammas)}
+    assert both == {True, False}         # steps with a rejection and all-accepted steps (bonus row) both occurred
 
 
 def test_tiny_f32_sampling_steps_match_oracle():
@@ -100,7 +102,7 @@ def test_7b_width_full_window_and_long_prompt():
 
 
 def _run_batch(name, prompt_lens, betas, n_steps, tol_logits, tol_alpha, mode=po.GREEDY, seed=5, max_seq=512,
-               n_layers_target=None):
+               n_layers_target=None, fixed_gamma=None, ragged=True):
     """Several sequences in lock step (ragged verify batch, per-sequence gamma, beta and length)
     against one oracle per sequence."""
     w = synth.workload(name)
@@ -115,21 +117,23 @@ def _run_batch(name, prompt_lens, betas, n_steps, tol_logits, tol_alpha, mode=po
         s.prefill(prompt, seq=i)
         o.prefill(prompt)
         cks.append(StepChecker(s, o, tol_logits, tol_alpha, mode=mode, seed=seed, seq=i))
-    gam = []
+    gam, full = [], []
     for _ in range(n_steps):
         idx = [ck.o.step_idx for ck in cks]
-        ros = [ck.o.step() for ck in cks]
-        rgs = s.step_batch(list(range(nb)), mode=mode, betas=betas, seed=seed, record=True)
+        ros = [ck.o.step(**({} if fixed_gamma is None else {"fixed_gamma": fixed_gamma})) for ck in cks]
+        rgs = s.step_batch(list(range(nb)), mode=mode, betas=betas, seed=seed, record=True, fixed_gamma=fixed_gamma)
         for ck, ro, rg, k in zip(cks, ros, rgs, idx):
             ck.check(ro, rg, k)
         gam.append([r["gamma"] for r in ros])
+        full.append([r["n"] == r["gamma"] for r in ros])
     for i, ck in enumerate(cks):
         assert s.tokens(i) == ck.o.tokens
     flips = [f for ck in cks for f in ck.flips]
     print(f"\n[batch {name} x{nb} mode={mode}] gammas={gam} max_err={[ck.max_err['target_logits'] for ck in cks]} flips={flips}")
     assert len(flips) <= max(2, n_steps * nb // 5)
-    assert len({tuple(g) for g in gam}) > 1 or len(set(gam[0])) > 1      # the batch really was ragged
+    assert not ragged or len({tuple(g) for g in gam}) > 1 or len(set(gam[0])) > 1      # the batch really was ragged
     s.close()
+    return full
 
 
 def test_batch_tiny_f32_ragged():
@@ -147,6 +151,16 @@ def test_batch_mid_bf16_ragged():
     """The batched workload in miniature: ragged batch, per-sequence beta in [1, 5], prompt lengths
     spread over several attention tiles; 4 sequences x up to 13 verify rows = two 32-row GEMM chunks."""
     _run_batch("mid", [40, 75, 150, 260], [1.0, 2.3, 3.7, 5.0], 6, 2e-2, 2e-2)
+
+
+def test_batch_mid_bf16_bonus_row_for_part_of_the_batch():
+    """Strong coupling and a short fixed window make all-accepted steps frequent: in most steps only some
+    of the sequences take the extra draft forward and the bonus row (Alg. 1, the all-accepted branch), whose
+    logits then sit at other slots than the sequences' indices in the second acceptance pass."""
+    for mode in (po.GREEDY, po.SAMPLE):
+        full = _run_batch("mid", [40, 75, 150, 33], [8.0, 1.0, 6.0, 10.0], 8, 2e-2, 2e-2, mode=mode, fixed_gamma=2, ragged=False)
+        assert any(any(f) and not all(f) for f in full)
+        assert any(not f[0] and any(f[1:]) for f in full)      # a later sequence without the first: slot != index
 
 
 def test_batch_mid_bf16_eight_sequences_wide_gemm():
