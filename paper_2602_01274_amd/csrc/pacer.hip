@@ -217,10 +217,13 @@ void launch_wide_mtb(pacer_ctx* c, GemmArgs ga, int n_tiles) {
   } else {
   // Output tiles per wave (NTW): blocks run two to a CU, so the launch takes about
   // ceil(blocks / 256) * NTW units; pick the NTW with the fewest units, the larger one on a tie (it reads
-  // the operand from LDS less often).  Fewer blocks than CUs: split K over two slices of waves instead.
+  // the operand from LDS less often).  Few output tiles (O and down projections): one tile per wave, so
+  // that there are about as many blocks as CUs, and K split over two or four slices of waves (at 144 rows
+  // the 13B down projection takes 79 us with one tile per wave, 105 us with two and half the CUs idle).
   auto blocks = [&](int ntw) { return (n_tiles + 4 * ntw - 1) / (4 * ntw) * row_groups; };
   auto units = [&](int ntw) { return (blocks(ntw) + 255) / 256 * ntw; };
-  if (blocks(2) <= 128 && ga.KT % 16 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 2, 4>(c, ga, n_tiles, row_groups);
+  if (blocks(1) <= 128 && ga.KT % 16 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 1, 4>(c, ga, n_tiles, row_groups);
+  else if (blocks(1) <= 256 && ga.KT % 8 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 1, 2>(c, ga, n_tiles, row_groups);
   else if (blocks(2) <= 256 && ga.KT % 8 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 2, 2>(c, ga, n_tiles, row_groups);
   else if (units(4) <= units(3) && units(4) <= units(2)) launch_wide_shape<EPI, TAG, HL, MTB, 4, 1>(c, ga, n_tiles, row_groups);
   else if (units(3) <= units(2)) launch_wide_shape<EPI, TAG, HL, MTB, 3, 1>(c, ga, n_tiles, row_groups);
