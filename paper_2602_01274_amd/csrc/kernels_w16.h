@@ -351,13 +351,13 @@ template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0, int H
 __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_kernel(const GemmArgs ga) {
   static_assert(!X17 || MT == 2, "the 17-row form uses two row tiles");
   __shared__ f32x4 red[WAVES][NT * MT][64];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id as a scalar
   const int nt0 = ga.nt_begin + blockIdx.x * NT;
   const int KT = ga.KT;
   // K steps are dealt to the block's waves round-robin (wave w takes w, w+WAVES, ...): at any moment
   // the waves of a block, and the blocks sharing a CU, read neighbouring operand tiles, which keeps the
   // operand in the CU's L1 instead of fetching it once per wave from L2
-  const int per = (KT + WAVES - 1) / WAVES;           // steps of this wave: index i -> kt = i*WAVES + wave
+  // steps of this wave: index i -> kt = i*WAVES + wave
   const int kb = 0;
   const int ke = (KT - wave + WAVES - 1) / WAVES;
   f32x4 acc[NT][MT];
@@ -368,57 +368,55 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
   const u32x4* wp[NT];
 #pragma unroll
   for (int a = 0; a < NT; ++a) wp[a] = ga.W + (size_t)(nt0 + a) * KT * 64 + lane;
-  const u32x4* xp = ga.X + (size_t)ga.mt0 * 128 + (lane & 15) * 4 + (lane >> 4);
+  // Operand pointers, one per row tile.  Lanes whose row does not exist read the tile's last live row instead
+  // (the same cache lines the live lanes fetch, and their accumulator columns are discarded): the operand
+  // traffic scales with the number of rows, not with whole 16-row tiles, and no load is conditional.
+  const u32x4* xpb[MT];
+#pragma unroll
+  for (int b = 0; b < MT; ++b) {
+    const int live = min(16, max(1, ga.R - (ga.mt0 + b) * 16));
+    xpb[b] = ga.X + (size_t)(ga.mt0 + b) * 128 + min(lane & 15, live - 1) * 4 + (lane >> 4);
+  }
   // row 0 of row tile mt0+1: its hi part for even operand columns, its lo part for odd ones
   const u32x4* xp17 = ga.X + (size_t)(ga.mt0 + 1) * 128 + (lane >> 4) + (HL == 2 ? (lane & 1) * 64 : 0);
   const bool x17_live = (lane & 15) < HL;
   const int mtt = ga.mt_total;
-  // operand columns beyond the last row are never fetched (their accumulator columns are discarded):
-  // the operand traffic scales with the number of rows instead of with whole 16-row tiles
-  bool col_live[MT];
-#pragma unroll
-  for (int b = 0; b < MT; ++b) col_live[b] = (ga.mt0 + b) * 16 + (lane & 15) < ga.R;
 
   constexpr int BW = X17 ? HL + 1 : MT * HL;           // operand tiles per K step: [row tile][part]
   u32x4 A0[U][NT], A1[U][NT], B0[U][BW], B1[U][BW];
   const u32x4 zero = {0u, 0u, 0u, 0u};
+  // The K loop has no branches: a branch around a load makes the compiler wait for every outstanding load
+  // where the paths join (the load counter completes in order, and the number of newer loads then differs
+  // by path), which would serialise each wave on memory latency.  K steps past the wave's last one re-read
+  // its last tile (an L1 hit) and their weights are replaced by zeros before use.
   auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][BW], int k0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int kt = (k0 + u) * WAVES + wave;
-      if (k0 + u < ke) {
+      const size_t kt = (size_t)min((k0 + u) * WAVES + wave, KT - 1);
 #pragma unroll
-        for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + (size_t)kt * 64);
-        if (X17) {
+      for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + kt * 64);
+      if (X17) {
 #pragma unroll
-          for (int h = 0; h < HL; ++h) B[u][h] = xp[((size_t)kt * mtt * 2 + h) * 64];
-          B[u][HL] = xp17[(size_t)kt * mtt * 2 * 64];
-        } else {
-#pragma unroll
-          for (int b = 0; b < MT; ++b)
-#pragma unroll
-            for (int h = 0; h < HL; ++h) {
-              B[u][b * HL + h] = zero;
-              if (col_live[b]) B[u][b * HL + h] = xp[(((size_t)kt * mtt + b) * 2 + h) * 64];
-            }
-        }
+        for (int h = 0; h < HL; ++h) B[u][h] = xpb[0][(kt * mtt * 2 + h) * 64];
+        B[u][HL] = xp17[kt * mtt * 2 * 64];
       } else {
 #pragma unroll
-        for (int a = 0; a < NT; ++a) A[u][a] = zero;
+        for (int b = 0; b < MT; ++b)
 #pragma unroll
-        for (int b = 0; b < BW; ++b) B[u][b] = zero;
+          for (int h = 0; h < HL; ++h) B[u][b * HL + h] = xpb[b][(kt * mtt * 2 + h) * 64];
       }
     }
   };
-  auto compute = [&](u32x4(&A)[U][NT], u32x4(&B)[U][BW]) {
+  auto compute = [&](u32x4(&A)[U][NT], u32x4(&B)[U][BW], int k0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+      const bool valid = k0 + u < ke;                  // wave-uniform
       half8 bh[BW];
 #pragma unroll
       for (int b = 0; b < BW; ++b) bh[b] = __builtin_bit_cast(half8, (X17 && b == HL && !x17_live) ? zero : B[u][b]);
 #pragma unroll
       for (int a = 0; a < NT; ++a) {
-        const half8 ah = __builtin_bit_cast(half8, A[u][a]);
+        const half8 ah = __builtin_bit_cast(half8, valid ? A[u][a] : zero);
 #pragma unroll
         for (int b = 0; b < MT; ++b)
 #pragma unroll
@@ -429,12 +427,20 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
       }
     }
   };
+  // Two register sets; each is refilled right after its products were issued, in the same order on every
+  // path into the loop, and the scheduler may not move loads across the phase boundaries: the wait before
+  // a phase's products then leaves the other set's loads in flight.
   load(A0, B0, kb);
+  __builtin_amdgcn_sched_barrier(0);
   for (int k0 = kb; k0 < ke; k0 += 2 * U) {
     load(A1, B1, k0 + U);
-    compute(A0, B0);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(A0, B0, k0);
+    __builtin_amdgcn_sched_barrier(0);
     load(A0, B0, k0 + 2 * U);
-    compute(A1, B1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(A1, B1, k0 + U);
+    __builtin_amdgcn_sched_barrier(0);
   }
 #pragma unroll
   for (int a = 0; a < NT; ++a)

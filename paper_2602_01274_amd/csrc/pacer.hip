@@ -269,13 +269,15 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
     if (TAG == 0) prof_begin(c);
     if (HL == 1) {
       if (mt == 1) {
-        // K <= 1024: 4 waves with at most 8 K steps each, all in flight at once (a prefetch depth above
-        // the wave's step count measured slower than one that matches it)
-        if (ga.KT <= 24) launch_w16<EPI, TAG, 1, 1, 1, 4, 6>(c, ga, n_tiles);
-        else if (many) launch_w16<EPI, TAG, 1, 1, 1, 4, 8>(c, ga, n_tiles);
-        else launch_w16<EPI, TAG, 1, 1, 1, 8, 4>(c, ga, n_tiles);
+        // K <= 768 (draft, pre-verification layer): 4 waves with at most 6 K steps each; the LM head and the
+        // gate/up matrix (many tiles) run one step per register set, the small ones three
+        if (ga.KT <= 24) {
+          if (n_tiles >= 256) launch_w16<EPI, TAG, 1, 1, 1, 4, 1>(c, ga, n_tiles);
+          else launch_w16<EPI, TAG, 1, 1, 1, 4, 3>(c, ga, n_tiles);
+        } else if (many && even && rows > 8) launch_w16<EPI, TAG, 1, 1, 2, 4, 2>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 1, 1, 1, 8, 2>(c, ga, n_tiles);
       } else if (rows == 17) {
-        if (many && even && n_tiles >= 1024) launch_w16<EPI, TAG, 1, 2, 2, 4, 4, 1>(c, ga, n_tiles);
+        if (many && even && n_tiles >= 1024) launch_w16<EPI, TAG, 1, 2, 2, 4, 2, 1>(c, ga, n_tiles);
         else if (many) launch_w16<EPI, TAG, 1, 2, 1, 4, 4, 1>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 1, 2, 1, 8, 2, 1>(c, ga, n_tiles);
       } else {
@@ -287,11 +289,11 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
         // QKV (768 tiles at d 4096): four output tiles per wave share one fetch of the operand
         if (EPI == EPI_QKV && many && n_tiles % 4 == 0 && n_tiles < 1024 && rows > 8) launch_w16<EPI, TAG, 2, 1, 4, 8, 1>(c, ga, n_tiles);
         else if (many && even && (n_tiles >= 1024 || rows > 8)) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
-        else launch_w16<EPI, TAG, 2, 1, 1, 8, 3>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 2, 1, 1, 8, 1>(c, ga, n_tiles);
       } else if (rows == 17) {
         if (EPI == EPI_QKV && many && n_tiles % 4 == 0 && n_tiles < 1024) launch_w16<EPI, TAG, 2, 2, 4, 8, 1, 1>(c, ga, n_tiles);
         else if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2, 1>(c, ga, n_tiles);
-        else launch_w16<EPI, TAG, 2, 2, 1, 8, 2, 1>(c, ga, n_tiles);
+        else launch_w16<EPI, TAG, 2, 2, 1, 8, 1, 1>(c, ga, n_tiles);
       } else {
         if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 2, 1, 8, 2>(c, ga, n_tiles);
