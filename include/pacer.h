@@ -123,7 +123,9 @@ int32_t pacer_bind(pacer_ctx* ctx, int32_t which, int32_t tensor_id, int32_t lay
  * the 1 KiB tile order the attention kernel's matrix instructions read: K as
  * [head][position/16][feature/32][64 lanes][8], V as [head][position/32][feature/16][64 lanes][8];
  * max_seq must be a multiple of 32).  The layout is the
- * library's own; contents need not be initialised.  pacer_kv_bytes returns the exact size
+ * library's own; contents need not be initialised: pacer_bind_kv clears the buffer (a memset
+ * enqueued on the context's stream), because attention reads whole 32-position groups and the
+ * slots past a sequence's end must hold finite values.  pacer_kv_bytes returns the exact size
  * pacer_bind_kv expects. */
 uint64_t pacer_kv_bytes(const pacer_ctx* ctx, int32_t which);
 int32_t pacer_bind_kv(pacer_ctx* ctx, int32_t which, void* dev_ptr, uint64_t nbytes);

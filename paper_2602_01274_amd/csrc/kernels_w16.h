@@ -681,98 +681,98 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
     for (int dt = 0; dt < DTS; ++dt) acc[dt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // K tiles (two 16-key tiles x KTS feature groups) and V^T fragments of one 32-key group
-  auto load_kv = [&](int kk, half8(&ka)[2][KTS], half8(&va)[DTS]) {
+  // One 32-key group = two 16-key K tiles x KTS feature groups, and DTS fragments of V^T.  K and V each have
+  // one register set; a set is refilled for the wave's next group as soon as its last product was issued
+  // (K after the scores, V after the values), so each load has half a step of this wave's arithmetic, and
+  // the other waves, to hide behind.  The loop has no branches and the loads keep their program order
+  // (sched_barrier): a wait for K then leaves the V loads in flight and vice versa.  The step after the
+  // wave's last one re-reads the last group (cache hits, unused).
+  // Cache slots of positions not written yet hold zeros or old finite values (the cache is cleared when it is
+  // bound), so their zero probabilities contribute nothing.
+  auto load_k = [&](int kk, half8(&ka)[2][KTS]) {
     const _Float16* kt0 = Kc + (size_t)(kk >> 4) * (KTS * 512) + lane * 8;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int kt = 0; kt < KTS; ++kt) ka[t][kt] = *reinterpret_cast<const half8*>(kt0 + (t * KTS + kt) * 512);
+  };
+  auto load_v = [&](int kk, half8(&va)[DTS]) {
     const _Float16* vg = Vt + (size_t)(kk >> 5) * (DTS * 512) + lane * 8;
-    const bool tail = kk + 32 > n_keys;
 #pragma unroll
-    for (int dt = 0; dt < DTS; ++dt) {
-      half8 v = *reinterpret_cast<const half8*>(vg + dt * 512);
-      if (tail) {   // slots of positions not written yet may hold anything, NaN included
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (kk + 4 * g + e >= n_keys) v[e] = (_Float16)0.f;
-          if (kk + 16 + 4 * g + e >= n_keys) v[4 + e] = (_Float16)0.f;
-        }
-      }
-      va[dt] = v;
-    }
+    for (int dt = 0; dt < DTS; ++dt) va[dt] = *reinterpret_cast<const half8*>(vg + dt * 512);
   };
-  auto step = [&](int kk, half8(&ka)[2][KTS], half8(&va)[DTS]) {
+  // scores of one group for row tile mt -> probabilities (f16, in the lane layout the value product wants
+  // for B) and the rescale factor of the running state
+  auto scores = [&](int kk, int mt, half8(&ka)[2][KTS], half8& pb, float& corr) {
+    f32x4 st[2];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      f32x4 st[2];
+    for (int t = 0; t < 2; ++t) {
+      f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+      for (int kt = 0; kt < KTS; ++kt)
 #pragma unroll
-        for (int kt = 0; kt < KTS; ++kt)
-#pragma unroll
-          for (int pq = 0; pq < QL; ++pq) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][kt], q[kt][mt][pq], s, 0, 0, 0);
-        st[t] = s;
-      }
-      const int pos = pos0 + mt * 16 + j;                // this lane's query row
-      float sv[8];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int key = kk + 16 * t + 4 * g + r;
-          const float v = (key <= pos && key < n_keys) ? st[t][r] * scale : -INFINITY;
-          sv[t * 4 + r] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mn = fmaxf(mrun[mt], mx);
-      float ps = 0.f;
-      half8 pb;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float p = (mn == -INFINITY) ? 0.f : expf(sv[e] - mn);
-        ps += p;
-        pb[e] = (_Float16)p;
-      }
-      ps += __shfl_xor(ps, 16, 64);
-      ps += __shfl_xor(ps, 32, 64);
-      const float corr = (mrun[mt] == -INFINITY) ? 0.f : expf(mrun[mt] - mn);
-      lrun[mt] = lrun[mt] * corr + ps;
-      mrun[mt] = mn;
-#pragma unroll
-      for (int dt = 0; dt < DTS; ++dt) {
-        acc[dt][mt] *= corr;
-        acc[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[dt], pb, acc[dt][mt], 0, 0, 0);
-      }
+        for (int pq = 0; pq < QL; ++pq) sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][kt], q[kt][mt][pq], sacc, 0, 0, 0);
+      st[t] = sacc;
     }
+    const int pos = pos0 + mt * 16 + j;                // this lane's query row
+    float sv[8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int key = kk + 16 * t + 4 * g + r;
+        const float v = (key <= pos && key < n_keys) ? st[t][r] * scale : -INFINITY;
+        sv[t * 4 + r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(mrun[mt], mx);
+    float ps = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float pe = (mn == -INFINITY) ? 0.f : expf(sv[e] - mn);
+      ps += pe;
+      pb[e] = (_Float16)pe;
+    }
+    ps += __shfl_xor(ps, 16, 64);
+    ps += __shfl_xor(ps, 32, 64);
+    corr = (mrun[mt] == -INFINITY) ? 0.f : expf(mrun[mt] - mn);
+    lrun[mt] = lrun[mt] * corr + ps;
+    mrun[mt] = mn;
   };
-  // the wave's 32-key groups; with one row tile there are registers to keep the next group's loads in
-  // flight while the current one is used
-  if (MT == 1) {
-    half8 ka0[2][KTS], ka1[2][KTS], va0[DTS], va1[DTS];
-    int kk = ks_begin + 32 * wave;
-    if (kk < ks_end) load_kv(kk, ka0, va0);
-    while (kk < ks_end) {
-      const int k1 = kk + 32 * NW;
-      if (k1 < ks_end) load_kv(k1, ka1, va1);
-      step(kk, ka0, va0);
-      kk = k1;
-      if (kk >= ks_end) break;
-      const int k2 = kk + 32 * NW;
-      if (k2 < ks_end) load_kv(k2, ka0, va0);
-      step(kk, ka1, va1);
-      kk = k2;
-    }
-  } else {
-    half8 ka0[2][KTS], va0[DTS];
-    for (int kk = ks_begin + 32 * wave; kk < ks_end; kk += 32 * NW) {
-      load_kv(kk, ka0, va0);
-      step(kk, ka0, va0);
+  {
+    const int wv = __builtin_amdgcn_readfirstlane(wave);           // scalar: the loop below is uniform per wave
+    const int first = ks_begin + 32 * wv;
+    const int G = first < ks_end ? (ks_end - first + 32 * NW - 1) / (32 * NW) : 0;
+    if (G > 0) {
+      half8 ka[2][KTS], va[DTS];
+      __builtin_amdgcn_sched_barrier(0);
+      load_k(first, ka);
+      __builtin_amdgcn_sched_barrier(0);
+      load_v(first, va);
+      __builtin_amdgcn_sched_barrier(0);
+      for (int gi = 0; gi < G; ++gi) {
+        const int kk = first + gi * (32 * NW), kn = first + min(gi + 1, G - 1) * (32 * NW);
+        half8 pb[MT];
+        float corr[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) scores(kk, mt, ka, pb[mt], corr[mt]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_k(kn, ka);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int dt = 0; dt < DTS; ++dt) {
+            acc[dt][mt] *= corr[mt];
+            acc[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[dt], pb[mt], acc[dt][mt], 0, 0, 0);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+        load_v(kn, va);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
 

@@ -730,6 +730,8 @@ int32_t pacer_bind_kv(pacer_ctx* c, int32_t which, void* p, uint64_t nbytes) {
   if (nbytes != pacer_kv_bytes(c, which)) return fail(c, PACER_EINVAL, "bind_kv: expected %llu bytes",
                                                       (unsigned long long)pacer_kv_bytes(c, which));
   if (reinterpret_cast<uintptr_t>(p) % 16) return fail(c, PACER_EINVAL, "bind_kv: pointer must be 16-byte aligned");
+  // attention reads whole 32-position groups; slots past a sequence's end must hold finite values
+  HIPCHK(c, hipMemsetAsync(p, 0, nbytes, c->stream));
   c->m[which].kv = p;
   return PACER_OK;
 }
