@@ -285,14 +285,29 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
         else launch_w16<EPI, TAG, 1, 2, 1, 8, 2>(c, ga, n_tiles);
       }
     } else {
+      // Output tiles per wave (NT): a wave's tiles share one fetch of the operand, so more is better, but the
+      // launch is only as fast as its busiest CU: blocks should come in multiples of the 256 CUs.  Cost model:
+      // ceil(blocks / 256) * NT; ties go to two tiles for very wide matrices, else to the larger NT.
+      // (7B QKV, 768 tiles: NT 3 = 256 blocks, 17 us; NT 4 = 192 blocks, 19.5 us; NT 2 = 384 blocks, 21 us.)
+      int nt = 1;
+      if (many) {
+        int best = 1 << 30;
+        for (int cand : {2, 3, 4}) {
+          if (n_tiles % cand) continue;
+          const int units = (n_tiles / cand + 255) / 256 * cand;
+          const bool tie_wins = n_tiles >= 1024 ? false : true;          // candidates come in increasing order
+          if (units < best || (units == best && tie_wins)) { best = units; nt = cand; }
+        }
+      }
       if (mt == 1) {
-        // QKV (768 tiles at d 4096): four output tiles per wave share one fetch of the operand
-        if (EPI == EPI_QKV && many && n_tiles % 4 == 0 && n_tiles < 1024 && rows > 8) launch_w16<EPI, TAG, 2, 1, 4, 8, 1>(c, ga, n_tiles);
-        else if (many && even && (n_tiles >= 1024 || rows > 8)) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
+        if (nt == 4) launch_w16<EPI, TAG, 2, 1, 4, 8, 1>(c, ga, n_tiles);
+        else if (nt == 3) launch_w16<EPI, TAG, 2, 1, 3, 8, 1>(c, ga, n_tiles);
+        else if (nt == 2) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 1, 1, 8, 1>(c, ga, n_tiles);
       } else if (rows == 17) {
-        if (EPI == EPI_QKV && many && n_tiles % 4 == 0 && n_tiles < 1024) launch_w16<EPI, TAG, 2, 2, 4, 8, 1, 1>(c, ga, n_tiles);
-        else if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2, 1>(c, ga, n_tiles);
+        if (nt == 4) launch_w16<EPI, TAG, 2, 2, 4, 8, 1, 1>(c, ga, n_tiles);
+        else if (nt == 3) launch_w16<EPI, TAG, 2, 2, 3, 8, 1, 1>(c, ga, n_tiles);
+        else if (nt == 2) launch_w16<EPI, TAG, 2, 2, 2, 4, 2, 1>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 2, 1, 8, 1, 1>(c, ga, n_tiles);
       } else {
         if (many && even) launch_w16<EPI, TAG, 2, 2, 2, 4, 2>(c, ga, n_tiles);
