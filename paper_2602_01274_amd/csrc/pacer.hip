@@ -202,41 +202,72 @@ void launch_w16(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
 }
 
 // More than 32 rows: one launch of the wide kernel (operand shared through LDS, weights read once).
+// K slices hand their sums over through the operand buffers: do they fit?
+constexpr bool wide_fits(int hl, int mtb, int ntw, int ks) {
+  return ks == 1 || 4 * ntw * mtb <= ks * 2 * (4 / ks) * ((mtb * hl + 3) / 4) * 4;
+}
 template <int EPI, int TAG, int HL, int MTB, int NTW, int KS>
 void launch_wide_shape(pacer_ctx* c, const GemmArgs& ga, int n_tiles, int row_groups) {
+  if constexpr (!wide_fits(HL, MTB, NTW, KS)) {
+    (void)fail(c, PACER_EINVAL, "wide GEMM shape %d x %d with %d K slices does not exist", NTW, MTB, KS);
+    return;
+  } else {
   const int n_groups = (n_tiles + 4 * NTW - 1) / (4 * NTW);
   const dim3 grid((unsigned)((n_groups + 7) / 8 * 8 * row_groups));
   hipLaunchKernelGGL((gemm_wide_kernel<EPI, NTW, MTB, HL, TAG, KS>), grid, dim3(256 * KS), 0, c->stream, ga, n_tiles, n_groups, row_groups);
-}
-template <int EPI, int TAG, int HL, int MTB>
-void launch_wide_mtb(pacer_ctx* c, GemmArgs ga, int n_tiles) {
-  const int row_groups = (ga.mt_total + MTB - 1) / MTB;
-  ga.mt0 = 0;
-  if constexpr (TAG != 0) {   // draft and pre-verification layer: small matrices, one shape
-    launch_wide_shape<EPI, TAG, HL, MTB, 2, 1>(c, ga, n_tiles, row_groups);
-  } else {
-  // Output tiles per wave (NTW): blocks run two to a CU, so the launch takes about
-  // ceil(blocks / 256) * NTW units; pick the NTW with the fewest units, the larger one on a tie (it reads
-  // the operand from LDS less often).  Few output tiles (O and down projections): one tile per wave, so
-  // that there are about as many blocks as CUs, and K split over two or four slices of waves (at 144 rows
-  // the 13B down projection takes 79 us with one tile per wave, 105 us with two and half the CUs idle).
-  auto blocks = [&](int ntw) { return (n_tiles + 4 * ntw - 1) / (4 * ntw) * row_groups; };
-  auto units = [&](int ntw) { return (blocks(ntw) + 255) / 256 * ntw; };
-  if (blocks(1) <= 128 && ga.KT % 16 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 1, 4>(c, ga, n_tiles, row_groups);
-  else if (blocks(1) <= 256 && ga.KT % 8 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 1, 2>(c, ga, n_tiles, row_groups);
-  else if (blocks(2) <= 256 && ga.KT % 8 == 0) launch_wide_shape<EPI, TAG, HL, MTB, 2, 2>(c, ga, n_tiles, row_groups);
-  else if (units(4) <= units(3) && units(4) <= units(2)) launch_wide_shape<EPI, TAG, HL, MTB, 4, 1>(c, ga, n_tiles, row_groups);
-  else if (units(3) <= units(2)) launch_wide_shape<EPI, TAG, HL, MTB, 3, 1>(c, ga, n_tiles, row_groups);
-  else launch_wide_shape<EPI, TAG, HL, MTB, 2, 1>(c, ga, n_tiles, row_groups);
   }
 }
+// Shape of a wide launch: row tiles per block (MTB), output tiles per wave (NTW), K slices (KS).
+// A block always multiplies MTB row tiles (a short group repeats its last tile).  The launch moves
+//   row_groups x weights  +  blocks x (the block's operand rows)
+// through the L2s, which is what bounds it (about 12 TB/s measured), and it is only as fast as its busiest
+// CU, so the estimate is that traffic times ceil(blocks / 256) / (blocks / 256).  Checked against
+// microbenchmarks of the 13B-width matrices at 96..272 rows (random data): the estimate ranks the shapes
+// as measured (e.g. QKV at 144 rows: 3 tiles x 3 row tiles = 240 blocks 61 us, 4 x 4 = 180 blocks 91 us; at
+// 160 rows 3 x 4 = 240 blocks 74 us, 3 x 3 = 320 blocks 105 us).  Up to 256 blocks: two K slices of waves
+// per block (8 waves on the CU); up to 128 blocks of one tile per wave: four.
+struct WideShape { int mtb, ntw, ks; };
+WideShape pick_wide_shape(int n_tiles, int mt_total, int KT, int hl) {
+  WideShape best{4, 2, 1};
+  double best_est = 1e300;
+  for (int mtb = 3; mtb <= 4; ++mtb) {
+    const int rg = (mt_total + mtb - 1) / mtb;
+    for (int ntw = 1; ntw <= 4; ++ntw) {
+      const int blocks = (n_tiles + 4 * ntw - 1) / (4 * ntw) * rg;
+      int ks = 1;
+      if (blocks <= 128 && ntw == 1 && KT % 16 == 0) ks = 4;
+      else if (blocks <= 256 && KT % 8 == 0) ks = 2;
+      if (!wide_fits(hl, mtb, ntw, ks)) ks = 1;
+      if (ks == 1 && ntw == 1) continue;              // one tile per wave exists only with K slices
+      const double traffic = (double)rg * n_tiles * 32.0 + (double)blocks * mtb * 64.0;
+      const double est = traffic * ((blocks + 255) / 256) * 256.0 / blocks;
+      if (est < best_est * 0.999 || (est < best_est * 1.001 && ntw > best.ntw)) { best_est = est; best = {mtb, ntw, ks}; }
+    }
+  }
+  return best;
+}
 template <int EPI, int TAG, int HL>
-void launch_wide(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
-  // row tiles per block: a block always multiplies MTB row tiles (a short group repeats its last tile), so
-  // the target model picks 3 or 4, whichever wastes fewer; equal waste -> 4 (fewer readers per weight tile)
-  const int mt = ga.mt_total;
-  if (TAG == 0 && (mt + 2) / 3 * 3 < (mt + 3) / 4 * 4) launch_wide_mtb<EPI, TAG, HL, (TAG == 0 ? 3 : 4)>(c, ga, n_tiles);
-  else launch_wide_mtb<EPI, TAG, HL, 4>(c, ga, n_tiles);
+void launch_wide(pacer_ctx* c, GemmArgs ga, int n_tiles) {
+  ga.mt0 = 0;
+  if constexpr (TAG != 0) {   // draft and pre-verification layer: small matrices, one shape
+    launch_wide_shape<EPI, TAG, HL, 4, 2, 1>(c, ga, n_tiles, (ga.mt_total + 3) / 4);
+  } else {
+    const WideShape w = pick_wide_shape(n_tiles, ga.mt_total, ga.KT, HL);
+    const int rg = (ga.mt_total + w.mtb - 1) / w.mtb;
+#define PACER_WIDE(MTB_, NTW_, KS_) launch_wide_shape<EPI, TAG, HL, MTB_, NTW_, KS_>(c, ga, n_tiles, rg)
+#define PACER_WIDE_MTB(MTB_)                                                     \
+    if (w.ks == 4) PACER_WIDE(MTB_, 1, 4);                                       \
+    else if (w.ks == 2) {                                                        \
+      if (w.ntw == 1) PACER_WIDE(MTB_, 1, 2); else if (w.ntw == 2) PACER_WIDE(MTB_, 2, 2); \
+      else if (w.ntw == 3) PACER_WIDE(MTB_, 3, 2); else PACER_WIDE(MTB_, 4, 2);  \
+    } else {                                                                     \
+      if (w.ntw == 2) PACER_WIDE(MTB_, 2, 1); else if (w.ntw == 3) PACER_WIDE(MTB_, 3, 1); \
+      else PACER_WIDE(MTB_, 4, 1);                                               \
+    }
+    if (w.mtb == 3) { PACER_WIDE_MTB(3) } else { PACER_WIDE_MTB(4) }
+#undef PACER_WIDE_MTB
+#undef PACER_WIDE
+  }
 }
 
 // Launches the GEMM over `n_tiles` output tiles starting at ga.nt_begin; up to 32 rows with the
