@@ -127,12 +127,16 @@ __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __re
   const int si = find_seq(sr, r);
   const int s = sr.seq[si];
   const int p = sr.pos0[si] + (r - sr.row_off[si]);
-  rope_row(rope, r, p, hd, theta);
+  // the token id first: the rotation table's double-precision arithmetic then runs while that load (and the
+  // embedding row's, which depends on it) is in flight
   const int tok = p < sr.len[si] ? tokens[(size_t)s * max_seq + p] : draft_tok[s * G1 + (p - sr.len[si])];
   const uint16_t* e = E + (size_t)tok * d;
+  uint2 w0 = {0u, 0u};
+  if ((int)threadIdx.x * 4 < d) w0 = *reinterpret_cast<const uint2*>(e + threadIdx.x * 4);
+  rope_row(rope, r, p, hd, theta);
   float ss = 0.f;
   for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
-    const uint2 w = *reinterpret_cast<const uint2*>(e + k);
+    const uint2 w = k == (int)threadIdx.x * 4 ? w0 : *reinterpret_cast<const uint2*>(e + k);
     const float v0 = __uint_as_float(w.x << 16), v1 = __uint_as_float(w.x & 0xffff0000u);
     const float v2 = __uint_as_float(w.y << 16), v3 = __uint_as_float(w.y & 0xffff0000u);
     *reinterpret_cast<float4*>(x + (size_t)r * ldx + k) = make_float4(v0, v1, v2, v3);
@@ -152,12 +156,15 @@ __global__ void mb_input_w16_kernel(const float* __restrict__ src, int lds, cons
   const int r = blockIdx.x;
   const int si = find_seq(sr, r);
   const int rr = r - sr.row_off[si];
-  rope_row(rope, r, sr.pos0[si] + rr, hd, theta);
   const float* h = src + (size_t)(mr.src_row0[si] + rr) * lds;
   const float* e = posemb + (size_t)(mr.e0[si] < 0 ? 0 : mr.e0[si] + rr) * d;
+  float4 a0 = {0.f, 0.f, 0.f, 0.f}, b0 = a0;          // first chunk requested before the rotation table's arithmetic
+  if ((int)threadIdx.x * 4 < d) { a0 = *reinterpret_cast<const float4*>(h + threadIdx.x * 4); b0 = *reinterpret_cast<const float4*>(e + threadIdx.x * 4); }
+  rope_row(rope, r, sr.pos0[si] + rr, hd, theta);
   float ss = 0.f;
   for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
-    const float4 a = *reinterpret_cast<const float4*>(h + k), b = *reinterpret_cast<const float4*>(e + k);
+    const bool first = k == (int)threadIdx.x * 4;
+    const float4 a = first ? a0 : *reinterpret_cast<const float4*>(h + k), b = first ? b0 : *reinterpret_cast<const float4*>(e + k);
     const float v0 = a.x + b.x, v1 = a.y + b.y, v2 = a.z + b.z, v3 = a.w + b.w;
     *reinterpret_cast<float4*>(x + (size_t)r * ldx + k) = make_float4(v0, v1, v2, v3);
     store_packed4(xp, MT_total, r, k, v0 * g[k], v1 * g[k + 1], v2 * g[k + 2], v3 * g[k + 3]);
@@ -860,15 +867,45 @@ __global__ void draft_tail_kernel(const float* __restrict__ x, int ldx, const fl
   __shared__ float redv[16];
   __shared__ int redi[16];
   const int si = blockIdx.x, s = pa.seq[si], j = pa.j[si];
+  // every input is requested before anything is used: the kernel is a chain of memory round trips otherwise
+  constexpr int XMAX = 8, CMAX = 16;                   // d <= 2048 and <= 4096 candidate tiles stay in registers
+  float xv[XMAX], gv[XMAX], cv[CMAX];
+  int ci[CMAX];
+  const bool in_regs = d <= XMAX * (int)blockDim.x && pick_tiles <= CMAX * (int)blockDim.x;
+  if (in_regs) {
+#pragma unroll
+    for (int u = 0; u < CMAX; ++u) {
+      const int t = threadIdx.x + u * blockDim.x;
+      cv[u] = t < pick_tiles ? pick_val[(size_t)si * pick_tiles + t] : -INFINITY;
+      ci[u] = t < pick_tiles ? pick_idx[(size_t)si * pick_tiles + t] : 0x7fffffff;
+    }
+#pragma unroll
+    for (int u = 0; u < XMAX; ++u) {
+      const int k = threadIdx.x + u * blockDim.x;
+      xv[u] = k < d ? x[(size_t)si * ldx + k] : 0.f;
+      gv[u] = k < d ? g[k] : 0.f;
+    }
+  }
   const float rs = row_scale(ssq, ssq_stride, si, inv_dim, eps);
   float* ho = hidden + (size_t)(s * G1 + j) * d;
-  for (int k = threadIdx.x; k < d; k += blockDim.x) ho[k] = x[(size_t)si * ldx + k] * g[k] * rs;
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int t = threadIdx.x; t < pick_tiles; t += blockDim.x) {
-    const float v = pick_val[(size_t)si * pick_tiles + t];
-    const int i = pick_idx[(size_t)si * pick_tiles + t];
-    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+  if (in_regs) {
+#pragma unroll
+    for (int u = 0; u < XMAX; ++u) {
+      const int k = threadIdx.x + u * blockDim.x;
+      if (k < d) ho[k] = xv[u] * gv[u] * rs;
+    }
+#pragma unroll
+    for (int u = 0; u < CMAX; ++u)
+      if (cv[u] > best || (cv[u] == best && ci[u] < bi)) { best = cv[u]; bi = ci[u]; }
+  } else {
+    for (int k = threadIdx.x; k < d; k += blockDim.x) ho[k] = x[(size_t)si * ldx + k] * g[k] * rs;
+    for (int t = threadIdx.x; t < pick_tiles; t += blockDim.x) {
+      const float v = pick_val[(size_t)si * pick_tiles + t];
+      const int i = pick_idx[(size_t)si * pick_tiles + t];
+      if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+    }
   }
   block_argmax(best, bi, redv, redi);
   if (threadIdx.x == 0) draft_tok[s * G1 + j] = bi;
