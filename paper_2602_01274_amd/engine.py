@@ -15,9 +15,10 @@ def _dev(t, dtype=None):
 
 class Session:
     def __init__(self, w, target, draft, preverify, max_seq, max_batch=1, t0=None, rho=None,
-                 block=None, gamma_max=None, halting=B.HALT_MEAN):
+                 block=None, gamma_max=None, halting=B.HALT_MEAN, kv_fill=None):
         """w: workload description (synth.workload); target/draft/preverify: weight dicts
-        (linear weights [out, in]; any device)."""
+        (linear weights [out, in]; any device).  kv_fill: byte value the KV buffers are filled with
+        before they are handed over (tests: the library must not depend on their contents)."""
         assert torch.cuda.is_available(), "the Pacer hot path needs a GPU"
         self.w = w
         self.dtype = w["dtype"]
@@ -43,6 +44,8 @@ class Session:
         self._bind_f32(B.PREVERIFY, B.T_CLS, 0, preverify["cls"])
         for which in (B.TARGET, B.DRAFT, B.PREVERIFY):
             kv = torch.empty(B.pacer_kv_bytes(self.ctx, which), dtype=torch.uint8, device="cuda")
+            if kv_fill is not None:
+                kv.fill_(kv_fill)
             self.keep.append(kv)
             B.pacer_bind_kv(self.ctx, which, kv)
         self.ws = torch.empty(B.pacer_workspace_bytes(self.ctx) + 256, dtype=torch.uint8, device="cuda")

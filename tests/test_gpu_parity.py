@@ -18,12 +18,12 @@ def _session(w, tgt, drf, mb, max_seq, **kw):
 
 
 def _run(name, n_prompt, n_new, tol_logits, tol_alpha, mode=po.GREEDY, seed=0, gain_jitter=0.1,
-         max_seq=512, step_kw=None, w_over=None, n_layers_target=None, halting="mean"):
+         max_seq=512, step_kw=None, w_over=None, n_layers_target=None, halting="mean", kv_fill=None):
     w = synth.workload(name)
     w.update(w_over or {})
     tgt, drf, mb = synth.make_pair(w, seed=0, gain_jitter=gain_jitter, n_layers_target=n_layers_target)
     prompt = synth.make_prompt(w["target"]["vocab"], n_prompt, 1).tolist()
-    s = _session(w, tgt, drf, mb, max_seq, halting={"mean": 0, "any": 1, "last": 2}[halting])
+    s = _session(w, tgt, drf, mb, max_seq, halting={"mean": 0, "any": 1, "last": 2}[halting], kv_fill=kv_fill)
     o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=seed, max_seq=max_seq, cache=True, halting=halting)
     s.prefill(prompt)
     o.prefill(prompt)
@@ -80,6 +80,14 @@ def test_mid_bf16_greedy_steps_match_oracle():
     """Workload `mid` (12-layer d768 V32000 target, 2-layer draft, bf16, b 4, gamma_max 12);
     the context crosses several 64-key attention tiles."""
     _run("mid", 150, 40, tol_logits=2e-2, tol_alpha=2e-2)
+
+
+def test_kv_buffers_full_of_nans_do_not_matter():
+    """Attention reads whole 32-position groups of the cache, including slots past the sequence's end; the
+    caller's buffers arrive here with every byte 0xFF (f16 and f32 NaNs) and the results must not change:
+    the library clears what it is given.  Prompt lengths that leave partly filled groups, both paths."""
+    _run("mid", 45, 12, tol_logits=2e-2, tol_alpha=2e-2, kv_fill=0xFF)
+    _run("tiny", 21, 12, tol_logits=1e-4, tol_alpha=1e-4, kv_fill=0xFF)
 
 
 def test_mid_bf16_sampling_steps_match_oracle():
