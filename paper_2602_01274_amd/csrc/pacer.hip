@@ -274,11 +274,12 @@ void launch_wide(pacer_ctx* c, GemmArgs ga, int n_tiles) {
 // weight-streaming kernel, more with the wide one.
 // HL = 2: multiply the operand's hi and lo tiles (target model, all GEMMs but the O projection and the
 // LM head, whose inputs' f16 rounding hardly shows in the logits); HL = 1: hi only.
-// Launch shapes, all measured on MI355X.  HL = 1: >= 512 output tiles -> 4 waves per block, 8 K steps
-// in flight; fewer tiles (O and down projections) -> 8 waves split K, held to 128 VGPRs so two blocks
-// fit a CU.  HL = 2 doubles the operand traffic from L2, which becomes the limiter as rows grow, so wide
-// GEMMs give each wave two output tiles that share the operand registers.  17 rows exactly (full window
-// + committed token): the second row tile is reduced to its one live column (X17).
+// Launch shapes <MT, NT, WAVES, U>, all measured on MI355X (U = K steps per register set; the loop keeps
+// two sets in flight, so one or two steps per set is enough).  Few tiles (O and down projections): 8 waves
+// split K, one tile per block, held to 128 VGPRs so that two blocks fit a CU.  Many tiles: the waves of a
+// block share an operand fetch among NT tiles; HL = 2 doubles the operand traffic from L2, which becomes
+// the limiter as rows grow.  17 rows exactly (full window + committed token): the second row tile is
+// reduced to its one live column (X17).
 // TAG gives the target model's launches their own kernel symbols; the GEMM profile counts those.
 template <int EPI, int TAG, int HL>
 void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
