@@ -655,15 +655,19 @@ __global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(
 template <int HD, int MT, int QL>
 __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restrict__ qp, const _Float16* __restrict__ kv, int layer,
                                                         int n_layers, int max_seq, int d, SeqRows sr, int kps, int S, int H,
-                                                        float* __restrict__ part, _Float16* __restrict__ xp_out, int MT_total_out) {
+                                                        float* __restrict__ part, _Float16* __restrict__ xp_out, int MT_total_out,
+                                                        int rt_split) {
   constexpr int KTS = HD / 32, DTS = HD / 16, NW = 8;
   extern __shared__ __align__(16) float att_state[];   // [8 waves][live rows][HD + 4]: values, running max, running sum
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
-  const int split = blockIdx.x, h = blockIdx.y, si = blockIdx.z;
-  const int r0 = sr.row_off[si], Rs = sr.row_off[si + 1] - r0, pos0 = sr.pos0[si];
-  const int n_keys = pos0 + Rs;
+  // rt_split (MT == 1 launches only): two blocks per key range, one per 16-row tile of the sequence
+  const int rt = rt_split ? (int)(blockIdx.x & 1) : 0;
+  const int split = rt_split ? (int)(blockIdx.x >> 1) : (int)blockIdx.x, h = blockIdx.y, si = blockIdx.z;
+  const int r0 = sr.row_off[si] + rt * 16, pos0 = sr.pos0[si];
+  const int n_keys = pos0 + sr.row_off[si + 1] - sr.row_off[si];
+  const int Rs = sr.row_off[si + 1] - r0;                // rows from this block's first one to the sequence's last
   const int n_split = (n_keys + kps - 1) / kps;
-  if (split >= n_split) return;
+  if (split >= n_split || Rs <= 0) return;
   const int ks_begin = split * kps, ks_end = min(n_keys, ks_begin + kps);
   const _Float16* Kc = kv + (((size_t)sr.seq[si] * n_layers + layer) * 2) * (size_t)max_seq * d + (size_t)h * HD * max_seq;
   const _Float16* Vt = Kc + (size_t)max_seq * d;
@@ -677,7 +681,7 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int pq = 0; pq < QL; ++pq)
-        q[kt][mt][pq] = *reinterpret_cast<const half8*>(qp + (((((size_t)si * H + h) * KTS + kt) * 2 + mt) * 2 + pq) * 512 + lane * 8);
+        q[kt][mt][pq] = *reinterpret_cast<const half8*>(qp + (((((size_t)si * H + h) * KTS + kt) * 2 + rt + mt) * 2 + pq) * 512 + lane * 8);
   f32x4 acc[DTS][MT];
   float mrun[MT], lrun[MT];
 #pragma unroll
@@ -721,7 +725,7 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
         for (int pq = 0; pq < QL; ++pq) sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][kt], q[kt][mt][pq], sacc, 0, 0, 0);
       st[t] = sacc;
     }
-    const int pos = pos0 + mt * 16 + j;                // this lane's query row
+    const int pos = pos0 + (rt + mt) * 16 + j;         // this lane's query row
     float sv[8];
     float mx = -INFINITY;
 #pragma unroll
@@ -753,6 +757,16 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
     const int wv = __builtin_amdgcn_readfirstlane(wave);           // scalar: the loop below is uniform per wave
     const int first = ks_begin + 32 * wv;
     const int G = first < ks_end ? (ks_end - first + 32 * NW - 1) / (32 * NW) : 0;
+    auto values = [&](half8(&va)[DTS], half8(&pb)[MT], float(&corr)[MT]) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int dt = 0; dt < DTS; ++dt) {
+          acc[dt][mt] *= corr[mt];
+          acc[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[dt], pb[mt], acc[dt][mt], 0, 0, 0);
+        }
+    };
+    auto key_of = [&](int gi) { return first + min(gi, G - 1) * (32 * NW); };
     if (G > 0) {
       half8 ka[2][KTS], va[DTS];
       __builtin_amdgcn_sched_barrier(0);
@@ -761,7 +775,7 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
       load_v(first, va);
       __builtin_amdgcn_sched_barrier(0);
       for (int gi = 0; gi < G; ++gi) {
-        const int kk = first + gi * (32 * NW), kn = first + min(gi + 1, G - 1) * (32 * NW);
+        const int kk = key_of(gi), kn = key_of(gi + 1);
         half8 pb[MT];
         float corr[MT];
 #pragma unroll
@@ -769,13 +783,7 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
         __builtin_amdgcn_sched_barrier(0);
         load_k(kn, ka);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int dt = 0; dt < DTS; ++dt) {
-            acc[dt][mt] *= corr[mt];
-            acc[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[dt], pb[mt], acc[dt][mt], 0, 0, 0);
-          }
+        values(va, pb, corr);
         __builtin_amdgcn_sched_barrier(0);
         load_v(kn, va);
         __builtin_amdgcn_sched_barrier(0);

@@ -415,16 +415,23 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
     }
     if (kv_only) continue;
     {
-      const dim3 grid(S, H, sr.n_seqs);
       const _Float16* kv = static_cast<const _Float16*>(m.kv);
+      // 17..32 rows per sequence: two row tiles.  With a short context and few (head, sequence) pairs the
+      // launch is a chain of memory latencies on a few dozen CUs, and the one-tile kernel run as two blocks
+      // per pair, one per row tile, is faster than the two-tile kernel although it reads the keys twice
+      // (7B shape, 550 keys, warm cache: 7.1 us against 10.0 us).  Long contexts and batches are bound by the
+      // cache traffic and keep the two-tile kernel.
+      const bool rt_split = max_rows > 16 && S == 1 && max_keys < 2048 && H * sr.n_seqs <= 64;
+      const int mrows = rt_split ? 16 : max_rows;
+      const dim3 grid(rt_split ? 2 * S : S, H, sr.n_seqs);
       // LDS for the wave states: 8 waves x live rows x (hd + 4) floats
-#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), (size_t)8 * std::min(max_rows, MT_ * 16) * (HD_ + 4) * 4, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total)
+#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), (size_t)8 * std::min(mrows, MT_ * 16) * (HD_ + 4) * 4, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total, rt_split ? 1 : 0)
       if (tag == 0) {
-        if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2, 2); else PACER_ATT(128, 1, 2); }
-        else           { if (max_rows > 16) PACER_ATT(64, 2, 2); else PACER_ATT(64, 1, 2); }
+        if (hd == 128) { if (mrows > 16) PACER_ATT(128, 2, 2); else PACER_ATT(128, 1, 2); }
+        else           { if (mrows > 16) PACER_ATT(64, 2, 2); else PACER_ATT(64, 1, 2); }
       } else {
-        if (hd == 128) { if (max_rows > 16) PACER_ATT(128, 2, 1); else PACER_ATT(128, 1, 1); }
-        else           { if (max_rows > 16) PACER_ATT(64, 2, 1); else PACER_ATT(64, 1, 1); }
+        if (hd == 128) { if (mrows > 16) PACER_ATT(128, 2, 1); else PACER_ATT(128, 1, 1); }
+        else           { if (mrows > 16) PACER_ATT(64, 2, 1); else PACER_ATT(64, 1, 1); }
       }
 #undef PACER_ATT
       if (S > 1) {
