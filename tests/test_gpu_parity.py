@@ -171,6 +171,12 @@ def test_batch_mid_bf16_bonus_row_for_part_of_the_batch():
         assert any(not f[0] and any(f[1:]) for f in full)      # a later sequence without the first: slot != index
 
 
+def test_7b_width_two_sequences_full_windows():
+    """Two sequences with 17 verify rows each (fixed window of 16) at the 7B width: 34 rows go through the
+    wide GEMM, and attention runs as two one-tile blocks per (head, sequence)."""
+    _run_batch("7b", [40, 75], [3.0, 4.0], 2, 2e-2, 2e-2, n_layers_target=2, fixed_gamma=16, ragged=False, max_seq=160)
+
+
 def test_batch_mid_bf16_eight_sequences_wide_gemm():
     """8 sequences x up to 13 verify rows = up to 104 rows: the wide GEMM with several row groups per
     output-tile group, ragged last row tile, per-sequence attention over different lengths."""
