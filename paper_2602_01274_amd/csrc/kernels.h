@@ -551,7 +551,7 @@ struct AccArgs { int n_seqs; int seq[PK_MAXB]; int slot[PK_MAXB]; int gamma[PK_M
 //   accept_finalize_kernel per sequence: best candidate over the chunks of each row, first rejection, tokens
 // Rows i < gamma first; the bonus row i = gamma (whose draft logits cost one more draft forward) only for the
 // sequences that turn out to have accepted every draft.
-#define ACC_CHUNKS 8
+#define ACC_CHUNKS 16
 #define ACC_PART 8      // floats per (row, chunk): [0..3] = mp, sp, mq, sq ; [4..7] = best, bi, bestp, bip
 
 __device__ __forceinline__ void acc_chunk_range(int V, int chunk, int& v0, int& v1) {
