@@ -196,6 +196,7 @@ struct GemmArgs {
   const u32x4* W;        // packed weights
   const u32x4* X;        // packed f16 operand [kt][mt_total][lane]
   int KT, R, mt0, mt_total, nt_begin;
+  int nt_end;            // one past the last output tile (streaming kernel: blocks may overhang it)
   const u64* ssq_in;     // row sums of squares of the operand's source rows (null: no row scale)
   int ssq_stride;
   float inv_dim, eps;
@@ -355,9 +356,12 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& ga, int nt, int m,
 // HL = operand parts multiplied: 2 = hi and lo tiles (the target model's QKV, gate/up and down GEMMs),
 // 1 = hi only (draft and pre-verification layer: two layers deep, their logits stay at 4e-3 of the RMS).
 template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0, int HL = 1>
-__global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_kernel(const GemmArgs ga) {
+__global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) void gemm_w16_kernel(const GemmArgs ga) {
   static_assert(!X17 || MT == 2, "the 17-row form uses two row tiles");
-  __shared__ f32x4 red[WAVES][NT * MT][64];
+  // partial sums of the waves; more than 64 KB of them are handed over in two halves
+  constexpr int RW = (WAVES * NT * MT > 64) ? WAVES / 2 : WAVES;
+  static_assert(RW * NT * MT <= 64, "the reduction buffer must fit the 64 KB of static LDS");
+  __shared__ f32x4 red[RW][NT * MT][64];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id as a scalar
   const int nt0 = ga.nt_begin + blockIdx.x * NT;
   const int KT = ga.KT;
@@ -374,7 +378,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
     for (int b = 0; b < MT; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
   const u32x4* wp[NT];
 #pragma unroll
-  for (int a = 0; a < NT; ++a) wp[a] = ga.W + (size_t)(nt0 + a) * KT * 64 + lane;
+  for (int a = 0; a < NT; ++a) wp[a] = ga.W + (size_t)min(nt0 + a, ga.nt_end - 1) * KT * 64 + lane;   // a tile past the end repeats the last one, unused
   // Operand pointers, one per row tile.  Lanes whose row does not exist read the tile's last live row instead
   // (the same cache lines the live lanes fetch, and their accumulator columns are discarded): the operand
   // traffic scales with the number of rows, not with whole 16-row tiles, and no load is conditional.
@@ -449,10 +453,28 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
     compute(A1, B1, k0 + U);
     __builtin_amdgcn_sched_barrier(0);
   }
+  if (RW < WAVES) {
+    if (wave >= RW) {
 #pragma unroll
-  for (int a = 0; a < NT; ++a)
+      for (int a = 0; a < NT; ++a)
 #pragma unroll
-    for (int b = 0; b < MT; ++b) red[wave][a * MT + b][lane] = acc[a][b];
+        for (int b = 0; b < MT; ++b) red[wave - RW][a * MT + b][lane] = acc[a][b];
+    }
+    __syncthreads();
+    if (wave < RW) {
+#pragma unroll
+      for (int a = 0; a < NT; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[a][b] += red[wave][a * MT + b][lane];
+    }
+    __syncthreads();
+  }
+  if (wave < RW) {
+#pragma unroll
+    for (int a = 0; a < NT; ++a)
+#pragma unroll
+      for (int b = 0; b < MT; ++b) red[wave][a * MT + b][lane] = acc[a][b];
+  }
   __syncthreads();
 
   // Epilogue.  One wave-sized group of threads per (tile a, row tile b); thread l of the group owns the
@@ -463,22 +485,23 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? 4 : 1)) void gemm_w16_ker
     const int g4 = l >> 4;
     const int m = (ga.mt0 + b) * 16 + (l & 15);
     const int nt = nt0 + a;
+    if (nt >= ga.nt_end) continue;
     const bool paired = (EPI == EPI_SWIGLU) || (EPI == EPI_QKV);
     f32x4 s = red[0][ab][l];
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) s += red[w][ab][l];
+    for (int w = 1; w < RW; ++w) s += red[w][ab][l];
     f32x4 s2 = {0.f, 0.f, 0.f, 0.f};                   // partner rows i+8 (paired layouts, threads with g4 < 2)
     if (paired && g4 < 2) {
       s2 = red[0][ab][l + 32];
 #pragma unroll
-      for (int w = 1; w < WAVES; ++w) s2 += red[w][ab][l + 32];
+      for (int w = 1; w < RW; ++w) s2 += red[w][ab][l + 32];
     }
     if (X17 && HL == 2 && b == 1 && (l & 15) == 0) {   // row 16: hi product in column 0, lo product in column 1
 #pragma unroll
-      for (int w = 0; w < WAVES; ++w) s += red[w][ab][l + 1];
+      for (int w = 0; w < RW; ++w) s += red[w][ab][l + 1];
       if (paired && g4 < 2) {
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) s2 += red[w][ab][l + 33];
+        for (int w = 0; w < RW; ++w) s2 += red[w][ab][l + 33];
       }
     }
     gemm_epilogue<EPI>(ga, nt, m, l, s, s2);

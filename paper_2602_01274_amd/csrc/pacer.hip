@@ -198,7 +198,7 @@ u64* slot(pacer_ctx* c, int s) { return c->ssq + (size_t)s * SSQ_SUB * c->rcap; 
 
 template <int EPI, int TAG, int HL, int MT, int NT, int WAVES, int U, int X17 = 0>
 void launch_w16(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
-  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17, HL>), dim3(n_tiles / NT), dim3(WAVES * 64), 0, c->stream, ga);
+  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17, HL>), dim3((n_tiles + NT - 1) / NT), dim3(WAVES * 64), 0, c->stream, ga);
 }
 
 // More than 32 rows: one launch of the wide kernel (operand shared through LDS, weights read once).
@@ -286,6 +286,7 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
   const int mt_total = (ga.R + 15) / 16;
   ga.mt_total = mt_total;
   ga.KT = K / 32;
+  ga.nt_end = ga.nt_begin + n_tiles;
   const bool many = n_tiles >= 512;
   const bool even = n_tiles % 2 == 0;
   if (mt_total > 2 && ga.KT % 4 == 0) {
@@ -318,26 +319,38 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
       }
     } else {
       // Output tiles per wave (NT): a wave's tiles share one fetch of the operand, so more is better, but the
-      // launch is only as fast as its busiest CU: blocks should come in multiples of the 256 CUs.  Cost model:
-      // ceil(blocks / 256) * NT; ties go to two tiles for very wide matrices, else to the larger NT.
-      // (7B QKV, 768 tiles: NT 3 = 256 blocks, 17 us; NT 4 = 192 blocks, 19.5 us; NT 2 = 384 blocks, 21 us.)
+      // launch is only as fast as its busiest CU.  Cost model: ceil(blocks / 256) * NT with blocks =
+      // ceil(tiles / NT) (the last block may overhang).  Ties go to the shape with at most one block per CU
+      // (each CU then fetches the operand once), else to two tiles for very wide matrices, else to the larger NT.
+      // 7B QKV, 768 tiles: NT 3 = 256 blocks 17 us, NT 4 = 192 blocks 19.5 us, NT 2 = 384 blocks 21 us.
+      // 7B gate/up, 1376 tiles, 13 rows: NT 6 = 230 blocks 29.7 us (the weights-only time), NT 2 = 688 blocks 33.6 us.
       int nt = 1;
       if (many) {
         int best = 1 << 30;
-        for (int cand : {2, 3, 4}) {
-          if (n_tiles % cand) continue;
-          const int units = (n_tiles / cand + 255) / 256 * cand;
-          const bool tie_wins = n_tiles >= 1024 ? false : true;          // candidates come in increasing order
-          if (units < best || (units == best && tie_wins)) { best = units; nt = cand; }
+        bool best_single = false;
+        for (int cand : {2, 3, 4, 6, 7, 8}) {
+          if (cand > 4 && rows <= 8) break;              // up to 8 rows the operand is small and more blocks stream better
+          const int blocks = (n_tiles + cand - 1) / cand;
+          const int units = (blocks + 255) / 256 * cand;
+          const bool single = blocks <= 256;
+          bool take = units < best;
+          if (units == best) take = single ? !best_single : (!best_single && n_tiles < 1024);   // candidates come in increasing order
+          if (take) { best = units; nt = cand; best_single = single; }
         }
       }
       if (mt == 1) {
-        if (nt == 4) launch_w16<EPI, TAG, 2, 1, 4, 8, 1>(c, ga, n_tiles);
+        if (nt == 8) launch_w16<EPI, TAG, 2, 1, 8, 8, 1>(c, ga, n_tiles);
+        else if (nt == 7) launch_w16<EPI, TAG, 2, 1, 7, 8, 1>(c, ga, n_tiles);
+        else if (nt == 6) launch_w16<EPI, TAG, 2, 1, 6, 8, 1>(c, ga, n_tiles);
+        else if (nt == 4) launch_w16<EPI, TAG, 2, 1, 4, 8, 1>(c, ga, n_tiles);
         else if (nt == 3) launch_w16<EPI, TAG, 2, 1, 3, 8, 1>(c, ga, n_tiles);
         else if (nt == 2) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 1, 1, 8, 1>(c, ga, n_tiles);
       } else if (rows == 17) {
-        if (nt == 4) launch_w16<EPI, TAG, 2, 2, 4, 8, 1, 1>(c, ga, n_tiles);
+        if (nt == 8) launch_w16<EPI, TAG, 2, 2, 8, 8, 1, 1>(c, ga, n_tiles);
+        else if (nt == 7) launch_w16<EPI, TAG, 2, 2, 7, 8, 1, 1>(c, ga, n_tiles);
+        else if (nt == 6) launch_w16<EPI, TAG, 2, 2, 6, 8, 1, 1>(c, ga, n_tiles);
+        else if (nt == 4) launch_w16<EPI, TAG, 2, 2, 4, 8, 1, 1>(c, ga, n_tiles);
         else if (nt == 3) launch_w16<EPI, TAG, 2, 2, 3, 8, 1, 1>(c, ga, n_tiles);
         else if (nt == 2) launch_w16<EPI, TAG, 2, 2, 2, 4, 2, 1>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 2, 1, 8, 1, 1>(c, ga, n_tiles);
