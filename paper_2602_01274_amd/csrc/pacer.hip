@@ -328,7 +328,7 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
       if (many) {
         int best = 1 << 30;
         bool best_single = false;
-        for (int cand : {2, 3, 4, 6, 7, 8}) {
+        for (int cand : {2, 3, 4, 6, 7}) {
           if (cand > 4 && rows <= 8) break;              // up to 8 rows the operand is small and more blocks stream better
           const int blocks = (n_tiles + cand - 1) / cand;
           const int units = (blocks + 255) / 256 * cand;
@@ -339,16 +339,14 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
         }
       }
       if (mt == 1) {
-        if (nt == 8) launch_w16<EPI, TAG, 2, 1, 8, 8, 1>(c, ga, n_tiles);
-        else if (nt == 7) launch_w16<EPI, TAG, 2, 1, 7, 8, 1>(c, ga, n_tiles);
+        if (nt == 7) launch_w16<EPI, TAG, 2, 1, 7, 8, 1>(c, ga, n_tiles);
         else if (nt == 6) launch_w16<EPI, TAG, 2, 1, 6, 8, 1>(c, ga, n_tiles);
         else if (nt == 4) launch_w16<EPI, TAG, 2, 1, 4, 8, 1>(c, ga, n_tiles);
         else if (nt == 3) launch_w16<EPI, TAG, 2, 1, 3, 8, 1>(c, ga, n_tiles);
         else if (nt == 2) launch_w16<EPI, TAG, 2, 1, 2, 4, 4>(c, ga, n_tiles);
         else launch_w16<EPI, TAG, 2, 1, 1, 8, 1>(c, ga, n_tiles);
       } else if (rows == 17) {
-        if (nt == 8) launch_w16<EPI, TAG, 2, 2, 8, 8, 1, 1>(c, ga, n_tiles);
-        else if (nt == 7) launch_w16<EPI, TAG, 2, 2, 7, 8, 1, 1>(c, ga, n_tiles);
+        if (nt == 7) launch_w16<EPI, TAG, 2, 2, 7, 8, 1, 1>(c, ga, n_tiles);
         else if (nt == 6) launch_w16<EPI, TAG, 2, 2, 6, 8, 1, 1>(c, ga, n_tiles);
         else if (nt == 4) launch_w16<EPI, TAG, 2, 2, 4, 8, 1, 1>(c, ga, n_tiles);
         else if (nt == 3) launch_w16<EPI, TAG, 2, 2, 3, 8, 1, 1>(c, ga, n_tiles);
