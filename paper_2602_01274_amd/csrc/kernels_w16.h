@@ -223,12 +223,14 @@ struct GemmArgs {
 // tile rows (outputs) 4*(l/16)..+3 of activation row m; s2 holds the same for the partner outputs i+8
 // (paired weight layouts: rotation pairs of QKV, gate/up of SwiGLU; lanes with l/16 < 2).  All 64 lanes
 // of the tile call this together (the row reductions use wave shuffles).
+// ssq_pre: the row's sum of squares (the integer parts added up) if the caller fetched it ahead of time
 template <int EPI>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs& ga, int nt, int m, int l, f32x4 s, f32x4 s2) {
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& ga, int nt, int m, int l, f32x4 s, f32x4 s2, const u64* ssq_pre = nullptr) {
   const int g4 = l >> 4;
   const bool live = m < ga.R;
   float rs = 1.f;
-  if (ga.ssq_in && live) rs = row_scale(ga.ssq_in, ga.ssq_stride, m, ga.inv_dim, ga.eps);
+  if (ga.ssq_in && live)
+    rs = ssq_pre ? 1.0f / sqrtf((float)*ssq_pre * SSQ_INV_SCALE * ga.inv_dim + ga.eps) : row_scale(ga.ssq_in, ga.ssq_stride, m, ga.inv_dim, ga.eps);
 
   if (EPI == EPI_STORE) {
     const int n = nt * 16 + g4 * 4;
@@ -441,6 +443,19 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) v
   // Two register sets; each is refilled right after its products were issued, in the same order on every
   // path into the loop, and the scheduler may not move loads across the phase boundaries: the wait before
   // a phase's products then leaves the other set's loads in flight.
+  // The epilogue's row scale needs the operand rows' sums of squares: they are requested here, ahead of the
+  // weight stream, so that the epilogue does not end the kernel on one more memory round trip.
+  constexpr int EIT = (NT * MT * 64 + WAVES * 64 - 1) / (WAVES * 64);     // epilogue items per thread
+  u64 ssq_pre[EIT][SSQ_SUB];
+#pragma unroll
+  for (int it = 0; it < EIT; ++it) {
+    const int t = threadIdx.x + it * WAVES * 64;
+    const int m = (ga.mt0 + (t >> 6) % MT) * 16 + (t & 15);
+    const bool want = ga.ssq_in && t < NT * MT * 64 && m < ga.R;
+#pragma unroll
+    for (int i = 0; i < SSQ_SUB; ++i) ssq_pre[it][i] = want ? ga.ssq_in[(size_t)i * ga.ssq_stride + m] : 0ull;
+  }
+  __builtin_amdgcn_sched_barrier(0);
   load(A0, B0, kb);
   __builtin_amdgcn_sched_barrier(0);
   for (int k0 = kb; k0 < ke; k0 += 2 * U) {
@@ -479,7 +494,13 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) v
 
   // Epilogue.  One wave-sized group of threads per (tile a, row tile b); thread l of the group owns the
   // accumulator lane l: activation row m = 16*(mt0+b) + l%16, tile rows 4*(l/16)..+3.
-  for (int t = threadIdx.x; t < NT * MT * 64; t += WAVES * 64) {
+#pragma unroll
+  for (int it = 0; it < EIT; ++it) {
+    const int t = threadIdx.x + it * WAVES * 64;
+    if (t >= NT * MT * 64) break;
+    u64 ssq_sum = 0;
+#pragma unroll
+    for (int i = 0; i < SSQ_SUB; ++i) ssq_sum += ssq_pre[it][i];
     const int l = t & 63, ab = t >> 6;
     const int a = ab / MT, b = ab % MT;
     const int g4 = l >> 4;
@@ -504,7 +525,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) v
         for (int w = 0; w < RW; ++w) s2 += red[w][ab][l + 33];
       }
     }
-    gemm_epilogue<EPI>(ga, nt, m, l, s, s2);
+    gemm_epilogue<EPI>(ga, nt, m, l, s, s2, &ssq_sum);
   }
 }
 
