@@ -76,6 +76,12 @@ def test_halting_variants_any_and_last():
     assert g["any"] <= g["mean"] + 2      # per block 'any' stops whenever the mean does (step boundaries differ, so only roughly)
 
 
+def test_halting_variants_bf16_path():
+    """The same criteria through the bf16 path's pre-verification head kernel."""
+    for h in ("any", "last"):
+        _run("mid", 60, 16, tol_logits=2e-2, tol_alpha=2e-2, halting=h)
+
+
 def test_mid_bf16_greedy_steps_match_oracle():
     """Workload `mid` (12-layer d768 V32000 target, 2-layer draft, bf16, b 4, gamma_max 12);
     the context crosses several 64-key attention tiles."""
