@@ -217,6 +217,10 @@ struct GemmArgs {
   uint64_t pick_seed;
   uint32_t pick_step;
   SeqRows sr;
+  // K split across blocks (streaming kernel, KSB > 1): per-block partial sums [group][KSB][NT*MT][64] f32x4
+  // and one arrival counter per group of output tiles (zero between launches)
+  float* sk_part;
+  unsigned* sk_cnt;
 };
 
 // Epilogue of one accumulator lane, shared by the GEMM kernels.  Lane l of a 16x16 result tile holds
@@ -357,22 +361,38 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& ga, int nt, int m,
 // 8-wave blocks are held to 128 VGPRs (4 waves per SIMD) so that two blocks fit a CU.
 // HL = operand parts multiplied: 2 = hi and lo tiles (the target model's QKV, gate/up and down GEMMs),
 // 1 = hi only (draft and pre-verification layer: two layers deep, their logits stay at 4e-3 of the RMS).
-template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0, int HL = 1>
+// KSB > 1: K is also split across KSB blocks (block id = group * KSB + slice; a group is NT output tiles).
+// Every block of the launch needs the operand rows of its K range, so a matrix with about as many tiles as
+// there are CUs (O and down projections) fetches the operand once per tile; with KSB slices of NT = KSB
+// tiles each the block count stays and each block fetches 1/KSB of it.  The slices' sums meet in memory
+// without a device-scope fence (which writes back and invalidates a whole L2 and costs far more than it
+// saves here): each block writes its partial tiles with agent-scope relaxed atomic stores (write-through
+// to memory: `sc1`), waits until they have completed (vmcnt 0), and then bumps the group's counter with
+// an agent-scope atomic add; the block that sees the other KSB-1 arrivals reads all partials back with
+// agent-scope atomic loads (which do not hit in its XCD's L2), adds them in slice order (so the result
+// does not depend on which block came last), resets the counter and runs the epilogue.  Nobody waits
+// for anybody: a block that is not the last one simply ends.
+template <int EPI, int MT, int NT, int WAVES, int U, int TAG, int X17 = 0, int HL = 1, int KSB = 1>
 __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) void gemm_w16_kernel(const GemmArgs ga) {
   static_assert(!X17 || MT == 2, "the 17-row form uses two row tiles");
   // partial sums of the waves; more than 64 KB of them are handed over in two halves
   constexpr int RW = (WAVES * NT * MT > 64) ? WAVES / 2 : WAVES;
   static_assert(RW * NT * MT <= 64, "the reduction buffer must fit the 64 KB of static LDS");
+  static_assert(KSB <= RW, "the partial sums of the K slices are gathered in the reduction buffer");
+  constexpr int NRED = KSB > 1 ? KSB : RW;            // summands per accumulator lane in the epilogue
   __shared__ f32x4 red[RW][NT * MT][64];
+  __shared__ unsigned sk_arrived;
+  const int grp = blockIdx.x / KSB, ks = blockIdx.x % KSB;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id as a scalar
-  const int nt0 = ga.nt_begin + blockIdx.x * NT;
+  const int nt0 = ga.nt_begin + grp * NT;
   const int KT = ga.KT;
+  const int kbeg = (int)((long)ks * KT / KSB), kend = (int)((long)(ks + 1) * KT / KSB);   // this block's K steps
   // K steps are dealt to the block's waves round-robin (wave w takes w, w+WAVES, ...): at any moment
   // the waves of a block, and the blocks sharing a CU, read neighbouring operand tiles, which keeps the
   // operand in the CU's L1 instead of fetching it once per wave from L2
-  // steps of this wave: index i -> kt = i*WAVES + wave
+  // steps of this wave: index i -> kt = kbeg + i*WAVES + wave
   const int kb = 0;
-  const int ke = (KT - wave + WAVES - 1) / WAVES;
+  const int ke = (kend - kbeg - wave + WAVES - 1) / WAVES;
   f32x4 acc[NT][MT];
 #pragma unroll
   for (int a = 0; a < NT; ++a)
@@ -405,7 +425,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) v
   auto load = [&](u32x4(&A)[U][NT], u32x4(&B)[U][BW], int k0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const size_t kt = (size_t)min((k0 + u) * WAVES + wave, KT - 1);
+      const size_t kt = (size_t)min(kbeg + (k0 + u) * WAVES + wave, kend - 1);
 #pragma unroll
       for (int a = 0; a < NT; ++a) A[u][a] = __builtin_nontemporal_load(wp[a] + kt * 64);
       if (X17) {
@@ -491,6 +511,42 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) v
       for (int b = 0; b < MT; ++b) red[wave][a * MT + b][lane] = acc[a][b];
   }
   __syncthreads();
+  if (KSB > 1) {
+    u64* part = reinterpret_cast<u64*>(ga.sk_part);
+#pragma unroll
+    for (int it = 0; it < EIT; ++it) {
+      const int t = threadIdx.x + it * WAVES * 64;
+      if (t < NT * MT * 64) {
+        f32x4 p = red[0][t >> 6][t & 63];
+#pragma unroll
+        for (int w = 1; w < RW; ++w) p += red[w][t >> 6][t & 63];
+        u64* dst = part + ((size_t)(grp * KSB + ks) * NT * MT * 64 + t) * 2;
+        const float2 lo = {p[0], p[1]}, hi = {p[2], p[3]};
+        __hip_atomic_store(dst, __builtin_bit_cast(u64, lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(dst + 1, __builtin_bit_cast(u64, hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's write-through stores have completed
+    __syncthreads();
+    if (threadIdx.x == 0) sk_arrived = __hip_atomic_fetch_add(ga.sk_cnt + grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (sk_arrived != KSB - 1) return;
+    if (threadIdx.x == 0) __hip_atomic_store(ga.sk_cnt + grp, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int it = 0; it < EIT; ++it) {
+      const int t = threadIdx.x + it * WAVES * 64;
+      if (t < NT * MT * 64) {
+#pragma unroll
+        for (int k = 0; k < KSB; ++k) {
+          const u64* src = part + ((size_t)(grp * KSB + k) * NT * MT * 64 + t) * 2;
+          const float2 lo = __builtin_bit_cast(float2, __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          const float2 hi = __builtin_bit_cast(float2, __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          red[k][t >> 6][t & 63] = f32x4{lo.x, lo.y, hi.x, hi.y};
+        }
+      }
+    }
+    __syncthreads();
+  }
 
   // Epilogue.  One wave-sized group of threads per (tile a, row tile b); thread l of the group owns the
   // accumulator lane l: activation row m = 16*(mt0+b) + l%16, tile rows 4*(l/16)..+3.
@@ -510,19 +566,19 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) v
     const bool paired = (EPI == EPI_SWIGLU) || (EPI == EPI_QKV);
     f32x4 s = red[0][ab][l];
 #pragma unroll
-    for (int w = 1; w < RW; ++w) s += red[w][ab][l];
+    for (int w = 1; w < NRED; ++w) s += red[w][ab][l];
     f32x4 s2 = {0.f, 0.f, 0.f, 0.f};                   // partner rows i+8 (paired layouts, threads with g4 < 2)
     if (paired && g4 < 2) {
       s2 = red[0][ab][l + 32];
 #pragma unroll
-      for (int w = 1; w < RW; ++w) s2 += red[w][ab][l + 32];
+      for (int w = 1; w < NRED; ++w) s2 += red[w][ab][l + 32];
     }
     if (X17 && HL == 2 && b == 1 && (l & 15) == 0) {   // row 16: hi product in column 0, lo product in column 1
 #pragma unroll
-      for (int w = 0; w < RW; ++w) s += red[w][ab][l + 1];
+      for (int w = 0; w < NRED; ++w) s += red[w][ab][l + 1];
       if (paired && g4 < 2) {
 #pragma unroll
-        for (int w = 0; w < RW; ++w) s2 += red[w][ab][l + 33];
+        for (int w = 0; w < NRED; ++w) s2 += red[w][ab][l + 33];
       }
     }
     gemm_epilogue<EPI>(ga, nt, m, l, s, s2, &ssq_sum);

@@ -66,6 +66,8 @@ struct pacer_ctx {
   u64* ssq = nullptr;                                         // bf16 path: row sums of squares, [2*Lmax+1][rcap]
   float* pick_val = nullptr;                                  // bf16 path: per (row, vocab tile) token candidates
   int* pick_idx = nullptr;
+  float* sk_part = nullptr;                                   // bf16 path: partial tiles of GEMMs whose K is split across blocks
+  unsigned* sk_cnt = nullptr;                                 // their arrival counters (zero between launches)
   int lmax = 0;
   // pinned host memory the kernels write and the host polls: [0..31] (n, z) per sequence, [32..47] accept
   // tickets, [48..63] stop flags with their tickets
@@ -124,6 +126,10 @@ struct Carve {
   }
 };
 
+// K split across blocks (few-tile GEMMs of the target): room for the partial tiles and the counters
+constexpr size_t kSplitPartFloats = (size_t)1 << 20;   // 4 MiB: blocks x tiles per block x row tiles x 256 floats
+constexpr int kSplitGroups = 512;
+
 size_t carve(pacer_ctx* c, void* base) {
   Carve k(base);
   const int B = c->max_batch, G1 = c->G1, V = c->m[PACER_DRAFT].cfg.vocab, dD = c->m[PACER_DRAFT].cfg.d_model;
@@ -147,6 +153,8 @@ size_t carve(pacer_ctx* c, void* base) {
   c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * SSQ_SUB * c->rcap);
   c->pick_val = k.take<float>((size_t)c->max_batch * (V / 16 + 1));
   c->pick_idx = k.take<int>((size_t)c->max_batch * (V / 16 + 1));
+  c->sk_part = k.take<float>(kSplitPartFloats);
+  c->sk_cnt = k.take<unsigned>(kSplitGroups);
   return k.off;
 }
 
@@ -196,9 +204,38 @@ u64* slot(pacer_ctx* c, int s) { return c->ssq + (size_t)s * SSQ_SUB * c->rcap; 
 
 // ===== bf16-weight path: fused GEMM epilogues, MFMA attention ================================
 
-template <int EPI, int TAG, int HL, int MT, int NT, int WAVES, int U, int X17 = 0>
-void launch_w16(pacer_ctx* c, const GemmArgs& ga, int n_tiles) {
-  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17, HL>), dim3((n_tiles + NT - 1) / NT), dim3(WAVES * 64), 0, c->stream, ga);
+template <int EPI, int TAG, int HL, int MT, int NT, int WAVES, int U, int X17 = 0, int KSB = 1>
+void launch_w16(pacer_ctx* c, GemmArgs ga, int n_tiles) {
+  ga.sk_part = c->sk_part;
+  ga.sk_cnt = c->sk_cnt;
+  hipLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17, HL, KSB>), dim3((n_tiles + NT - 1) / NT * KSB), dim3(WAVES * 64), 0, c->stream, ga);
+}
+
+// Few-tile matrices of the target (O and down projections: about as many output tiles as CUs): tiles per
+// block and K slices across blocks.  Every block fetches the operand rows of its K range, so with one
+// tile per block the operand crosses L2 -> L1 once per tile, and a block count just above the CU count
+// (320 or 448 tiles) takes two rounds.  The estimate counts what occupies the CU's outstanding-line
+// capacity (about 128 lines): a weight line for ~1500 cycles (from HBM), an operand line for ~600 (from
+// L2), on the busiest CU, plus the exchange of the partial sums.  Measured at 2.4 GHz, hi+lo operand:
+//   7B down (256 tiles, K 11008), 17 rows: 1x1 25.4 us, 2x2 21.4, 4x4 21.5; 5 rows 19.6 / 17.7 / 19.7
+//   13B down (320 tiles, K 13824), 13 rows: 1x1 47.7, 2x1 34.8, 4x2 31.4, 4x3 25.8
+//   33B down (448 tiles, K 19200), 13 rows: 1x1 69.5, 2x1 52.2, 4x2 47.0; 17 rows 79.0 / 57.2 / 49.3
+// (QKV and gate/up, with three or more tiles per block already, do not gain.)
+struct SplitShape { int nt, ksb; };
+SplitShape pick_split_shape(int n_tiles, int KT, int rows, int hl) {
+  static const SplitShape cands[] = {{1, 1}, {2, 1}, {2, 2}, {3, 2}, {4, 2}, {4, 3}};
+  static const double exchange_us[] = {0.0, 0.0, 1.5, 2.5};
+  SplitShape best{1, 1};
+  double best_us = 1e300;
+  const double x_lines = hl * ((rows + 1) / 2);
+  for (const SplitShape& s : cands) {
+    const int blocks = (n_tiles + s.nt - 1) / s.nt * s.ksb;
+    const int rounds = (blocks + 255) / 256;
+    const double steps = (double)((KT + s.ksb - 1) / s.ksb);
+    const double us = rounds * steps * (s.nt * 8 * 1500.0 + x_lines * 600.0) / 128.0 / 2400.0 + exchange_us[s.ksb];
+    if (us < best_us) { best_us = us; best = s; }
+  }
+  return best;
 }
 
 // More than 32 rows: one launch of the wide kernel (operand shared through LDS, weights read once).
@@ -300,6 +337,24 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
     const int rows = ga.R - 16 * mt0;
     ga.mt0 = mt0;
     if (TAG == 0) prof_begin(c);
+    if constexpr (TAG == 0 && EPI == EPI_RESID) {
+      const SplitShape sp = (!many && ga.KT >= 64) ? pick_split_shape(n_tiles, ga.KT, std::min(rows, 32), HL) : SplitShape{1, 1};
+      const size_t part_floats = (size_t)((n_tiles + sp.nt - 1) / sp.nt) * sp.ksb * sp.nt * mt * 256;
+      if (sp.nt > 1 && part_floats <= kSplitPartFloats && (n_tiles + sp.nt - 1) / sp.nt <= kSplitGroups) {
+#define PACER_SPLIT(NT_, KSB_)                                                                       \
+        if (mt == 1) launch_w16<EPI, TAG, HL, 1, NT_, 8, 1, 0, KSB_>(c, ga, n_tiles);                \
+        else if (rows == 17) launch_w16<EPI, TAG, HL, 2, NT_, 8, 1, 1, KSB_>(c, ga, n_tiles);        \
+        else launch_w16<EPI, TAG, HL, 2, NT_, 8, 1, 0, KSB_>(c, ga, n_tiles)
+        if (sp.nt == 2 && sp.ksb == 1) { PACER_SPLIT(2, 1); }
+        else if (sp.nt == 2) { PACER_SPLIT(2, 2); }
+        else if (sp.nt == 3) { PACER_SPLIT(3, 2); }
+        else if (sp.ksb == 2) { PACER_SPLIT(4, 2); }
+        else { PACER_SPLIT(4, 3); }
+#undef PACER_SPLIT
+        prof_end(c, (double)n_tiles * 16.0 * K * 2.0);
+        continue;
+      }
+    }
     if (HL == 1) {
       if (mt == 1) {
         // K <= 768 (draft, pre-verification layer): 4 waves with at most 6 K steps each; the LM head and the
@@ -814,6 +869,7 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
                                                      (unsigned long long)pacer_workspace_bytes(c));
   if (c->ws_bound) return fail(c, PACER_ESTATE, "workspace already bound");
   carve(c, p);
+  HIPCHK(c, hipMemsetAsync(c->sk_cnt, 0, sizeof(unsigned) * kSplitGroups, c->stream));
   void* hp = nullptr;
   HIPCHK(c, hipHostMalloc(&hp, sizeof(int) * 4 * PACER_MAX_BATCH, hipHostMallocMapped));
   c->host_res = static_cast<int*>(hp);
