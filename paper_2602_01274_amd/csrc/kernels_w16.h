@@ -750,14 +750,19 @@ __global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(
 //           holds), and V^T rows are contiguous along keys.
 // The 8 wave states meet in LDS (dynamic, 8 x live rows x (HD + 4) floats) and are combined in one pass.
 // With one split the block writes the f16 operand of the O projection directly; with several, each block
-// writes a partial and attn_merge_kernel combines them.
+// writes a partial (un-normalised values, running max, running sum per row) and the block of a (head,
+// sequence, row tile) that arrives last combines them, in split order.  The hand-over needs no device-scope
+// fence (see gemm_w16_kernel): write-through stores, a wait for their completion, an agent-scope counter,
+// and loads that bypass the reader's L2.  `cnt` holds one counter per (sequence slot, head, row-tile half),
+// zero between launches.
 // QL = 2: the query operand is used as hi + lo (target model), 1: hi only.
 template <int HD, int MT, int QL>
 __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restrict__ qp, const _Float16* __restrict__ kv, int layer,
                                                         int n_layers, int max_seq, int d, SeqRows sr, int kps, int S, int H,
                                                         float* __restrict__ part, _Float16* __restrict__ xp_out, int MT_total_out,
-                                                        int rt_split) {
+                                                        int rt_split, unsigned* __restrict__ cnt) {
   constexpr int KTS = HD / 32, DTS = HD / 16, NW = 8;
+  __shared__ unsigned arrived;
   extern __shared__ __align__(16) float att_state[];   // [8 waves][live rows][HD + 4]: values, running max, running sum
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
   // rt_split (MT == 1 launches only): two blocks per key range, one per 16-row tile of the sequence
@@ -927,39 +932,54 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
       const float inv = 1.0f / L;
       store_packed4(xp_out, MT_total_out, r0 + rl, h * HD + d4, a[0] * inv, a[1] * inv, a[2] * inv, a[3] * inv);
     } else {
-      // several splits: un-normalised partial (values, running max, running sum) for attn_merge_kernel
-      float* o = part + (((size_t)(r0 + rl) * H + h) * S + split) * (HD + 2);
-      o[d4] = a[0]; o[d4 + 1] = a[1]; o[d4 + 2] = a[2]; o[d4 + 3] = a[3];
-      if (d4 == 0) { o[HD] = M; o[HD + 1] = L; }
+      // several splits: un-normalised partial (values, running max, running sum), written through to memory
+      u64* o = reinterpret_cast<u64*>(part + (((size_t)(r0 + rl) * H + h) * S + split) * (HD + 2));
+      const float2 a01 = {a[0], a[1]}, a23 = {a[2], a[3]}, ml = {M, L};
+      __hip_atomic_store(o + d4 / 2, __builtin_bit_cast(u64, a01), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(o + d4 / 2 + 1, __builtin_bit_cast(u64, a23), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (d4 == 0) __hip_atomic_store(o + HD / 2, __builtin_bit_cast(u64, ml), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-}
-
-// Merge of the key splits of attn_mfma_kernel (its own launch: a merge by the block that arrives last
-// needs device-scope fences, which cost more than a launch on this part).  grid (heads, sequences);
-// a thread owns 4 consecutive dims of one row; output = the f16 operand of the O projection.
-template <int HD>
-__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part, SeqRows sr, int kps, int S, int H,
-                                                         _Float16* __restrict__ xp_out, int MT_total_out) {
-  const int h = blockIdx.x, si = blockIdx.y;
-  const int r0 = sr.row_off[si], Rs = sr.row_off[si + 1] - r0;
-  const int n_split = (sr.pos0[si] + Rs + kps - 1) / kps;
-  if (n_split <= 1) return;                                   // that sequence's block wrote its output itself
-  for (int o4 = threadIdx.x; o4 < Rs * (HD / 4); o4 += blockDim.x) {
+  if (n_split == 1) return;
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's write-through stores have completed
+  __syncthreads();
+  unsigned* my_cnt = cnt + ((size_t)si * H + h) * 2 + rt;
+  if (threadIdx.x == 0) arrived = __hip_atomic_fetch_add(my_cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (arrived != (unsigned)(n_split - 1)) return;
+  if (threadIdx.x == 0) __hip_atomic_store(my_cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // last block of this (sequence, head, row tile): combine the splits, eight at a time (all loads of a
+  // batch are issued before the first is used; a split past the last repeats it and is skipped)
+  for (int o4 = threadIdx.x; o4 < rcap * (HD / 4); o4 += NW * 64) {
     const int rl = o4 / (HD / 4), d4 = (o4 % (HD / 4)) * 4;
-    const float* p = part + ((size_t)(r0 + rl) * H + h) * S * (HD + 2);
-    float M = -INFINITY;
-    for (int c = 0; c < n_split; ++c) M = fmaxf(M, p[(size_t)c * (HD + 2) + HD]);
-    float L = 0.f;
+    const u64* p = reinterpret_cast<const u64*>(part + ((size_t)(r0 + rl) * H + h) * S * (HD + 2));
+    float M = -INFINITY, L = 0.f;
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < n_split; ++c) {
-      const float* pc = p + (size_t)c * (HD + 2);
-      const float m = pc[HD];
-      const float w = (m == -INFINITY) ? 0.f : expf(m - M);
-      L += pc[HD + 1] * w;
-      typedef float f32x2 __attribute__((ext_vector_type(2)));
-      const f32x2 a01 = *reinterpret_cast<const f32x2*>(pc + d4), a23 = *reinterpret_cast<const f32x2*>(pc + d4 + 2);
-      a[0] += a01[0] * w; a[1] += a01[1] * w; a[2] += a23[0] * w; a[3] += a23[1] * w;
+    for (int c0 = 0; c0 < n_split; c0 += 8) {
+      u64 ml[8], v01[8], v23[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const u64* pc = p + (size_t)min(c0 + i, n_split - 1) * (HD / 2 + 1);
+        ml[i] = __hip_atomic_load(pc + HD / 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v01[i] = __hip_atomic_load(pc + d4 / 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v23[i] = __hip_atomic_load(pc + d4 / 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      float Mb = M;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (c0 + i < n_split) Mb = fmaxf(Mb, __builtin_bit_cast(float2, ml[i]).x);
+      const float keep = (M == -INFINITY) ? 0.f : expf(M - Mb);
+      L *= keep;
+      a *= keep;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float2 mli = __builtin_bit_cast(float2, ml[i]);
+        const float w = (c0 + i < n_split && mli.x != -INFINITY) ? expf(mli.x - Mb) : 0.f;
+        const float2 x01 = __builtin_bit_cast(float2, v01[i]), x23 = __builtin_bit_cast(float2, v23[i]);
+        L += mli.y * w;
+        a[0] += x01.x * w; a[1] += x01.y * w; a[2] += x23.x * w; a[3] += x23.y * w;
+      }
+      M = Mb;
     }
     const float inv = 1.0f / L;
     store_packed4(xp_out, MT_total_out, r0 + rl, h * HD + d4, a[0] * inv, a[1] * inv, a[2] * inv, a[3] * inv);

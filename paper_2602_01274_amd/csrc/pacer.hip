@@ -68,6 +68,7 @@ struct pacer_ctx {
   int* pick_idx = nullptr;
   float* sk_part = nullptr;                                   // bf16 path: partial tiles of GEMMs whose K is split across blocks
   unsigned* sk_cnt = nullptr;                                 // their arrival counters (zero between launches)
+  unsigned* att_cnt = nullptr;                                // attention key splits: arrival counters per (slot, head, row-tile half)
   int lmax = 0;
   // pinned host memory the kernels write and the host polls: [0..31] (n, z) per sequence, [32..47] accept
   // tickets, [48..63] stop flags with their tickets
@@ -155,6 +156,7 @@ size_t carve(pacer_ctx* c, void* base) {
   c->pick_idx = k.take<int>((size_t)c->max_batch * (V / 16 + 1));
   c->sk_part = k.take<float>(kSplitPartFloats);
   c->sk_cnt = k.take<unsigned>(kSplitGroups);
+  c->att_cnt = k.take<unsigned>((size_t)PK_MAXB * c->hmax * 2);
   return k.off;
 }
 
@@ -444,16 +446,20 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
     max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
     max_rows = std::max(max_rows, sr.row_off[i + 1] - sr.row_off[i]);
   }
-  // Keys per block (8 waves).  One block per (head, sequence) writes its output itself; splitting the keys
-  // over several blocks costs a merge launch.  Measured (32 heads, one sequence): no split wins up to 2k
-  // keys; beyond, blocks of 1024 keys or more, and never more blocks than CUs (544 blocks of 256 keys take
-  // twice as long as 160 blocks of 1024).
+  // Keys per block (8 waves).  One block per (head, sequence) writes its output itself; with the keys split
+  // over several blocks the last one to finish combines the partial results (about 2 us for the hand-over).
+  // A (head, sequence) pair's keys stream through one CU's outstanding-line capacity, so few pairs with
+  // many keys want splits: never more blocks than CUs (544 blocks of 256 keys take twice as long as 160
+  // blocks of 1024), and at least 160 keys per block.  Measured, 32 heads, one sequence, cold cache, 13 rows:
+  // 300 keys 6.9 us unsplit, 8.6 with 2 splits; 800 keys 13.4 / 10.3 (6 splits); 1600 keys 20.9 / 13.2 (8);
+  // 4300 keys 46.0 / 19.3 (8).
   int kps = (max_keys + 31) / 32 * 32;
   {
     const int pairs = H * sr.n_seqs;
-    const int most = 256 / pairs;                               // splits that still leave one block per CU
-    if (most >= 2 && max_keys >= 2048 && R <= c->prows) kps = std::max(1024, ((max_keys + most - 1) / most + 31) / 32 * 32);
-    kps = std::max(kps, ((max_keys + kMaxChunks - 1) / kMaxChunks + 31) / 32 * 32);   // the partial buffer holds kMaxChunks splits
+    const int most = std::min({256 / pairs, max_keys / 160, kMaxChunks});   // splits that still leave one block per CU
+    // 17..32 rows below 1000 keys: two one-tile blocks per pair instead (see the attention launch)
+    const bool two_tiles_short = max_rows > 16 && max_keys < 1000;
+    if (most >= 2 && !two_tiles_short && R <= c->prows) kps = ((max_keys + most - 1) / most + 31) / 32 * 32;
   }
   const int S = (max_keys + kps - 1) / kps;
   GemmArgs base{};
@@ -487,11 +493,11 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       // per pair, one per row tile, is faster than the two-tile kernel although it reads the keys twice
       // (7B shape, 550 keys, warm cache: 7.1 us against 10.0 us).  Long contexts and batches are bound by the
       // cache traffic and keep the two-tile kernel.
-      const bool rt_split = max_rows > 16 && S == 1 && max_keys < 2048 && H * sr.n_seqs <= 64;
+      const bool rt_split = max_rows > 16 && S == 1 && max_keys < 1000 && H * sr.n_seqs <= 64;
       const int mrows = rt_split ? 16 : max_rows;
       const dim3 grid(rt_split ? 2 * S : S, H, sr.n_seqs);
       // LDS for the wave states: 8 waves x live rows x (hd + 4) floats
-#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), (size_t)8 * std::min(mrows, MT_ * 16) * (HD_ + 4) * 4, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total, rt_split ? 1 : 0)
+#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), (size_t)8 * std::min(mrows, MT_ * 16) * (HD_ + 4) * 4, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total, rt_split ? 1 : 0, c->att_cnt)
       if (tag == 0) {
         if (hd == 128) { if (mrows > 16) PACER_ATT(128, 2, 2); else PACER_ATT(128, 1, 2); }
         else           { if (mrows > 16) PACER_ATT(64, 2, 2); else PACER_ATT(64, 1, 2); }
@@ -500,10 +506,6 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
         else           { if (mrows > 16) PACER_ATT(64, 2, 1); else PACER_ATT(64, 1, 1); }
       }
 #undef PACER_ATT
-      if (S > 1) {
-        if (hd == 128) hipLaunchKernelGGL((attn_merge_kernel<128>), dim3(H, sr.n_seqs), dim3(256), 0, c->stream, c->part, sr, kps, S, H, c->xpB, mt_total);
-        else hipLaunchKernelGGL((attn_merge_kernel<64>), dim3(H, sr.n_seqs), dim3(256), 0, c->stream, c->part, sr, kps, S, H, c->xpB, mt_total);
-      }
     }
     {
       GemmArgs ga = base;
@@ -870,6 +872,7 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
   if (c->ws_bound) return fail(c, PACER_ESTATE, "workspace already bound");
   carve(c, p);
   HIPCHK(c, hipMemsetAsync(c->sk_cnt, 0, sizeof(unsigned) * kSplitGroups, c->stream));
+  HIPCHK(c, hipMemsetAsync(c->att_cnt, 0, sizeof(unsigned) * PK_MAXB * c->hmax * 2, c->stream));
   void* hp = nullptr;
   HIPCHK(c, hipHostMalloc(&hp, sizeof(int) * 4 * PACER_MAX_BATCH, hipHostMallocMapped));
   c->host_res = static_cast<int*>(hp);
