@@ -456,7 +456,10 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
   int kps = (max_keys + 31) / 32 * 32;
   {
     const int pairs = H * sr.n_seqs;
-    const int most = std::min({256 / pairs, max_keys / 160, kMaxChunks});   // splits that still leave one block per CU
+    // (the small draft model's keys are re-read every few microseconds and sit in L2: 770 keys, 12 heads take
+    // 6.6 us unsplit and 7.3 us in 4 splits, so its blocks keep at least 1024 keys)
+    const int min_keys = tag == 0 ? 160 : 1024;
+    const int most = std::min({256 / pairs, max_keys / min_keys, kMaxChunks});   // splits that still leave one block per CU
     // 17..32 rows below 1000 keys: two one-tile blocks per pair instead (see the attention launch)
     const bool two_tiles_short = max_rows > 16 && max_keys < 1000;
     if (most >= 2 && !two_tiles_short && R <= c->prows) kps = ((max_keys + most - 1) / most + 31) / 32 * 32;
