@@ -227,6 +227,15 @@ int32_t pacer_get_state(pacer_ctx* ctx, int32_t seq, int32_t* gamma, int32_t* le
 /* Device pointer (inside the workspace) of a per-sequence buffer; valid while bound. */
 int32_t pacer_peek(pacer_ctx* ctx, int32_t seq, int32_t what, void** dev_ptr, uint64_t* nbytes);
 
+/* Host only, no context: how the weight-streaming GEMM of the target model would be launched for a
+ * few-tile matrix (fewer than 512 output tiles of 16: the O and down projections) of n_out x n_in
+ * weights on `rows` activation rows (1..32) with `operand_parts` f16 parts per activation (1 = hi,
+ * 2 = hi + lo): output tiles per block and K slices across blocks (1 = K is not split; with more, the
+ * blocks of a tile group add their partial tiles through the workspace).  PACER_EINVAL on a null
+ * pointer or sizes outside those bounds. */
+int32_t pacer_launch_plan(int32_t n_out, int32_t n_in, int32_t rows, int32_t operand_parts,
+                          int32_t* tiles_per_block, int32_t* k_slices);
+
 /* Kernel timing for benchmarks: while enabled, every launch of the weight-streaming GEMM is
  * bracketed by HIP events on the context's stream.  pacer_profile_read synchronises and returns
  * the number of launches, their summed duration and the summed weight bytes they streamed, then

@@ -27,7 +27,7 @@ EXPORTS = [
     "pacer_kv_bytes", "pacer_bind_kv", "pacer_workspace_bytes", "pacer_bind_workspace",
     "pacer_prefill", "pacer_force_commit", "pacer_begin_step", "pacer_draft_step",
     "pacer_preverify_block", "pacer_wait_stop", "pacer_verify", "pacer_accept_rollback", "pacer_get_state",
-    "pacer_peek", "pacer_profile_enable", "pacer_profile_read",
+    "pacer_peek", "pacer_profile_enable", "pacer_profile_read", "pacer_launch_plan",
 ]
 
 
@@ -75,6 +75,7 @@ def _load():
         "pacer_get_state": (i32, [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(i32), C.POINTER(i32)]),
         "pacer_peek": (i32, [vp, i32, i32, C.POINTER(vp), C.POINTER(u64)]),
         "pacer_profile_enable": (i32, [vp, i32]),
+        "pacer_launch_plan": (i32, [i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]),
         "pacer_profile_read": (i32, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     }
     for name, (res, args) in sig.items():
@@ -194,6 +195,14 @@ def pacer_peek(ctx, seq, what):
     p, nb = C.c_void_p(), C.c_uint64()
     _chk(ctx, _lib.pacer_peek(ctx, seq, what, C.byref(p), C.byref(nb)))
     return p.value, nb.value
+
+
+def pacer_launch_plan(n_out, n_in, rows, operand_parts):
+    nt, ksb = C.c_int32(), C.c_int32()
+    rc = _lib.pacer_launch_plan(n_out, n_in, rows, operand_parts, C.byref(nt), C.byref(ksb))
+    if rc != OK:
+        raise PacerError(rc, "pacer_launch_plan: bad arguments")
+    return nt.value, ksb.value
 
 
 def pacer_profile_enable(ctx, on):

@@ -1201,6 +1201,17 @@ int32_t pacer_peek(pacer_ctx* c, int32_t s, int32_t what, void** p, uint64_t* nb
   return PACER_OK;
 }
 
+int32_t pacer_launch_plan(int32_t n_out, int32_t n_in, int32_t rows, int32_t operand_parts, int32_t* tiles_per_block,
+                          int32_t* k_slices) {
+  if (!tiles_per_block || !k_slices || n_out < 16 || n_out % 16 || n_out / 16 >= 512 || n_in < 32 || n_in % 32 || rows < 1 ||
+      rows > 32 || operand_parts < 1 || operand_parts > 2)
+    return PACER_EINVAL;
+  const SplitShape sp = n_in / 32 >= 64 ? pick_split_shape(n_out / 16, n_in / 32, rows, operand_parts) : SplitShape{1, 1};
+  *tiles_per_block = sp.nt;
+  *k_slices = sp.ksb;
+  return PACER_OK;
+}
+
 int32_t pacer_profile_enable(pacer_ctx* c, int32_t on) {
   if (!c) return PACER_EINVAL;
   if (!c->ws_bound) return fail(c, PACER_ESTATE, "workspace not bound");

@@ -100,3 +100,29 @@ def test_calls_out_of_order_and_bad_arguments_fail_on_the_host(B):
         B.pacer_get_state(ctx, 2)
     assert e.value.code == B.EINVAL
     B.pacer_destroy(ctx)
+
+
+def test_launch_plan_of_the_few_tile_projections(B):
+    """Tiles per block and K slices across blocks for the target's O and down projections: the
+    measured choices at the three model widths, and bounds that hold for any size."""
+    for rows in (5, 13, 17, 32):
+        assert B.pacer_launch_plan(4096, 11008, rows, 2) == (2, 2)      # 7B down: 256 tiles, 256 blocks
+        assert B.pacer_launch_plan(5120, 13824, rows, 2) == (4, 3)      # 13B down: 320 tiles, 240 blocks
+        assert B.pacer_launch_plan(7168, 19200, rows, 2) == (4, 2)      # 33B down: 448 tiles, 224 blocks
+        if rows <= 17:
+            assert B.pacer_launch_plan(4096, 4096, rows, 1) == (1, 1)   # 7B O, hi only: its operand is small
+    assert B.pacer_launch_plan(768, 768, 4, 1) == (1, 1)                # K below 2048: never split
+    for n_out in range(16, 8192, 16 * 7):
+        for n_in in (2048, 4096, 11008, 19200):
+            for rows in (1, 9, 17, 32):
+                for parts in (1, 2):
+                    nt, ksb = B.pacer_launch_plan(n_out, n_in, rows, parts)
+                    tiles = n_out // 16
+                    groups = -(-tiles // nt)
+                    assert 1 <= ksb <= 3 and 1 <= nt <= 4 and ksb <= max(nt, 1)
+                    assert groups <= 512                                   # arrival counters in the workspace
+                    assert groups * ksb * nt * 2 * 256 <= 1 << 20 or ksb == 1   # partial tiles fit their 4 MiB
+                    assert n_in // 32 // ksb >= 8                          # every slice has K steps for all 8 waves
+    for bad in ((8, 4096, 4, 1), (4096, 100, 4, 1), (4096, 4096, 0, 1), (4096, 4096, 33, 1), (4096, 4096, 4, 3), (16 * 512, 4096, 4, 1)):
+        with pytest.raises(B.PacerError):
+            B.pacer_launch_plan(*bad)
