@@ -3,7 +3,8 @@
 // One decoder layer is five launches:
 //   QKV GEMM   (epilogue: row scale of the RMSNorm, RoPE, Q -> f16 attention operand, K/V -> cache)
 //   attention  (MFMA scores and weighted values, 8 waves per key range merged through LDS, output = the
-//               f16 operand of the O projection; long contexts: several key ranges + a merge launch)
+//               f16 operand of the O projection; few heads or long contexts: several key ranges per
+//               head, combined by the block that finishes last)
 //   O GEMM     (epilogue: residual add, next norm's operand x*g as f16, row sum of squares)
 //   gate/up GEMM (epilogue: row scale, SwiGLU, f16 operand of the down projection)
 //   down GEMM  (epilogue: residual add, next norm's operand, row sum of squares)

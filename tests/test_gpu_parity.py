@@ -109,8 +109,8 @@ def test_7b_width_two_layers_bf16():
 
 def test_7b_width_full_window_and_long_prompt():
     """gamma = gamma_max = 16 every step (17 verify rows: one full row tile + row 16), on a 2100-token
-    prompt: target, draft and pre-verification attention each split their keys over 3 blocks of up to
-    1024 keys and combine them in the merge kernel."""
+    prompt: the target's attention splits its keys over 8 blocks per head, the draft's and the
+    pre-verification layer's over 2, and the block that finishes last combines the partial results."""
     _run("7b", 2100, 12, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2, max_seq=2304,
          w_over=dict(mode="greedy"), step_kw=dict(force_stop=lambda k, a: False))
 
