@@ -167,6 +167,14 @@ def test_batch_mid_bf16_ragged():
     _run_batch("mid", [40, 75, 150, 260], [1.0, 2.3, 3.7, 5.0], 6, 2e-2, 2e-2)
 
 
+def test_batch_mid_bf16_key_splits_differ_per_sequence():
+    """Three sequences of 30, 420 and 700 prompt tokens in one launch: the target's attention splits the
+    keys in blocks of 192, so the first sequence has one block per head (it writes its output itself), the
+    second three and the third four (combined by the block that finishes last), step after step on the
+    same counters."""
+    _run_batch("mid", [30, 420, 700], [3.0, 2.0, 4.0], 5, 2e-2, 2e-2, max_seq=1024)
+
+
 def test_batch_mid_bf16_bonus_row_for_part_of_the_batch():
     """Strong coupling and a short fixed window make all-accepted steps frequent: in most steps only some
     of the sequences take the extra draft forward and the bonus row (Alg. 1, the all-accepted branch), whose
