@@ -67,6 +67,7 @@ struct pacer_ctx {
   float* pick_val = nullptr;                                  // bf16 path: per (row, vocab tile) token candidates
   int* pick_idx = nullptr;
   float* sk_part = nullptr;                                   // bf16 path: partial tiles of GEMMs whose K is split across blocks
+  size_t sk_part_floats = 0;
   unsigned* sk_cnt = nullptr;                                 // their arrival counters (zero between launches)
   unsigned* att_cnt = nullptr;                                // attention key splits: arrival counters per (slot, head, row-tile half)
   int lmax = 0;
@@ -154,7 +155,9 @@ size_t carve(pacer_ctx* c, void* base) {
   c->ssq = k.take<u64>((size_t)(2 * c->lmax + 1) * SSQ_SUB * c->rcap);
   c->pick_val = k.take<float>((size_t)c->max_batch * (V / 16 + 1));
   c->pick_idx = k.take<int>((size_t)c->max_batch * (V / 16 + 1));
-  c->sk_part = k.take<float>(kSplitPartFloats);
+  // streaming kernel: kSplitPartFloats; wide kernel with K slices: up to 3 slices x padded rows x padded outputs (d wide)
+  c->sk_part_floats = std::max(kSplitPartFloats, (size_t)3 * (c->rcap + 32) * (c->dmax + 128));
+  c->sk_part = k.take<float>(c->sk_part_floats);
   c->sk_cnt = k.take<unsigned>(kSplitGroups);
   c->att_cnt = k.take<unsigned>((size_t)PK_MAXB * c->hmax * 2);
   return k.off;
@@ -285,6 +288,54 @@ WideShape pick_wide_shape(int n_tiles, int mt_total, int KT, int hl) {
   }
   return best;
 }
+// Few-tile projections at 6..12 row tiles (96..192 rows: batched verification): the 8-wave kernel with K
+// slices across blocks.  Two row groups of MTB = ceil(row tiles / 2) tiles, one output tile per wave, and as
+// many K slices (3, else 2) as keep the launch within the CU count.  Measured at d 5120 (320 tiles -> 40 groups x
+// 2 x 3 = 240 blocks), hi+lo down projection: 52 / 63 / 74 us at MTB 4 / 5 / 6 against 75 / 80 / 84 us for the best
+// shape of the 4-wave kernel; hi-only O projection 26 / 31.5 us at MTB 4 / 5 against 31 / 33 us (no gain at 6).
+// Returns false if the shape is not covered (the caller then takes the 4-wave kernel).
+constexpr int kWide8KC = 4;
+// The gate/up GEMM (many tiles) takes the same kernel without K slices at 7..12 row tiles when two tiles per
+// wave x two row groups give 192..256 blocks (d 5120: 108 groups -> 216 blocks): 82 / 106 / 117 us at MTB 4 / 5 / 6
+// against 88 / 115 / 123 us.  The QKV GEMM does not gain (94 against 62 us).
+template <int EPI, int TAG, int HL, int NTW, int MTB, int KSB>
+void launch_wide8_shape(pacer_ctx* c, const GemmArgs& ga, int n_tiles, int n_groups) {
+  const size_t lds = (size_t)2 * kWide8KC * MTB * HL * 1024;
+  hipLaunchKernelGGL((gemm_wide8_kernel<EPI, NTW, MTB, HL, TAG, kWide8KC, KSB>), dim3((unsigned)((n_groups + 7) / 8 * 8 * 2 * KSB)), dim3(512), lds,
+                     c->stream, ga, n_tiles, n_groups, 2);
+}
+template <int EPI, int TAG, int HL>
+bool launch_wide8(pacer_ctx* c, GemmArgs ga, int n_tiles) {
+  if constexpr (TAG == 0 && EPI == EPI_SWIGLU && HL == 2) {
+    const int mt = ga.mt_total;
+    const int n_groups = (n_tiles + 15) / 16;
+    if (mt < 7 || mt > 12 || ga.KT % 4 || ga.KT < 64 || n_groups * 2 < 192 || n_groups * 2 > 256) return false;
+    const int mtb = std::max(4, (mt + 1) / 2);
+    ga.mt0 = 0;
+    if (mtb == 4) launch_wide8_shape<EPI, TAG, HL, 2, 4, 1>(c, ga, n_tiles, n_groups);
+    else if (mtb == 5) launch_wide8_shape<EPI, TAG, HL, 2, 5, 1>(c, ga, n_tiles, n_groups);
+    else launch_wide8_shape<EPI, TAG, HL, 2, 6, 1>(c, ga, n_tiles, n_groups);
+    return true;
+  } else if constexpr (TAG != 0 || EPI != EPI_RESID) {
+    return false;
+  } else {
+    const int mt = ga.mt_total;
+    if (mt < 6 || mt > (HL == 2 ? 12 : 10) || n_tiles >= 512 || ga.KT % 4 || ga.KT < 64) return false;
+    const int n_groups = (n_tiles + 7) / 8;
+    const int mtb = std::max(4, (mt + 1) / 2);
+    const int ksb = n_groups * 2 * 3 <= 256 ? 3 : (n_groups * 2 * 2 <= 256 ? 2 : 0);
+    if (ksb == 0 || n_groups * 2 > kSplitGroups) return false;
+    if ((size_t)n_groups * 2 * ksb * 8 * mtb * 256 > c->sk_part_floats) return false;
+    ga.mt0 = 0;
+    ga.sk_part = c->sk_part;
+    ga.sk_cnt = c->sk_cnt;
+#define PACER_W8(MTB_) if (ksb == 3) launch_wide8_shape<EPI, TAG, HL, 1, MTB_, 3>(c, ga, n_tiles, n_groups); else launch_wide8_shape<EPI, TAG, HL, 1, MTB_, 2>(c, ga, n_tiles, n_groups)
+    if (mtb == 4) { PACER_W8(4); } else if (mtb == 5) { PACER_W8(5); } else { PACER_W8(6); }
+#undef PACER_W8
+    return true;
+  }
+}
+
 template <int EPI, int TAG, int HL>
 void launch_wide(pacer_ctx* c, GemmArgs ga, int n_tiles) {
   ga.mt0 = 0;
@@ -330,7 +381,7 @@ void gemm_w16_tag(pacer_ctx* c, GemmArgs ga, int n_tiles, int K) {
   const bool even = n_tiles % 2 == 0;
   if (mt_total > 2 && ga.KT % 4 == 0) {
     if (TAG == 0) prof_begin(c);
-    launch_wide<EPI, TAG, HL>(c, ga, n_tiles);
+    if (!launch_wide8<EPI, TAG, HL>(c, ga, n_tiles)) launch_wide<EPI, TAG, HL>(c, ga, n_tiles);
     if (TAG == 0) prof_end(c, (double)n_tiles * 16.0 * K * 2.0);
     return;
   }
@@ -891,6 +942,14 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
     PACER_ATT_LDS(128, 2, 1); PACER_ATT_LDS(128, 1, 1); PACER_ATT_LDS(64, 2, 1); PACER_ATT_LDS(64, 1, 1);
 #undef PACER_ATT_LDS
   }
+  // the 8-wave wide GEMM stages its operand in dynamic LDS: up to 2 x 4 K steps x 6 row tiles x hi+lo KiB = 96 KiB
+#define PACER_W8_LDS(HL_, MTB_, KSB_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide8_kernel<EPI_RESID, 1, MTB_, HL_, 0, kWide8KC, KSB_>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kWide8KC * MTB_ * HL_ * 1024))
+  PACER_W8_LDS(1, 4, 2); PACER_W8_LDS(1, 4, 3); PACER_W8_LDS(1, 5, 2); PACER_W8_LDS(1, 5, 3); PACER_W8_LDS(1, 6, 2); PACER_W8_LDS(1, 6, 3);
+  PACER_W8_LDS(2, 4, 2); PACER_W8_LDS(2, 4, 3); PACER_W8_LDS(2, 5, 2); PACER_W8_LDS(2, 5, 3); PACER_W8_LDS(2, 6, 2); PACER_W8_LDS(2, 6, 3);
+#undef PACER_W8_LDS
+#define PACER_W8_LDS(MTB_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide8_kernel<EPI_SWIGLU, 2, MTB_, 2, 0, kWide8KC, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kWide8KC * MTB_ * 2 * 1024))
+  PACER_W8_LDS(4); PACER_W8_LDS(5); PACER_W8_LDS(6);
+#undef PACER_W8_LDS
   c->ws_bound = true;
   return PACER_OK;
 }
