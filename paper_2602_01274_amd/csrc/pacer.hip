@@ -292,7 +292,8 @@ WideShape pick_wide_shape(int n_tiles, int mt_total, int KT, int hl) {
 // slices across blocks.  Two row groups of MTB = ceil(row tiles / 2) tiles, one output tile per wave, and as
 // many K slices (3, else 2) as keep the launch within the CU count.  Measured at d 5120 (320 tiles -> 40 groups x
 // 2 x 3 = 240 blocks), hi+lo down projection: 52 / 63 / 74 us at MTB 4 / 5 / 6 against 75 / 80 / 84 us for the best
-// shape of the 4-wave kernel; hi-only O projection 26 / 31.5 us at MTB 4 / 5 against 31 / 33 us (no gain at 6).
+// shape of the 4-wave kernel.  The hi-only O projection (26 / 31.5 us at MTB 4 / 5 against 31 / 33 us in the same
+// microbenchmark) turned out slower in the real sequence (33 against 29 us) and stays with the 4-wave kernel.
 // Returns false if the shape is not covered (the caller then takes the 4-wave kernel).
 constexpr int kWide8KC = 4;
 // The gate/up GEMM (many tiles) takes the same kernel without K slices at 7..12 row tiles when two tiles per
@@ -316,11 +317,11 @@ bool launch_wide8(pacer_ctx* c, GemmArgs ga, int n_tiles) {
     else if (mtb == 5) launch_wide8_shape<EPI, TAG, HL, 2, 5, 1>(c, ga, n_tiles, n_groups);
     else launch_wide8_shape<EPI, TAG, HL, 2, 6, 1>(c, ga, n_tiles, n_groups);
     return true;
-  } else if constexpr (TAG != 0 || EPI != EPI_RESID) {
+  } else if constexpr (TAG != 0 || EPI != EPI_RESID || HL != 2) {
     return false;
   } else {
     const int mt = ga.mt_total;
-    if (mt < 6 || mt > (HL == 2 ? 12 : 10) || n_tiles >= 512 || ga.KT % 4 || ga.KT < 64) return false;
+    if (mt < 6 || mt > 12 || n_tiles >= 512 || ga.KT % 4 || ga.KT < 64) return false;
     const int n_groups = (n_tiles + 7) / 8;
     const int mtb = std::max(4, (mt + 1) / 2);
     const int ksb = n_groups * 2 * 3 <= 256 ? 3 : (n_groups * 2 * 2 <= 256 ? 2 : 0);
@@ -944,7 +945,6 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
   }
   // the 8-wave wide GEMM stages its operand in dynamic LDS: up to 2 x 4 K steps x 6 row tiles x hi+lo KiB = 96 KiB
 #define PACER_W8_LDS(HL_, MTB_, KSB_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide8_kernel<EPI_RESID, 1, MTB_, HL_, 0, kWide8KC, KSB_>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kWide8KC * MTB_ * HL_ * 1024))
-  PACER_W8_LDS(1, 4, 2); PACER_W8_LDS(1, 4, 3); PACER_W8_LDS(1, 5, 2); PACER_W8_LDS(1, 5, 3); PACER_W8_LDS(1, 6, 2); PACER_W8_LDS(1, 6, 3);
   PACER_W8_LDS(2, 4, 2); PACER_W8_LDS(2, 4, 3); PACER_W8_LDS(2, 5, 2); PACER_W8_LDS(2, 5, 3); PACER_W8_LDS(2, 6, 2); PACER_W8_LDS(2, 6, 3);
 #undef PACER_W8_LDS
 #define PACER_W8_LDS(MTB_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide8_kernel<EPI_SWIGLU, 2, MTB_, 2, 0, kWide8KC, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kWide8KC * MTB_ * 2 * 1024))
