@@ -236,10 +236,11 @@ int32_t pacer_peek(pacer_ctx* ctx, int32_t seq, int32_t what, void** dev_ptr, ui
 int32_t pacer_launch_plan(int32_t n_out, int32_t n_in, int32_t rows, int32_t operand_parts,
                           int32_t* tiles_per_block, int32_t* k_slices);
 
-/* Kernel timing for benchmarks: while enabled, every launch of the weight-streaming GEMM is
- * bracketed by HIP events on the context's stream.  pacer_profile_read synchronises and returns
- * the number of launches, their summed duration and the summed weight bytes they streamed, then
- * clears the counters. */
+/* Kernel timing for benchmarks: while enabled, every launch of the target model's GEMM kernels
+ * carries a pair of HIP events on the context's stream that receive the kernel's own begin and end
+ * time stamps (up to 16384 launches between two reads; later ones run untimed).
+ * pacer_profile_read synchronises and returns the number of timed launches, their summed duration
+ * and the summed weight bytes they streamed, then clears the counters. */
 int32_t pacer_profile_enable(pacer_ctx* ctx, int32_t on);
 int32_t pacer_profile_read(pacer_ctx* ctx, int64_t* n_launches, double* total_ms,
                            double* weight_bytes);
