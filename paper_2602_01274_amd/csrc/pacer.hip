@@ -510,15 +510,16 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
   // over several blocks the last one to finish combines the partial results (about 2 us for the hand-over).
   // A (head, sequence) pair's keys stream through one CU's outstanding-line capacity, so few pairs with
   // many keys want splits: never more blocks than CUs (544 blocks of 256 keys take twice as long as 160
-  // blocks of 1024), and at least 160 keys per block.  Measured, 32 heads, one sequence, cold cache, 13 rows:
-  // 300 keys 6.9 us unsplit, 8.6 with 2 splits; 800 keys 13.4 / 10.3 (6 splits); 1600 keys 20.9 / 13.2 (8);
-  // 4300 keys 46.0 / 19.3 (8).
+  // blocks of 1024; 512 blocks of 540 keys make the 4k-context verify pass 8 % slower than 256), and no splits
+  // below 512 keys.  Measured, 32 heads, one sequence, cold cache, 13 rows: 300 keys 6.9 us unsplit, 8.6 with 2
+  // splits; 800 keys 13.4 / 10.3 (6 splits); 1600 keys 20.9 / 13.2 (8); 4300 keys 46.0 / 19.3 (8).  In the decode
+  // loop at 770 keys, blocks of at least 96 / 128 / 160 keys (8 / 6 / 4 splits): verify pass 2.930 / 2.942 / 2.957 ms.
   int kps = (max_keys + 31) / 32 * 32;
   {
     const int pairs = H * sr.n_seqs;
     // (the small draft model's keys are re-read every few microseconds and sit in L2: 770 keys, 12 heads take
     // 6.6 us unsplit and 7.3 us in 4 splits, so its blocks keep at least 1024 keys)
-    const int min_keys = tag == 0 ? 160 : 1024;
+    const int min_keys = tag == 0 ? (max_keys >= 512 ? 96 : 256) : 1024;
     const int most = std::min({256 / pairs, max_keys / min_keys, kMaxChunks});   // splits that still leave one block per CU
     // 17..32 rows below 1000 keys: two one-tile blocks per pair instead (see the attention launch)
     const bool two_tiles_short = max_rows > 16 && max_keys < 1000;
