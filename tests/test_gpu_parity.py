@@ -191,6 +191,12 @@ def test_7b_width_two_sequences_full_windows():
     _run_batch("7b", [40, 75], [3.0, 4.0], 2, 2e-2, 2e-2, n_layers_target=2, fixed_gamma=16, ragged=False, max_seq=160)
 
 
+def test_7b_width_two_sequences_eighteen_rows():
+    """Two sequences with 9 verify rows each at the 7B width: 18 rows are two row tiles of the streaming GEMM
+    (not the 17-row form), with the down projection's K split across blocks."""
+    _run_batch("7b", [40, 75], [3.0, 4.0], 2, 2e-2, 2e-2, n_layers_target=2, fixed_gamma=8, ragged=False, max_seq=160)
+
+
 def test_batch_mid_bf16_eight_sequences_wide_gemm():
     """8 sequences x up to 13 verify rows = up to 104 rows: the wide GEMM with several row groups per
     output-tile group, ragged last row tile, per-sequence attention over different lengths."""
