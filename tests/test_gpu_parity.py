@@ -218,6 +218,13 @@ def test_33b_width_two_layers_bf16():
     _run("33b", 40, 10, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2, max_seq=128, w_over=dict(mode="greedy"))
 
 
+def test_33b_width_eight_sequences_down_projection_k_slices():
+    """Eight sequences x 13 verify rows = 104 rows at the 33B width: the down projection (448 output tiles)
+    runs in the 8-wave wide kernel with two K slices across blocks (56 tile groups x 2 row groups x 2)."""
+    _run_batch("33b", [12, 20, 9, 16, 14, 22, 11, 18], [3.0, 2.0, 4.0, 3.5, 2.5, 3.0, 4.5, 1.5], 1, 2e-2, 2e-2,
+               n_layers_target=2, fixed_gamma=12, ragged=False, max_seq=64)
+
+
 def test_13b_batch_full_depth_batch_invariance():
     """Workload `13b_batch` at full size (40 layers, 16 sequences) in the launch configuration bench.py
     times.  Property that holds at any size: a sequence verified inside the ragged batch (wide GEMM,
