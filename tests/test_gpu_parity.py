@@ -212,6 +212,13 @@ def test_13b_width_four_layers_batch_against_oracle():
                [1.0, 2.0, 3.0, 4.0, 5.0, 2.5, 3.5, 1.5, 4.5, 2.0, 3.0, 4.0], 2, 2e-2, 2e-2, max_seq=160, n_layers_target=4)
 
 
+def test_13b_width_ten_full_windows_six_row_tiles_per_block():
+    """Ten sequences x 17 verify rows = 170 rows = 11 row tiles: the down and gate/up GEMMs run in the 8-wave
+    wide kernel with two row groups of six row tiles (the largest operand stage, 96 KiB of LDS)."""
+    _run_batch("13b_batch", [18, 33, 47, 25, 60, 39, 21, 52, 30, 44], [1.0, 2.0, 3.0, 4.0, 5.0, 2.5, 3.5, 1.5, 4.5, 2.0], 1, 2e-2, 2e-2,
+               max_seq=160, n_layers_target=2, fixed_gamma=16, ragged=False)
+
+
 def test_33b_width_two_layers_bf16():
     """Shapes of the large pair (target d 7168, 56 heads of 128, FFN 19200, V 32256; 24-layer d 2048
     draft with 128-wide heads): tile counts and K lengths none of the other tests has."""
