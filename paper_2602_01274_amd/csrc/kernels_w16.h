@@ -679,19 +679,26 @@ __global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(
 #pragma unroll
       for (int j = 0; j < KC; ++j) loadB(Breg[j], k0 + ss * KC + 2 * KC + j);
       __builtin_amdgcn_sched_barrier(0);
+      // operand tiles of K step j+1 are read from LDS before the products of step j are issued (two register sets)
+      u32x4 bfr[2][BT];
+#pragma unroll
+      for (int t = 0; t < BT; ++t) bfr[0][t] = Bs[ks][buf][0][t][lane];
 #pragma unroll
       for (int j = 0; j < KC; ++j) {
         const int u = ss * KC + j;
+        if (j + 1 < KC) {
+#pragma unroll
+          for (int t = 0; t < BT; ++t) bfr[(j + 1) & 1][t] = Bs[ks][buf][j + 1][t][lane];
+        }
+        __builtin_amdgcn_sched_barrier(0);
         half8 af[NTW];
 #pragma unroll
         for (int a = 0; a < NTW; ++a) af[a] = __builtin_bit_cast(half8, Areg[u][a]);
-        half8 bf[BT];
-#pragma unroll
-        for (int t = 0; t < BT; ++t) bf[t] = __builtin_bit_cast(half8, Bs[ks][buf][j][t][lane]);
 #pragma unroll
         for (int t = 0; t < BT; ++t)
 #pragma unroll
-          for (int a = 0; a < NTW; ++a) acc[a][t / HL] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[a], bf[t], acc[a][t / HL], 0, 0, 0);
+          for (int a = 0; a < NTW; ++a)
+            acc[a][t / HL] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[a], __builtin_bit_cast(half8, bfr[j & 1][t]), acc[a][t / HL], 0, 0, 0);
         // the step's weight registers are free now: refill them for the step UA ahead (after the products, so
         // that the loads land in the same registers and need no copies at the loop's back edge)
         loadA(Areg[u], k0 + UA + u);
@@ -822,16 +829,30 @@ __global__ __launch_bounds__(512, 1) void gemm_wide8_kernel(const GemmArgs ga, i
       storeB(buf ^ 1);                                       // operand of the next super-step
       loadB(k0 + ss * KC + 2 * KC);
       __builtin_amdgcn_sched_barrier(0);
+      // The operand tiles of K step j+1 are read from LDS into a second register set before the products of
+      // step j are issued (with one set the compiler reads a tile, waits, multiplies, reads the next into the
+      // same registers: the LDS latency then shows once per tile and the matrix unit idles two thirds of the time).
+      u32x4 bfr[2][BT];
+      {
+        const u32x4* bsrc = wide8_stage + ((size_t)(buf * KC) * BT) * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < BT; ++t) bfr[0][t] = bsrc[t * 64];
+      }
 #pragma unroll
       for (int j = 0; j < KC; ++j) {
         const int u = ss * KC + j;
+        if (j + 1 < KC) {
+          const u32x4* bsrc = wide8_stage + ((size_t)(buf * KC + j + 1) * BT) * 64 + lane;
+#pragma unroll
+          for (int t = 0; t < BT; ++t) bfr[(j + 1) & 1][t] = bsrc[t * 64];
+        }
+        __builtin_amdgcn_sched_barrier(0);
         half8 af[NTW];
 #pragma unroll
         for (int a = 0; a < NTW; ++a) af[a] = __builtin_bit_cast(half8, Areg[u][a]);
-        const u32x4* bsrc = wide8_stage + ((size_t)(buf * KC + j) * BT) * 64 + lane;
 #pragma unroll
         for (int t = 0; t < BT; ++t) {
-          const half8 bf = __builtin_bit_cast(half8, bsrc[t * 64]);
+          const half8 bf = __builtin_bit_cast(half8, bfr[j & 1][t]);
 #pragma unroll
           for (int a = 0; a < NTW; ++a) acc[a][t / HL] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[a], bf, acc[a][t / HL], 0, 0, 0);
         }
