@@ -333,6 +333,34 @@ def test_7b_full_depth_against_oracle_and_losslessness():
     s.close()
 
 
+def test_verify_twice_gives_the_same_bits():
+    """The K slices of the down projection and the attention's key splits are added by whichever block finishes
+    last, always in slice order: two verify passes over the same drafts (the second re-writes the same cache
+    rows) must agree bit for bit, for 13 rows (8 key splits per head) and for 17 (two row-tile blocks per head)."""
+    import torch
+    from paper_2602_01274_amd import binding as B
+    w = synth.workload("7b")
+    tgt, drf, mb = synth.make_pair(w, seed=0, gain_jitter=0.1, n_layers_target=3)
+    s = _session(w, tgt, drf, mb, 768)
+    s.prefill(synth.make_prompt(w["target"]["vocab"], 600, 1).tolist())
+    for gamma in (12, 16):
+        B.pacer_begin_step(s.ctx, 0)
+        for _ in range(gamma):
+            B.pacer_draft_step(s.ctx, [0], B.GREEDY, 0, s.step_idx[0])
+        B.pacer_verify(s.ctx, [0], None, s.logits)
+        torch.cuda.synchronize()
+        first = s.logits[0, :gamma + 1].clone()
+        for _ in range(3):
+            B.pacer_verify(s.ctx, [0], None, s.logits)
+            torch.cuda.synchronize()
+            assert torch.equal(first, s.logits[0, :gamma + 1])
+        assert torch.isfinite(first).all()
+        B.pacer_accept_rollback(s.ctx, [0], B.GREEDY, [w["beta"]], 0, s.step_idx[0], s.logits, s.n_acc, s.next_tok)
+        B.pacer_get_state(s.ctx, 0)
+        s.step_idx[0] += 1
+    s.close()
+
+
 def test_wait_stop_and_get_state_match_the_device_buffers():
     """The host-polled words (stop flags, accept results) carry what the kernels wrote to the caller's
     device buffers, call after call, also across a re-prefill (tickets are never reused)."""
