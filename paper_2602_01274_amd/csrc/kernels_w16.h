@@ -758,13 +758,13 @@ __global__ __launch_bounds__(256 * KS, (KS == 1 ? 2 : 1)) void gemm_wide_kernel(
 // counter, L2-bypassing loads: see gemm_w16_kernel).  Measured at d 5120, K 13824, 128 rows: 53 us against
 // 75 us for the best shape of the kernel above; 144 rows: 63 against 80 us.
 //   grid = ceil(groups / 8) * 8 * row_groups * KSB, block id -> (XCD = id % 8, then row group, K slice, group)
-//   dynamic LDS = 3 * KC * MTB * HL KiB (operand of three super-steps of KC K steps)
+//   dynamic LDS = 2 * KC * MTB * HL KiB (operand of two super-steps of KC K steps)
 // Requires KT % 4 == 0 and KT / 4 >= KSB.
 template <int EPI, int NTW, int MTB, int HL, int TAG, int KC, int KSB>
 __global__ __launch_bounds__(512, 1) void gemm_wide8_kernel(const GemmArgs ga, int n_tiles, int n_groups, int row_groups) {
   constexpr int WV = 8, UA = 4, BT = MTB * HL, ITS = (KC * BT + WV - 1) / WV;
   static_assert(UA % KC == 0, "super-steps divide the weight prefetch depth");
-  extern __shared__ __align__(16) u32x4 wide8_stage[];     // [3][KC][BT][64]
+  extern __shared__ __align__(16) u32x4 wide8_stage[];     // [2][KC][BT][64]
   __shared__ unsigned arrived;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -813,43 +813,36 @@ __global__ __launch_bounds__(512, 1) void gemm_wide8_kernel(const GemmArgs ga, i
 #pragma unroll
     for (int it = 0; it < ITS; ++it) wide8_stage[(size_t)buf * KC * BT * 64 + xdst[it]] = Breg[it];
   };
-  // same load order in the prologue and in the loop, pinned (see gemm_wide_kernel).
-  // Three LDS stages: super-step s multiplies from stage s % 3 while stage (s + 2) % 3 is written, so stage
-  // (s + 1) % 3 was completed one barrier ago and its first K step can be read before this super-step's barrier.
-  static_assert(KC % 2 == 0, "the two operand register sets alternate per K step across super-steps");
+  // same load order in the prologue and in the loop, pinned (see gemm_wide_kernel)
   loadB(kb);
   storeB(0);
   loadB(kb + KC);
-  storeB(1);
-  loadB(kb + 2 * KC);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int u = 0; u < UA; ++u) loadA(Areg[u], kb + u);
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
-  // The operand tiles of K step j+1 are read from LDS into a second register set before the products of
-  // step j are issued (with one set the compiler reads a tile, waits, multiplies, reads the next into the
-  // same registers: the LDS latency then shows once per tile and the matrix unit idles two thirds of the time).
-  u32x4 bfr[2][BT];
-  {
-    const u32x4* bsrc = wide8_stage + lane;
-#pragma unroll
-    for (int t = 0; t < BT; ++t) bfr[0][t] = bsrc[t * 64];
-  }
   int buf = 0;
   for (int k0 = kb; k0 < ke; k0 += UA) {
 #pragma unroll
     for (int ss = 0; ss < UA / KC; ++ss) {
-      const int buf1 = buf == 2 ? 0 : buf + 1, buf2 = buf1 == 2 ? 0 : buf1 + 1;
-      storeB(buf2);                                          // operand of the super-step after the next
-      loadB(k0 + ss * KC + 3 * KC);
+      storeB(buf ^ 1);                                       // operand of the next super-step
+      loadB(k0 + ss * KC + 2 * KC);
       __builtin_amdgcn_sched_barrier(0);
+      // The operand tiles of K step j+1 are read from LDS into a second register set before the products of
+      // step j are issued (with one set the compiler reads a tile, waits, multiplies, reads the next into the
+      // same registers: the LDS latency then shows once per tile and the matrix unit idles two thirds of the time).
+      u32x4 bfr[2][BT];
+      {
+        const u32x4* bsrc = wide8_stage + ((size_t)(buf * KC) * BT) * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < BT; ++t) bfr[0][t] = bsrc[t * 64];
+      }
 #pragma unroll
       for (int j = 0; j < KC; ++j) {
         const int u = ss * KC + j;
-        {
-          // next K step: of this stage, or the first one of the next stage
-          const u32x4* bsrc = wide8_stage + ((size_t)((j + 1 < KC ? buf : buf1) * KC + (j + 1 < KC ? j + 1 : 0)) * BT) * 64 + lane;
+        if (j + 1 < KC) {
+          const u32x4* bsrc = wide8_stage + ((size_t)(buf * KC + j + 1) * BT) * 64 + lane;
 #pragma unroll
           for (int t = 0; t < BT; ++t) bfr[(j + 1) & 1][t] = bsrc[t * 64];
         }
@@ -867,7 +860,7 @@ __global__ __launch_bounds__(512, 1) void gemm_wide8_kernel(const GemmArgs ga, i
         __builtin_amdgcn_sched_barrier(0);
       }
       __syncthreads();
-      buf = buf1;
+      buf ^= 1;
     }
   }
   if (KSB > 1) {

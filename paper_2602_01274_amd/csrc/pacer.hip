@@ -309,7 +309,7 @@ constexpr int kWide8KC = 4;
 // against 88 / 115 / 123 us.  The QKV GEMM does not gain (94 against 62 us).
 template <int EPI, int TAG, int HL, int NTW, int MTB, int KSB>
 void launch_wide8_shape(pacer_ctx* c, const GemmArgs& ga, int n_tiles, int n_groups) {
-  const size_t lds = (size_t)3 * kWide8KC * MTB * HL * 1024;
+  const size_t lds = (size_t)2 * kWide8KC * MTB * HL * 1024;
   hipExtLaunchKernelGGL((gemm_wide8_kernel<EPI, NTW, MTB, HL, TAG, kWide8KC, KSB>), dim3((unsigned)((n_groups + 7) / 8 * 8 * 2 * KSB)), dim3(512), lds,
                         c->stream, c->pe0, c->pe1, 0, ga, n_tiles, n_groups, 2);
 }
@@ -952,11 +952,11 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
     PACER_ATT_LDS(128, 2, 1); PACER_ATT_LDS(128, 1, 1); PACER_ATT_LDS(64, 2, 1); PACER_ATT_LDS(64, 1, 1);
 #undef PACER_ATT_LDS
   }
-  // the 8-wave wide GEMM stages its operand in dynamic LDS: up to 3 x 4 K steps x 6 row tiles x hi+lo KiB = 144 KiB
-#define PACER_W8_LDS(HL_, MTB_, KSB_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide8_kernel<EPI_RESID, 1, MTB_, HL_, 0, kWide8KC, KSB_>), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * kWide8KC * MTB_ * HL_ * 1024))
+  // the 8-wave wide GEMM stages its operand in dynamic LDS: up to 2 x 4 K steps x 6 row tiles x hi+lo KiB = 96 KiB
+#define PACER_W8_LDS(HL_, MTB_, KSB_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide8_kernel<EPI_RESID, 1, MTB_, HL_, 0, kWide8KC, KSB_>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kWide8KC * MTB_ * HL_ * 1024))
   PACER_W8_LDS(2, 4, 2); PACER_W8_LDS(2, 4, 3); PACER_W8_LDS(2, 5, 2); PACER_W8_LDS(2, 5, 3); PACER_W8_LDS(2, 6, 2); PACER_W8_LDS(2, 6, 3);
 #undef PACER_W8_LDS
-#define PACER_W8_LDS(MTB_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide8_kernel<EPI_SWIGLU, 2, MTB_, 2, 0, kWide8KC, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * kWide8KC * MTB_ * 2 * 1024))
+#define PACER_W8_LDS(MTB_) HIPCHK(c, hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_wide8_kernel<EPI_SWIGLU, 2, MTB_, 2, 0, kWide8KC, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kWide8KC * MTB_ * 2 * 1024))
   PACER_W8_LDS(4); PACER_W8_LDS(5); PACER_W8_LDS(6);
 #undef PACER_W8_LDS
   c->ws_bound = true;
