@@ -116,17 +116,19 @@ class KVCache:
 
 
 def _attention_rows(q, K, V, pos, H, hd):
-    """q: [R, H*hd] (already rotated); K, V: cache arrays; row r attends to keys 0..pos[r]."""
+    """q: [R, H*hd] (already rotated); K, V: cache arrays; row r attends to keys 0..pos[r].
+    Per head: softmax(Q K^T / sqrt(hd) + causal mask) V, the masked-matrix form of Eq. 2."""
     R = q.shape[0]
+    pos = np.asarray(pos, dtype=np.int64)
+    n = int(pos.max()) + 1
     out = np.zeros((R, H * hd), dtype=F64)
     scale = 1.0 / np.sqrt(float(hd))
-    for r in range(R):
-        n = int(pos[r]) + 1
-        Kr = K[:n].reshape(n, H, hd)
-        Vr = V[:n].reshape(n, H, hd)
-        s = np.einsum("hd,nhd->hn", q[r].reshape(H, hd), Kr) * scale
-        p = softmax(s)
-        out[r] = np.einsum("hn,nhd->hd", p, Vr).reshape(-1)
+    hidden = np.arange(n)[None, :] > pos[:, None]          # [R, n]: keys after the row's own position
+    for h in range(H):
+        cols = slice(h * hd, (h + 1) * hd)
+        s = (q[:, cols] @ K[:n, cols].T) * scale           # [R, n]
+        s[hidden] = -np.inf
+        out[:, cols] = softmax(s) @ V[:n, cols]
     return out
 
 
