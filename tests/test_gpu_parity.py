@@ -36,9 +36,8 @@ def _run(name, n_prompt, n_new, tol_logits, tol_alpha, mode=po.GREEDY, seed=0, g
         ns.append(ro["n"])
     toks = s.tokens()
     assert toks == o.tokens
-    print(f"\n[{name} mode={mode}] steps={ck.steps} gamma mean={np.mean(gammas):.2f} tau={np.mean(ns):.2f} "
-          f"max_err={ck.max_err} flips={ck.flips}")
-    assert len(ck.flips) <= max(2, ck.steps // 5)      # each step holds gamma+2 integer decisions
+    print(f"\n[{name} mode={mode}] gamma mean={np.mean(gammas):.2f} tau={np.mean(ns):.2f} {ck.summary()}")
+    ck.assert_flip_budget()                            # ties (< 1e-3) are only logged; within_error: 1 per 50 decisions
     s.close()
     return ck, gammas, ns
 
@@ -107,6 +106,23 @@ def test_7b_width_two_layers_bf16():
          w_over=dict(mode="greedy"))
 
 
+def test_7b_width_two_layers_sampling():
+    """The headline workload's own decoding mode (stochastic sampling at temperature 1) at its width and
+    vocabulary (d 4096, V 32000, gamma_max 16, b 4, beta 3): Gumbel-max draft tokens, the accept test
+    r <= p/q and the residual resampling of Eq. 5 over 32000 entries, against the oracle on the same
+    Philox streams."""
+    _run("7b", 100, 24, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2, mode=po.SAMPLE, seed=3)
+
+
+def test_7b_width_long_context_4100_keys():
+    """The long-context workload's regime (4096-token prompt) at the 7B width: 4100 prompt tokens, so every
+    cache offset and position beyond 4096 is exercised, full windows (17 verify rows over more than 4100
+    keys: 8 key splits per head for the target, 4 for the draft and the pre-verification layer, combined by
+    the block that finishes last), prompt ingestion in nine 512-row passes."""
+    _run("7b", 4100, 10, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2, max_seq=4352,
+         w_over=dict(mode="greedy"), step_kw=dict(force_stop=lambda k, a: False))
+
+
 def test_7b_width_full_window_and_long_prompt():
     """gamma = gamma_max = 16 every step (17 verify rows: one full row tile + row 16), on a 2100-token
     prompt: the target's attention splits its keys over 8 blocks per head, the draft's and the
@@ -142,9 +158,12 @@ def _run_batch(name, prompt_lens, betas, n_steps, tol_logits, tol_alpha, mode=po
         full.append([r["n"] == r["gamma"] for r in ros])
     for i, ck in enumerate(cks):
         assert s.tokens(i) == ck.o.tokens
-    flips = [f for ck in cks for f in ck.flips]
-    print(f"\n[batch {name} x{nb} mode={mode}] gammas={gam} max_err={[ck.max_err['target_logits'] for ck in cks]} flips={flips}")
-    assert len(flips) <= max(2, n_steps * nb // 5)
+    ties = [f for ck in cks for f in ck.ties()]
+    werr = [f for ck in cks for f in ck.within_error()]
+    decisions = sum(ck.decisions for ck in cks)
+    print(f"\n[batch {name} x{nb} mode={mode}] gammas={gam} max_err={[ck.max_err['target_logits'] for ck in cks]} "
+          f"decisions={decisions} ties={ties} within_error={werr}")
+    assert len(werr) <= max(1, decisions // 50)
     assert not ragged or len({tuple(g) for g in gam}) > 1 or len(set(gam[0])) > 1      # the batch really was ragged
     s.close()
     return full
@@ -292,30 +311,40 @@ def _host_copy(x):
     return x.cpu()
 
 
-def test_7b_full_depth_against_oracle_and_losslessness():
-    """Workload `7b` (the headline configuration) at full size (32 layers, d 4096, FFN 11008, V 32000; 68M-shaped draft), in
-    the launch configuration bench.py times (weights generated on the device, gamma_max 16, b 4,
-    beta 3).  (i) Two Pacer steps after a short prompt are compared with the oracle row by row
-    (every logit of every verify row).  (ii) Property that holds at any size: greedy speculative
-    decoding emits the tokens of target-only greedy decoding run through the same kernels; a
-    mismatch must sit at a near-tie of the GPU's own deciding logits."""
+def test_7b_full_depth_headline_settings_against_oracle_and_losslessness(capsys):
+    """Workload `7b` as BASELINE names it: full size (32 layers, d 4096, FFN 11008, V 32000; 68M-shaped draft),
+    512-token prompt, stochastic sampling at temperature 1, gamma_max 16, b 4, beta 3, in the launch
+    configuration bench.py times (weights generated on the device).  (i) Two sampling steps and one greedy
+    step at that context are compared with the oracle row by row (every logit of every verify row, every
+    draft logit, alpha, every integer decision).  (ii) Property that holds at any size: greedy speculative
+    decoding emits the tokens of target-only greedy decoding run through the same kernels; a mismatch must
+    sit at a near-tie of the GPU's own deciding logits."""
+    def say(msg):
+        with capsys.disabled():
+            print(f"[7b full depth] {msg}", flush=True)
     w = synth.workload("7b")
-    w["mode"] = "greedy"
+    assert w["mode"] == "sample" and w["prompt"] == 512
     tgt, drf, mb = synth.make_pair(w, seed=0, device="cuda")
     s = _session(w, tgt, drf, mb, 1024)
     host = (_host_copy(tgt), _host_copy(drf), _host_copy(mb))
     del tgt, drf, mb
     torch.cuda.empty_cache()
-    prompt = synth.make_prompt(32000, 12, 1).tolist()
-    o = helpers.build_oracle(w, host[0], host[1], host[2], mode=po.GREEDY, max_seq=64)
+    prompt = synth.make_prompt(32000, w["prompt"], 1).tolist()
+    o = helpers.build_oracle(w, host[0], host[1], host[2], mode=po.SAMPLE, seed=3, max_seq=640)
     s.prefill(prompt)
+    say("oracle: 511-row prompt pass through 32 layers ...")
     o.prefill(prompt)
-    ck = StepChecker(s, o, 2e-2, 2e-2)
-    for _ in range(2):
-        ck.step()
-    print(f"\n[7b full depth] max_err={ck.max_err} flips={ck.flips}")
+    ck = StepChecker(s, o, 2e-2, 2e-2, mode=po.SAMPLE, seed=3)
+    for i in range(2):
+        ro, _ = ck.step()
+        say(f"sampling step {i}: gamma {ro['gamma']} n {ro['n']} {ck.summary()}")
+    o.mode = ck.mode = po.GREEDY
+    ro, _ = ck.step()
+    say(f"greedy step: gamma {ro['gamma']} n {ro['n']} {ck.summary()}")
+    ck.assert_flip_budget()
     assert s.tokens() == o.tokens
     # (ii) losslessness on the GPU itself, longer run, 300-token prompt
+    w["mode"] = "greedy"
     prompt = synth.make_prompt(32000, 300, 2).tolist()
     s.prefill(prompt)
     spec, recs = s.generate(40, record=True)
@@ -327,7 +356,7 @@ def test_7b_full_depth_against_oracle_and_losslessness():
         r = recs_ar[k]
         eff = (r["target_logits"][0] + w["beta"] * r["draft_logits"][0]).double().cpu().numpy()
         top = np.sort(eff)[-2:]
-        print(f"speculative and autoregressive runs part at token {k}: top-2 gap {top[1] - top[0]:.2e}")
+        say(f"speculative and autoregressive runs part at token {k}: top-2 gap {top[1] - top[0]:.2e}")
         assert top[1] - top[0] < 2e-2 * np.sqrt(np.mean(eff ** 2))
     assert any(r["n"] > 0 for r in recs) and any(r["n"] < r["gamma"] for r in recs)
     s.close()
@@ -361,6 +390,41 @@ def test_verify_twice_gives_the_same_bits():
     s.close()
 
 
+def test_verify_twice_gives_the_same_bits_batched_13b_width():
+    """The same guard for the batched kernels: ten sequences x 17 rows = 170 rows at the 13B width put the down
+    projection through the 8-wave wide kernel with three K slices across blocks (partial tiles added by the
+    block that finishes last), and prompts of 40 to 1500 tokens give the sequences one to several key splits
+    in one attention launch.  Repeated verify passes over the same drafts must agree bit for bit; the run
+    stops at the first mismatch."""
+    from paper_2602_01274_amd import binding as B
+    w = synth.workload("13b_batch")
+    tgt, drf, mb = synth.make_pair(w, seed=0, gain_jitter=0.1, n_layers_target=2)
+    lens = [40, 1500, 90, 700, 33, 1100, 260, 64, 900, 130]
+    nb = len(lens)
+    s = _session(w, tgt, drf, mb, 1600, max_batch=nb)
+    seqs = list(range(nb))
+    for i, n in enumerate(lens):
+        s.prefill(synth.make_prompt(w["target"]["vocab"], n, 70 + i).tolist(), seq=i)
+    for gamma in (16, 12):
+        for i in seqs:
+            B.pacer_begin_step(s.ctx, i)
+        for _ in range(gamma):
+            B.pacer_draft_step(s.ctx, seqs, B.GREEDY, 0, s.step_idx[0])
+        B.pacer_verify(s.ctx, seqs, None, s.logits)
+        torch.cuda.synchronize()
+        first = s.logits[:, :gamma + 1].clone()
+        assert torch.isfinite(first).all()
+        for rep in range(3):
+            B.pacer_verify(s.ctx, seqs, None, s.logits)
+            torch.cuda.synchronize()
+            assert torch.equal(first, s.logits[:, :gamma + 1]), f"gamma {gamma}: repeat {rep} differs"
+        B.pacer_accept_rollback(s.ctx, seqs, B.GREEDY, [3.0] * nb, 0, s.step_idx[0], s.logits, s.n_acc, s.next_tok)
+        for i in seqs:
+            B.pacer_get_state(s.ctx, i)
+            s.step_idx[i] += 1
+    s.close()
+
+
 def test_wait_stop_and_get_state_match_the_device_buffers():
     """The host-polled words (stop flags, accept results) carry what the kernels wrote to the caller's
     device buffers, call after call, also across a re-prefill (tickets are never reused)."""
@@ -384,8 +448,6 @@ def test_wait_stop_and_get_state_match_the_device_buffers():
                 B.pacer_preverify_block(s.ctx, seqs, s.alpha, s.stop)
                 flags = B.pacer_wait_stop(s.ctx, seqs)
                 assert flags == s.stop[:3].tolist()
-                assert flags == [int(np.float32(np.mean(np.float32(a))) <= np.float32(w["t0"] * w["rho"] ** blk))
-                                 for a in s.alpha[:3].tolist()] or True   # (alpha is compared with the oracle elsewhere)
             B.pacer_verify(s.ctx, seqs, None, s.logits)
             B.pacer_accept_rollback(s.ctx, seqs, B.GREEDY, [4.0, 1.0, 2.5], 0, step, s.logits, s.n_acc, s.next_tok)
             for k, i in enumerate(seqs):
