@@ -101,7 +101,7 @@ typedef struct {
 int32_t pacer_create(pacer_ctx** out, const pacer_model_cfg* target, const pacer_model_cfg* draft,
                      const pacer_pv_cfg* pv, int32_t max_batch, void* hip_stream);
 void pacer_destroy(pacer_ctx* ctx);
-const char* pacer_last_error(const pacer_ctx* ctx);
+const char* pacer_last_error(const pacer_ctx* ctx); /* ctx may be NULL: last failure of a context-free call on this thread */
 
 /* Re-tiles a row-major bf16 matrix [n_out][n_in] (dev_src) into the layout the bf16 kernels
  * stream (dev_dst, same size, must not alias).  The packed copy holds each bf16 value as an IEEE
@@ -210,6 +210,31 @@ int32_t pacer_accept_rollback(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seq
                               const float* beta, uint64_t rng_seed, uint64_t rng_ctr,
                               const float* dev_logits, int32_t* dev_n_accepted,
                               int32_t* dev_next_token);
+
+/* For callers that cannot allocate device memory and hold no context: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The acceptance rule of pacer_accept_rollback for ONE sequence on
+ * logits the caller holds, through the same kernels, with their scratch (per-row, per-vocabulary-chunk statistics,
+ * token candidates and reject flags; 17 KiB) in a fixed array inside the library's device image instead of a
+ * workspace.  Calls no hipMalloc / hipFree and no allocating routine; enqueues on hip_stream and returns.
+ *   dev_target_logits [gamma+1][vocab] f32  row i = target logits after y_1..y_i (row gamma: the bonus row)
+ *   dev_draft_logits  [gamma+1][vocab] f32  row i = draft logits q_{i+1}; row gamma is read only if bonus_row != 0
+ *   dev_draft_tokens  [gamma] i32           y_1..y_gamma
+ *   bonus_row         nonzero: if every draft is accepted the new token is taken from row gamma of both logits
+ *                     buffers; zero: that case yields next token -1 and the caller evaluates the bonus row later
+ *   beta, mode, rng_seed, rng_ctr, seq      as in pacer_accept_rollback (seq 0..PACER_MAX_BATCH-1 keys the random streams)
+ *   dev_n_accepted[1], dev_next_token[1]    results (device memory, valid after the stream has passed the call)
+ * gamma may be 0..PACER_NOALLOC_MAX_GAMMA; a larger gamma is refused with PACER_EOVERFLOW.  Nothing but the two
+ * results is written: no tokens are committed and no cache length changes.  The device that is current when the
+ * call is made must be the one hip_stream belongs to; on the first call on a device the library looks up that
+ * device's copy of the array.  All calls on one GPU share that GPU's array: calls whose kernels may overlap there
+ * (different streams, or several threads) race and must be serialised by the caller; calls on one stream are
+ * ordered.  The array keeps the previous call's contents; every word a call reads it has written itself before.
+ * After a failure pacer_last_error(NULL) returns the message (per thread). */
+#define PACER_NOALLOC_MAX_GAMMA 31
+int32_t pacer_accept_noalloc(const float* dev_target_logits, const float* dev_draft_logits,
+                             const int32_t* dev_draft_tokens, int32_t gamma, int32_t bonus_row, int32_t vocab,
+                             int32_t mode, float beta, uint64_t rng_seed, uint64_t rng_ctr, int32_t seq,
+                             int32_t* dev_n_accepted, int32_t* dev_next_token, void* hip_stream);
 
 /* Waits for the sequence's pending pacer_accept_rollback, if any (by polling the pinned host
  * words its last kernel writes; it does not synchronise the stream), folds the result into the

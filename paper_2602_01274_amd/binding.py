@@ -27,7 +27,7 @@ EXPORTS = [
     "pacer_kv_bytes", "pacer_bind_kv", "pacer_workspace_bytes", "pacer_bind_workspace",
     "pacer_prefill", "pacer_force_commit", "pacer_begin_step", "pacer_draft_step",
     "pacer_preverify_block", "pacer_wait_stop", "pacer_verify", "pacer_accept_rollback", "pacer_get_state",
-    "pacer_peek", "pacer_profile_enable", "pacer_profile_read", "pacer_launch_plan",
+    "pacer_peek", "pacer_profile_enable", "pacer_profile_read", "pacer_launch_plan", "pacer_accept_noalloc",
 ]
 
 
@@ -77,6 +77,7 @@ def _load():
         "pacer_profile_enable": (i32, [vp, i32]),
         "pacer_launch_plan": (i32, [i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]),
         "pacer_profile_read": (i32, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "pacer_accept_noalloc": (i32, [vp, vp, vp, i32, i32, i32, i32, C.c_float, u64, u64, i32, vp, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -182,6 +183,15 @@ def pacer_accept_rollback(ctx, seqs, mode, beta, rng_seed, rng_ctr, dev_logits, 
     b = (C.c_float * len(beta))(*beta)
     _chk(ctx, _lib.pacer_accept_rollback(ctx, _i32s(seqs), len(seqs), mode, b, rng_seed, rng_ctr,
                                          _ptr(dev_logits), _ptr(dev_n), _ptr(dev_z)))
+
+
+def pacer_accept_noalloc(dev_target_logits, dev_draft_logits, dev_draft_tokens, gamma, bonus_row, vocab, mode, beta,
+                         rng_seed, rng_ctr, seq, dev_n, dev_z, stream):
+    rc = _lib.pacer_accept_noalloc(_ptr(dev_target_logits), _ptr(dev_draft_logits), _ptr(dev_draft_tokens), gamma,
+                                   1 if bonus_row else 0, vocab, mode, beta, rng_seed, rng_ctr, seq, _ptr(dev_n), _ptr(dev_z),
+                                   C.c_void_p(stream))
+    if rc != OK:
+        raise PacerError(rc, _lib.pacer_last_error(None).decode())
 
 
 def pacer_get_state(ctx, seq):

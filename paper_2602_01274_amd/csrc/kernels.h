@@ -539,7 +539,9 @@ __global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const floa
 // slot: the sequence's index in the verify call that wrote the logits (row slot*G1 + i of tl, entry slot of the
 // caller's n / z arrays).  The kernels run in two phases: phase 0 covers rows i < gamma (everything a step needs
 // unless every draft is accepted), phase 1 the bonus row i = gamma of the sequences that accepted all drafts.
-struct AccArgs { int n_seqs; int seq[PK_MAXB]; int slot[PK_MAXB]; int gamma[PK_MAXB]; int len[PK_MAXB]; float beta[PK_MAXB]; };
+// qslot: the sequence's block of G1 rows in the draft logits and draft token buffers (the sequence id for a context's
+// rings); seq itself keys the random streams and indexes the committed tokens and the host words.
+struct AccArgs { int n_seqs; int seq[PK_MAXB]; int slot[PK_MAXB]; int qslot[PK_MAXB]; int gamma[PK_MAXB]; int len[PK_MAXB]; float beta[PK_MAXB]; };
 
 // One row of logits is split into ACC_CHUNKS vocabulary ranges, one block each (a single block per row
 // spent 53 us walking 32000 entries three times).  Three launches:
@@ -561,15 +563,18 @@ __device__ __forceinline__ void acc_chunk_range(int V, int chunk, int& v0, int& 
 }
 
 // grid (gamma_max+1, n_seqs, ACC_CHUNKS)
+// done_z (phase 1 only, may be null): the phase-0 results; a sequence whose entry is >= 0 already has its token
+// (a draft was rejected) and the bonus row is skipped.
 __global__ __launch_bounds__(256) void accept_stats_kernel(const float* __restrict__ tl, const float* __restrict__ ring, AccArgs aa, int G1,
-                                                           int V, int phase, float* __restrict__ part) {
+                                                           int V, int phase, float* __restrict__ part, const int* __restrict__ done_z) {
   __shared__ float redv[16];
-  const int si = blockIdx.y, ch = blockIdx.z, s = aa.seq[si], sl = aa.slot[si];
+  const int si = blockIdx.y, ch = blockIdx.z, sl = aa.slot[si];
   const int i = phase ? aa.gamma[si] : blockIdx.x;
   if (!phase && i >= aa.gamma[si]) return;
+  if (phase && done_z && done_z[sl] >= 0) return;
   const float beta = aa.beta[si];
   const float* t = tl + (size_t)(sl * G1 + i) * V;
-  const float* q = ring + (size_t)(s * G1 + i) * V;
+  const float* q = ring + (size_t)(aa.qslot[si] * G1 + i) * V;
   int v0, v1;
   acc_chunk_range(V, ch, v0, v1);
   float mp = -INFINITY, mq = -INFINITY;
@@ -591,17 +596,18 @@ __global__ __launch_bounds__(256) void accept_stats_kernel(const float* __restri
 __global__ __launch_bounds__(256) void accept_rows_kernel(const float* __restrict__ tl, const float* __restrict__ ring,
                                                           const int* __restrict__ draft_tok, AccArgs aa, int G1, int V, int mode,
                                                           uint64_t seed, uint32_t step, int phase, float* __restrict__ part,
-                                                          int* __restrict__ rej) {
+                                                          int* __restrict__ rej, const int* __restrict__ done_z) {
   __shared__ float redv[16];
   __shared__ int redi[16];
   const int si = blockIdx.y, ch = blockIdx.z, s = aa.seq[si], sl = aa.slot[si];
   const int gamma = aa.gamma[si];
   const int i = phase ? gamma : blockIdx.x;
   if (!phase && i >= gamma) return;
+  if (phase && done_z && done_z[sl] >= 0) return;
   const float beta = aa.beta[si];
   const float* t = tl + (size_t)(sl * G1 + i) * V;
-  const float* q = ring + (size_t)(s * G1 + i) * V;
-  const int y = i < gamma ? draft_tok[s * G1 + i] : -1;
+  const float* q = ring + (size_t)(aa.qslot[si] * G1 + i) * V;
+  const int y = i < gamma ? draft_tok[aa.qslot[si] * G1 + i] : -1;
   float* prow = part + (size_t)(sl * G1 + i) * ACC_CHUNKS * ACC_PART;
   float* o = prow + ch * ACC_PART;
   int v0, v1;
@@ -673,14 +679,17 @@ __global__ __launch_bounds__(256) void accept_rows_kernel(const float* __restric
 
 // Phase 0: n = first rejected row (or gamma).  n < gamma: next token = row n's candidate, tokens appended, results
 // (n, z) to the caller's arrays and to pinned host memory.  n = gamma: the bonus row has not been evaluated yet
-// (its draft logits need one more draft forward): the drafts are appended and (gamma, -1) tells the host to run
-// phase 1, which takes the token of row gamma.  The ticket is written last; the host polls for it.
+// (its draft logits need one more draft forward): the drafts are appended and (gamma, -1) says that phase 1, which
+// takes the token of row gamma, is still to come.  The ticket is written last; the host polls for it.
+// skip_done (phase 1): leave a sequence alone whose phase-0 result already holds a token (out_z >= 0).
+// tokens and the host words may be null (acceptance on caller-held logits without a context).
 __global__ void accept_finalize_kernel(const float* __restrict__ part, const int* __restrict__ rej, const int* __restrict__ draft_tok,
                                        AccArgs aa, int G1, int mode, int phase, int max_seq, int* __restrict__ tokens,
                                        int* __restrict__ out_n, int* __restrict__ out_z, int* __restrict__ host_res,
-                                       int* __restrict__ host_tick, int ticket) {
-  const int si = blockIdx.x, s = aa.seq[si], sl = aa.slot[si];
+                                       int* __restrict__ host_tick, int ticket, int skip_done) {
+  const int si = blockIdx.x, s = aa.seq[si], sl = aa.slot[si], qs = aa.qslot[si];
   const int gamma = aa.gamma[si];
+  if (phase && skip_done && out_z[sl] >= 0) return;
   int n = gamma;
   if (!phase) {
     if (mode == 0) {
@@ -694,7 +703,7 @@ __global__ void accept_finalize_kernel(const float* __restrict__ part, const int
           const int id = __float_as_int(pr[c * ACC_PART + 7]);
           if (v > best || (v == best && id < bi)) { best = v; bi = id; }
         }
-        if (bi != draft_tok[s * G1 + i]) n = i;
+        if (bi != draft_tok[qs * G1 + i]) n = i;
       }
     } else {
       for (int i = gamma - 1; i >= 0; --i)
@@ -715,17 +724,19 @@ __global__ void accept_finalize_kernel(const float* __restrict__ part, const int
     }
     z = (n < gamma && best > -INFINITY) ? bi : bip;
   }
-  int* tk = tokens + (size_t)s * max_seq + aa.len[si];
-  if (!phase)
-    for (int k = threadIdx.x; k < n; k += blockDim.x) tk[k] = draft_tok[s * G1 + k];
+  int* tk = tokens ? tokens + (size_t)s * max_seq + aa.len[si] : nullptr;
+  if (!phase && tk)
+    for (int k = threadIdx.x; k < n; k += blockDim.x) tk[k] = draft_tok[qs * G1 + k];
   if (threadIdx.x == 0) {
-    if (z >= 0) tk[n] = z;
+    if (z >= 0 && tk) tk[n] = z;
     out_n[sl] = n;
     out_z[sl] = z;
-    host_res[2 * s] = n;
-    host_res[2 * s + 1] = z;
-    __threadfence_system();            // the results first, then the ticket the host polls for
-    host_tick[s] = ticket;
+    if (host_res) {
+      host_res[2 * s] = n;
+      host_res[2 * s + 1] = z;
+      __threadfence_system();            // the results first, then the ticket the host polls for
+      host_tick[s] = ticket;
+    }
   }
 }
 

@@ -12,6 +12,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -780,6 +781,53 @@ int fold(pacer_ctx* c, int s) {
   return PACER_OK;
 }
 
+// ---- acceptance without a context and without any allocation ---------------------------------
+// The per-(row, vocabulary chunk) statistics and candidates and the per-row reject flags of the acceptance
+// kernels, for PACER_NOALLOC_MAX_GAMMA + 1 rows, in an array that is part of the library's device image: each
+// GPU the library runs on holds its own copy until the process ends.  Host code never uses the array's name as
+// an address (on the host it is only a stand-in for the symbol): the device address is looked up once per
+// device and kept.
+constexpr int kNoAllocRows = PACER_NOALLOC_MAX_GAMMA + 1;
+struct NoAllocScratch {
+  float part[kNoAllocRows * ACC_CHUNKS * ACC_PART];
+  int rej[kNoAllocRows];
+};
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+thread_local char g_err[256] = {0};     // last failure of a call that takes no context
+
+int fail_noctx(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[sizeof(NoAllocScratch)];
+
+namespace {
+
+// device address of `scratch` on the current device (looked up on the first call on that device)
+int scratch_on_current_device(NoAllocScratch** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_noctx(PACER_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail_noctx(PACER_EHIP, "device index %d beyond the %d this library keeps scratch for", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail_noctx(PACER_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<NoAllocScratch*>(g_scratch_ptr[dev]);
+  return PACER_OK;
+}
+
 }  // namespace
 
 // =============================================================================================
@@ -840,7 +888,7 @@ void pacer_destroy(pacer_ctx* c) {
   delete c;
 }
 
-const char* pacer_last_error(const pacer_ctx* c) { return c ? c->err : "null context"; }
+const char* pacer_last_error(const pacer_ctx* c) { return c ? c->err : (g_err[0] ? g_err : "null context"); }
 
 int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int32_t n_in, int32_t tensor_id, int32_t head_dim,
                           void* hip_stream) {
@@ -1183,13 +1231,14 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
     if (rows > 0) {
       const dim3 grid(rows, aa.n_seqs, ACC_CHUNKS);
       if (mode != PACER_GREEDY)
-        hipLaunchKernelGGL(accept_stats_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, aa, c->G1, V, phase, c->acc_part);
+        hipLaunchKernelGGL(accept_stats_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, aa, c->G1, V, phase, c->acc_part,
+                           (const int*)nullptr);
       hipLaunchKernelGGL(accept_rows_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode, seed,
-                         (uint32_t)ctr, phase, c->acc_part, c->rej);
+                         (uint32_t)ctr, phase, c->acc_part, c->rej, (const int*)nullptr);
     }
     hipLaunchKernelGGL(accept_finalize_kernel, dim3(aa.n_seqs), dim3(64), 0, c->stream, c->acc_part, c->rej, c->draft_tok, aa, c->G1,
                        mode, phase, c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev, c->host_res_dev + 2 * PACER_MAX_BATCH,
-                       ++c->acc_calls);
+                       ++c->acc_calls, 0);
     for (int i = 0; i < aa.n_seqs; ++i) c->seq[aa.seq[i]].acc_ticket = c->acc_calls;
   };
   mb_prefix(seqs, n, false);
@@ -1198,7 +1247,7 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
   int gmax = 0;
   for (int i = 0; i < n; ++i) {
     const Seq& q = c->seq[seqs[i]];
-    aa.seq[i] = seqs[i];
+    aa.seq[i] = aa.qslot[i] = seqs[i];
     aa.slot[i] = i;
     aa.gamma[i] = q.verified;
     aa.len[i] = q.len;
@@ -1216,7 +1265,7 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
     const Seq& q = c->seq[seqs[i]];
     if (int rc = wait_ticket(c, c->host_res + 2 * PACER_MAX_BATCH + seqs[i], q.acc_ticket, 0)) return rc;
     if (c->host_res[2 * seqs[i] + 1] >= 0) continue;
-    sub[m] = ab.seq[m] = seqs[i];
+    sub[m] = ab.seq[m] = ab.qslot[m] = seqs[i];
     jb[m] = q.verified;
     ab.slot[m] = i;
     ab.gamma[m] = q.verified;
@@ -1236,6 +1285,49 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
     q.in_step = false;
   }
   HIPCHK(c, hipGetLastError());
+  return PACER_OK;
+}
+
+int32_t pacer_accept_noalloc(const float* dev_target_logits, const float* dev_draft_logits, const int32_t* dev_draft_tokens,
+                             int32_t gamma, int32_t bonus_row, int32_t vocab, int32_t mode, float beta, uint64_t seed, uint64_t ctr,
+                             int32_t seq, int32_t* dev_n, int32_t* dev_z, void* hip_stream) {
+  if (!dev_target_logits || !dev_draft_logits || !dev_draft_tokens || !dev_n || !dev_z)
+    return fail_noctx(PACER_EINVAL, "accept_noalloc: null argument");
+  if (gamma < 0 || vocab < 1 || seq < 0 || seq >= PACER_MAX_BATCH) return fail_noctx(PACER_EINVAL, "accept_noalloc: bad gamma, vocab or sequence id");
+  if (mode != PACER_GREEDY && mode != PACER_SAMPLE) return fail_noctx(PACER_EINVAL, "accept_noalloc: bad mode %d", mode);
+  if (gamma > PACER_NOALLOC_MAX_GAMMA)
+    return fail_noctx(PACER_EOVERFLOW, "accept_noalloc: gamma %d exceeds PACER_NOALLOC_MAX_GAMMA = %d (the fixed scratch holds %d rows)", gamma,
+                      PACER_NOALLOC_MAX_GAMMA, kNoAllocRows);
+  if (gamma == 0 && !bonus_row) return fail_noctx(PACER_EINVAL, "accept_noalloc: nothing to evaluate (gamma 0 and no bonus row)");
+  NoAllocScratch* sc = nullptr;
+  if (int rc = scratch_on_current_device(&sc)) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  AccArgs aa{};
+  aa.n_seqs = 1;
+  aa.seq[0] = seq;
+  aa.slot[0] = 0;
+  aa.qslot[0] = 0;
+  aa.gamma[0] = gamma;
+  aa.len[0] = 0;
+  aa.beta[0] = beta;
+  const int G1 = gamma + 1;
+  // Every word of the scratch that a launch reads was written earlier in this same call (statistics by
+  // accept_stats, candidates and reject flags by accept_rows), so nothing has to start at zero.
+  for (int phase = 0; phase < (bonus_row ? 2 : 1); ++phase) {
+    const int rows = phase ? 1 : gamma;
+    if (rows > 0) {
+      const dim3 grid(rows, 1, ACC_CHUNKS);
+      const int* done = phase ? dev_z : nullptr;
+      if (mode != PACER_GREEDY)
+        hipLaunchKernelGGL(accept_stats_kernel, grid, dim3(256), 0, st, dev_target_logits, dev_draft_logits, aa, G1, vocab, phase, sc->part, done);
+      hipLaunchKernelGGL(accept_rows_kernel, grid, dim3(256), 0, st, dev_target_logits, dev_draft_logits, dev_draft_tokens, aa, G1, vocab, mode,
+                         seed, (uint32_t)ctr, phase, sc->part, sc->rej, done);
+    }
+    hipLaunchKernelGGL(accept_finalize_kernel, dim3(1), dim3(64), 0, st, sc->part, sc->rej, dev_draft_tokens, aa, G1, mode, phase, 0,
+                       (int*)nullptr, dev_n, dev_z, (int*)nullptr, (int*)nullptr, 0, 1);
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_noctx(PACER_EHIP, "accept_noalloc: %s", hipGetErrorString(e));
   return PACER_OK;
 }
 

@@ -126,3 +126,27 @@ def test_launch_plan_of_the_few_tile_projections(B):
     for bad in ((8, 4096, 4, 1), (4096, 100, 4, 1), (4096, 4096, 0, 1), (4096, 4096, 33, 1), (4096, 4096, 4, 3), (16 * 512, 4096, 4, 1)):
         with pytest.raises(B.PacerError):
             B.pacer_launch_plan(*bad)
+
+
+def test_accept_noalloc_validates_on_the_host(B):
+    """The allocation-free acceptance call checks its arguments before it touches a GPU: null pointers, modes,
+    and a window beyond the fixed scratch's capacity (refused with PACER_EOVERFLOW and a message naming the limit)."""
+    import numpy as np
+
+    class Fake:
+        def __init__(self, nbytes):
+            self.a = np.zeros(nbytes, dtype=np.uint8)
+        def data_ptr(self):
+            return self.a.ctypes.data
+    f = Fake(64)
+    ok = dict(dev_target_logits=f, dev_draft_logits=f, dev_draft_tokens=f, gamma=4, bonus_row=1, vocab=64, mode=B.GREEDY,
+              beta=1.0, rng_seed=0, rng_ctr=0, seq=0, dev_n=f, dev_z=f, stream=0)
+    for over, code in ((dict(dev_target_logits=None), B.EINVAL), (dict(dev_draft_tokens=None), B.EINVAL),
+                       (dict(dev_z=None), B.EINVAL), (dict(mode=2), B.EINVAL), (dict(gamma=-1), B.EINVAL),
+                       (dict(seq=16), B.EINVAL), (dict(vocab=0), B.EINVAL), (dict(gamma=0, bonus_row=0), B.EINVAL),
+                       (dict(gamma=32), B.EOVERFLOW), (dict(gamma=1000), B.EOVERFLOW)):
+        with pytest.raises(B.PacerError) as e:
+            B.pacer_accept_noalloc(**dict(ok, **over))
+        assert e.value.code == code, over
+        if code == B.EOVERFLOW:
+            assert "PACER_NOALLOC_MAX_GAMMA = 31" in str(e.value)
