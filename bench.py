@@ -32,6 +32,7 @@ def run_steps(sess, n, mode, seed, batch=None, **kw):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     toks, gam, acc, cnt = 0, 0, 0, 0
+    reached, accepted = [0] * 32, [0] * 32            # per draft position 1..gamma_max
     for _ in range(n):
         if batch is None:
             rs = [sess.step(mode=mode, seed=seed, **kw)]
@@ -42,32 +43,67 @@ def run_steps(sess, n, mode, seed, batch=None, **kw):
             gam += r["gamma"]
             acc += r["n"]
             cnt += 1
+            for i in range(r["gamma"]):               # position i+1 is tested iff the i before it were accepted
+                if r["n"] >= i:
+                    reached[i] += 1
+                    accepted[i] += 1 if r["n"] > i else 0
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     return dict(tokens=toks, seconds=dt, tok_s=toks / dt, ms_per_step=1e3 * dt / n,
-                mean_gamma=gam / cnt, tau=acc / cnt)
+                mean_gamma=gam / cnt, tau=acc / cnt, reached=reached, accepted=accepted)
 
 
-def cpu_baseline(w, tgt, drf, mb, prompt, mode, budget_steps=2, n_prompt=16):
-    """The CPU oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+def cpu_baseline(w, tgt, drf, mb, prompt, mode, budget_steps=2, threads=None):
+    """The CPU oracle as it stands, on the host cores, on a bounded sample of the same workload: the
+    workload's full prompt (untimed, as on the GPU), then `budget_steps` decoding steps (timed)."""
     import numpy as np
     import helpers
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count()
-    o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=3, max_seq=n_prompt + 64)
-    o.prefill(prompt[:n_prompt])
+    from threadpoolctl import threadpool_info, threadpool_limits
+    ctl = threadpool_limits(limits=threads) if threads else None
+    cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=3, max_seq=len(prompt) + 64)
+    t0 = time.perf_counter()
+    o.prefill(prompt)
+    t_prompt = time.perf_counter() - t0
     t0 = time.perf_counter()
     toks = 0
     for _ in range(budget_steps):
         r = o.step()
         toks += r["n"] + 1
     dt = time.perf_counter() - t0
+    if ctl is not None:
+        ctl.restore_original_limits()
     return {"value": toks / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{budget_steps} Pacer steps ({toks} tokens, {dt:.1f} s) of the same pair after a "
-                      f"{n_prompt}-token prompt; numpy float64 oracle, BLAS threads = cores"}
+            "sample": f"{budget_steps} Pacer decoding steps ({toks} tokens, {dt:.1f} s, timed) of the same pair after the "
+                      f"workload's full {len(prompt)}-token prompt ({t_prompt:.1f} s, untimed); numpy float64 oracle, "
+                      f"BLAS threads = cores"}
+
+
+def stream_ceiling(torch, B):
+    """What this GPU delivers to kernels that only move data: a streaming read (the library's probe kernel) and a
+    plain device-to-device copy of 1 GiB, in GB/s (the copy counts read + written bytes)."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        best = 1e30
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best
+    read_ms = timed(lambda: B.pacer_stream_probe(src, sink, st))
+    copy_ms = timed(lambda: dst.copy_(src))
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"streaming_read_GBps": round(n / 1e6 / read_ms, 1), "device_copy_GBps": round(2 * n / 1e6 / copy_ms, 1),
+            "bytes": n, "note": "best of 5; the read kernel is the library's probe (16-byte loads, 1024 blocks of 8 waves)"}
 
 
 def main():
@@ -78,6 +114,8 @@ def main():
     ap.add_argument("--workload", default="7b")
     ap.add_argument("--layers", type=int, default=None, help="truncate target depth (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-one-thread", action="store_true",
+                    help="also time the CPU oracle with one BLAS thread (small workloads: tiny, mid)")
     ap.add_argument("--no-context", action="store_true", help="skip the AR / fixed-gamma context runs")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
@@ -152,6 +190,7 @@ def main():
     prof_steps = min(K, 40)
     run_steps(sess, prof_steps, mode, 3, batch)
     tm = sess.read_timers()
+    nl = sess.read_launches()
     sess.timers = None
     L = a.layers if a.layers else w["target"]["n_layers"]
     ctx_len = sum(lens) + 0.5 * main_run["tokens"]        # summed over the batch
@@ -166,7 +205,8 @@ def main():
         q = sorted(ts)
         pct = lambda f: q[min(len(q) - 1, int(f * len(q)))]
         calls[name] = {"mean_ms": round(ms, 4), "median_ms": round(pct(0.5), 4), "p10_ms": round(pct(0.1), 4),
-                       "p90_ms": round(pct(0.9), 4), "n": len(ts)}
+                       "p90_ms": round(pct(0.9), 4), "n": len(ts),
+                       "launches_per_call": round(sum(nl.get(name, [0])) / max(1, len(nl.get(name, [0]))), 2)}
         if name in alg:
             calls[name]["algorithmic_GB"] = round(alg[name] / 1e9, 4)
             calls[name]["GBps"] = round(alg[name] / 1e6 / ms, 1)
@@ -193,6 +233,10 @@ def main():
     cpu = None
     if host is not None:
         cpu = cpu_baseline(w, host[0], host[1], host[2], prompt, 1 if mode == B.SAMPLE else 0)
+        if a.cpu_one_thread:
+            one = cpu_baseline(w, host[0], host[1], host[2], prompt, 1 if mode == B.SAMPLE else 0, threads=1)
+            cpu["one_thread"] = {"value": one["value"], "cores": one["cores"], "sample": one["sample"]}
+    ceiling = stream_ceiling(torch, B)
 
     if a.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -216,13 +260,22 @@ def main():
         "metric": "decode tokens/s (7B-shape target, bs1) + verify-step achieved HBM GB/s",
         "value": round(main_run["tok_s"], 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(main_run["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None,
+        "dtype": ("f16 MFMA, f32 accumulate (bf16 weights held as f16; target activations as f16 hi + lo parts; f16 KV cache)"
+                  if w["dtype"] == "bf16" else "f32"),
+        "data": "synthetic",
         "config": {"workload": f"{a.workload}: {L}-layer d{w['target']['d_model']} target + {w['draft']['n_layers']}-layer "
                                f"d{w['draft']['d_model']} draft, prompt {n_prompt if nb == 1 else lens}, "
                                f"{'sampling T=1' if mode else 'greedy'}, gamma_max {w['gamma_max']}, "
                                f"b {w['block']}, beta {round(w['beta'], 3) if nb == 1 else 'U[1,5] per sequence'}, t0 {w['t0']}, rho {w['rho']}",
                    "batch": nb, "new_tokens": main_run["tokens"]},
         "tau": round(main_run["tau"], 3), "mean_gamma": round(main_run["mean_gamma"], 3),
+        # realised acceptance rate by draft position (accepted / tested at that position), to set beside the
+        # acceptance-versus-position figure of Sec. 3.1; positions never reached are null
+        "acceptance_by_position": [round(a / r, 3) if r else None
+                                   for a, r in zip(main_run["accepted"][:w["gamma_max"]], main_run["reached"][:w["gamma_max"]])],
+        "tested_by_position": main_run["reached"][:w["gamma_max"]],
+        "stream_ceiling": ceiling,
         "forwards": counts, "verify_GBps": calls.get("verify", {}).get("GBps"),
         "calls": calls, "context": context,
         "prefill": {"ms": round(prefill_ms, 2), "tokens": int(sum(lens)), "tok_s": round(sum(lens) / prefill_ms * 1e3, 1)},
@@ -230,6 +283,7 @@ def main():
                                + ", target-model launches (template TAG 0), all shapes",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "frac_of_streaming_read": round(achieved / ceiling["streaming_read_GBps"], 4),
                      "launches": int(n_launch), "avg_launch_us": round(1e3 * gemm_ms / max(1, n_launch), 3),
                      "avg_launch_bytes": round(gemm_bytes / max(1, n_launch), 1)},
         "cpu_baseline": cpu,

@@ -109,9 +109,14 @@ const char* pacer_last_error(const pacer_ctx* ctx); /* ctx may be NULL: last fai
  * to the nearest half subnormal).  The tiling depends on the role of the matrix:
  * tensor_id is the PACER_T_* id it will be bound as (WQKV, WO, WGU, WD or HEAD); head_dim is
  * needed for WQKV (rotation pairs of a head share a tile) and ignored otherwise.
+ * Half floats end at 65504: a weight beyond that (or an inf / NaN in the source) becomes a non-finite
+ * half.  dev_not_finite (device int32, may be NULL; the caller zeroes it) is incremented once per such
+ * weight, so that the caller can refuse the model instead of decoding garbage.  The same range holds for
+ * what the kernels store as half floats at run time: normalised activations times the norm gain, the
+ * SwiGLU product and the K/V cache entries must stay below 65504 in magnitude.
  * Enqueued on hip_stream. */
 int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int32_t n_in,
-                          int32_t tensor_id, int32_t head_dim, void* hip_stream);
+                          int32_t tensor_id, int32_t head_dim, int32_t* dev_not_finite, void* hip_stream);
 
 /* Borrow one weight tensor.  nbytes must equal the tensor's size for the model's shape. */
 int32_t pacer_bind(pacer_ctx* ctx, int32_t which, int32_t tensor_id, int32_t layer,
@@ -153,8 +158,8 @@ int32_t pacer_force_commit(pacer_ctx* ctx, int32_t seq, int32_t from, const int3
 /* ---- the hot path -------------------------------------------------------------------- */
 
 /* Start of one outer iteration of Alg. 1 for `seq`: threshold <- t0, draft position <- 1,
- * no drafts.  Waits for the sequence's previous pacer_accept_rollback, if its result has not
- * been collected yet (pacer_get_state collects it as well). */
+ * no drafts.  Collects the sequence's previous pacer_accept_rollback first, as pacer_get_state does, if
+ * that has not happened yet (this waits for its kernels). */
 int32_t pacer_begin_step(pacer_ctx* ctx, int32_t seq);
 
 /* Eq. 3 / Eq. 6: one draft-model forward per listed sequence on its newest token (the last
@@ -174,6 +179,13 @@ int32_t pacer_draft_step(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, in
  * exist since the last call. */
 int32_t pacer_preverify_block(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs,
                               float* dev_alpha, int32_t* dev_stop);
+
+/* Test tap: forces the stop flag of the NEXT pacer_preverify_block of `seq` (flag 1 = stop, 0 = go on; -1 takes a
+ * pending force back).  The pre-verification kernel still computes and writes alpha, then writes the forced flag to
+ * dev_stop and to the host-polled word instead of its own decision; the force is used up by that call.  Any stopping
+ * rule that looks only at draft-side quantities leaves the output law unchanged (Sec. 2.2), so sweeping forced
+ * patterns checks losslessness for every pre-verification decision. */
+int32_t pacer_force_stop(pacer_ctx* ctx, int32_t seq, int32_t flag);
 
 /* The stop flags of the last pacer_preverify_block of each listed sequence, as host values:
  * host_stop[n_seqs] (host array).  The kernel also writes each flag, tagged with the number of
@@ -197,15 +209,19 @@ int32_t pacer_verify(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs,
  * equal to the effective argmax and emits the argmax at the first mismatch (or of the bonus
  * row); PACER_SAMPLE accepts y_i while r_i <= p_i[y_i]/q_i[y_i], then samples from
  * norm(max(0, p - q)) at the first rejection or from p_{gamma+1}.  Extends M_B's cache over
- * positions that no pacer_preverify_block covered.  The call waits (polling pinned host words,
- * no stream synchronisation) until n is known for every listed sequence; for those that accepted
- * all gamma drafts it then runs the draft forward on y_gamma (it completes the draft cache and
- * yields the draft logits of the bonus row) and evaluates the bonus row.  The kernels of that
- * second part may still be in flight when the call returns.  Appends
+ * positions that no pacer_preverify_block covered.  The call only enqueues (rows i < gamma: the
+ * accept tests and the token at the first rejection) and returns; it does not wait for the verify
+ * pass.  A sequence that accepted all gamma drafts still needs the draft forward on y_gamma (it
+ * completes the draft cache and yields the draft logits of the bonus row) and the bonus row's
+ * token: that part is enqueued by the call that collects the result (pacer_get_state, or the
+ * sequence's next pacer_begin_step), which is where the host first learns n.  Appends
  * y_1..y_n and the new token to the committed tokens; all three caches then logically hold
  * committed_length-1 positions (rollback = shorter length, nothing is erased).
  * dev_logits: the buffer pacer_verify wrote.  dev_n_accepted[n_seqs], dev_next_token[n_seqs]
- * receive n and the new token; the same values reach the host through pacer_get_state. */
+ * receive n and the new token (-1 until the bonus row has been evaluated); the same values reach
+ * the host through pacer_get_state.  dev_logits, dev_n_accepted and dev_next_token must stay valid
+ * until the result has been collected.  PACER_ESTATE if a listed sequence still has an uncollected
+ * result. */
 int32_t pacer_accept_rollback(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, int32_t mode,
                               const float* beta, uint64_t rng_seed, uint64_t rng_ctr,
                               const float* dev_logits, int32_t* dev_n_accepted,
@@ -237,7 +253,8 @@ int32_t pacer_accept_noalloc(const float* dev_target_logits, const float* dev_dr
                              int32_t* dev_n_accepted, int32_t* dev_next_token, void* hip_stream);
 
 /* Waits for the sequence's pending pacer_accept_rollback, if any (by polling the pinned host
- * words its last kernel writes; it does not synchronise the stream), folds the result into the
+ * words its last kernel writes; it does not synchronise the stream), enqueues and awaits the bonus-row
+ * part for sequences that accepted every draft, folds the result into the
  * host-side state and reports: gamma (drafts of the current/last step), len (committed tokens), t (current
  * threshold), n_accepted / next_token of the last finished step (-1 if none).  Any output
  * pointer may be NULL. */
@@ -260,6 +277,15 @@ int32_t pacer_peek(pacer_ctx* ctx, int32_t seq, int32_t what, void** dev_ptr, ui
  * pointer or sizes outside those bounds. */
 int32_t pacer_launch_plan(int32_t n_out, int32_t n_in, int32_t rows, int32_t operand_parts,
                           int32_t* tiles_per_block, int32_t* k_slices);
+
+/* Number of kernels the context has enqueued since it was created (benchmarks: launches per call). */
+int32_t pacer_launch_count(const pacer_ctx* ctx, int64_t* n_launches);
+
+/* Benchmark support, no context: one kernel that reads dev_src[0..nbytes) once (16-byte loads, 1024 blocks of 8
+ * waves) and folds it into dev_sink (256 bytes of device memory, caller-zeroed or not).  Timed by the caller, it
+ * gives the streaming-read rate a kernel reaches on this GPU when it does nothing but load: the practical ceiling
+ * beside which the weight-streaming GEMMs' rates are reported.  dev_src must be 16-byte aligned. */
+int32_t pacer_stream_probe(const void* dev_src, uint64_t nbytes, void* dev_sink, void* hip_stream);
 
 /* Kernel timing for benchmarks: while enabled, every launch of the target model's GEMM kernels
  * carries a pair of HIP events on the context's stream that receive the kernel's own begin and end

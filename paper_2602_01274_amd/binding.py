@@ -28,6 +28,7 @@ EXPORTS = [
     "pacer_prefill", "pacer_force_commit", "pacer_begin_step", "pacer_draft_step",
     "pacer_preverify_block", "pacer_wait_stop", "pacer_verify", "pacer_accept_rollback", "pacer_get_state",
     "pacer_peek", "pacer_profile_enable", "pacer_profile_read", "pacer_launch_plan", "pacer_accept_noalloc",
+    "pacer_force_stop", "pacer_launch_count", "pacer_stream_probe",
 ]
 
 
@@ -58,7 +59,7 @@ def _load():
         "pacer_create": (i32, [C.POINTER(vp), C.POINTER(ModelCfg), C.POINTER(ModelCfg), C.POINTER(PvCfg), i32, vp]),
         "pacer_destroy": (None, [vp]),
         "pacer_last_error": (C.c_char_p, [vp]),
-        "pacer_pack_weight": (i32, [vp, vp, i32, i32, i32, i32, vp]),
+        "pacer_pack_weight": (i32, [vp, vp, i32, i32, i32, i32, vp, vp]),
         "pacer_bind": (i32, [vp, i32, i32, i32, vp, u64]),
         "pacer_kv_bytes": (u64, [vp, i32]),
         "pacer_bind_kv": (i32, [vp, i32, vp, u64]),
@@ -77,6 +78,9 @@ def _load():
         "pacer_profile_enable": (i32, [vp, i32]),
         "pacer_launch_plan": (i32, [i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]),
         "pacer_profile_read": (i32, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "pacer_stream_probe": (i32, [vp, u64, vp, vp]),
+        "pacer_force_stop": (i32, [vp, i32, i32]),
+        "pacer_launch_count": (i32, [vp, C.POINTER(C.c_int64)]),
         "pacer_accept_noalloc": (i32, [vp, vp, vp, i32, i32, i32, i32, C.c_float, u64, u64, i32, vp, vp, vp]),
     }
     for name, (res, args) in sig.items():
@@ -123,9 +127,10 @@ def pacer_last_error(ctx):
     return _lib.pacer_last_error(ctx).decode()
 
 
-def pacer_pack_weight(dst, src, tensor_id, head_dim, stream):
+def pacer_pack_weight(dst, src, tensor_id, head_dim, dev_not_finite, stream):
     n_out, n_in = src.shape
-    _chk(None, _lib.pacer_pack_weight(_ptr(dst), _ptr(src), n_out, n_in, tensor_id, head_dim, C.c_void_p(stream)))
+    _chk(None, _lib.pacer_pack_weight(_ptr(dst), _ptr(src), n_out, n_in, tensor_id, head_dim, _ptr(dev_not_finite),
+                                      C.c_void_p(stream)))
 
 
 def pacer_bind(ctx, which, tensor_id, layer, t):
@@ -166,6 +171,22 @@ def pacer_draft_step(ctx, seqs, mode, rng_seed, rng_ctr):
 
 def pacer_preverify_block(ctx, seqs, dev_alpha, dev_stop):
     _chk(ctx, _lib.pacer_preverify_block(ctx, _i32s(seqs), len(seqs), _ptr(dev_alpha), _ptr(dev_stop)))
+
+
+def pacer_stream_probe(src, sink, stream):
+    rc = _lib.pacer_stream_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink), C.c_void_p(stream))
+    if rc != OK:
+        raise PacerError(rc, _lib.pacer_last_error(None).decode())
+
+
+def pacer_force_stop(ctx, seq, flag):
+    _chk(ctx, _lib.pacer_force_stop(ctx, seq, flag))
+
+
+def pacer_launch_count(ctx):
+    n = C.c_int64()
+    _chk(ctx, _lib.pacer_launch_count(ctx, C.byref(n)))
+    return n.value
 
 
 def pacer_wait_stop(ctx, seqs):

@@ -502,7 +502,9 @@ __global__ __launch_bounds__(1024) void pick_token_kernel(const float* __restric
 // = 1/(1+exp(z0-z1)); stop = (mean alpha <= t) with the mean summed in index order in f32.
 // rule: 0 mean, 1 any, 2 last.  seq/ticket: the stop flag also goes to pinned host memory as
 // host_stop[seq] = ticket*2 + stop, which the host polls instead of synchronising the stream.
-struct HaltArgs { int n_seqs; int rule; float t[PK_MAXB]; int seq[PK_MAXB]; int ticket[PK_MAXB]; };
+// force: -1 = decide by the rule; 0 / 1 = the flag is forced (test tap: sweeps over stop patterns), the kernel still
+// computes and writes alpha
+struct HaltArgs { int n_seqs; int rule; float t[PK_MAXB]; int seq[PK_MAXB]; int ticket[PK_MAXB]; int force[PK_MAXB]; };
 // the halting test of one block, decided in f32 (al: the block's alpha values in index order)
 __device__ __forceinline__ int halt_decision(const float* al, int b, float t, int rule) {
   if (rule == 1) {
@@ -529,7 +531,7 @@ __global__ void mb_head_kernel(const float* __restrict__ xn, int ldx, const floa
   __syncthreads();
   if (threadIdx.x == 0) {
     for (int j = 0; j < b; ++j) alpha[si * b + j] = al[j];
-    const int st = halt_decision(al, b, ha.t[si], ha.rule);
+    const int st = ha.force[si] >= 0 ? ha.force[si] : halt_decision(al, b, ha.t[si], ha.rule);
     stop[si] = st;
     host_stop[ha.seq[si]] = ha.ticket[si] * 2 + st;
   }
@@ -742,4 +744,26 @@ __global__ void accept_finalize_kernel(const float* __restrict__ part, const int
 
 __global__ void copy_i32_kernel(int* __restrict__ dst, const int* __restrict__ src, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+// ------------------------------------------------------------------ streaming-read probe (benchmarks)
+// Reads n16 16-byte words once, each wave a contiguous 1 KiB per step and eight loads in flight per lane, and
+// folds them into one word per block: what a kernel that only streams from HBM through the L1s reaches on this
+// GPU, the practical ceiling the weight-streaming GEMMs are measured against.
+__global__ __launch_bounds__(512) void stream_probe_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  for (; i < n16; i += stride) acc ^= src[i];
+  uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x ^= __shfl_xor(x, o, 64);
+  if ((threadIdx.x & 63) == 0) atomicXor(sink + blockIdx.x % 64, x);
 }

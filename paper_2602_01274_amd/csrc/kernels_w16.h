@@ -57,7 +57,9 @@ __device__ __forceinline__ void ssq_init_row(u64* ssq, int n_slots, int stride, 
   for (int i = threadIdx.x; i < n_slots * SSQ_SUB; i += blockDim.x) ssq[(size_t)i * stride + r] = (i == 0) ? (u64)(ss * SSQ_SCALE + 0.5f) : 0ull;
 }
 
-__global__ void pack_weight_kind_kernel(uint4* __restrict__ dst, const uint16_t* __restrict__ src, int N, int K, int kind, int param) {
+// bad (may be null): incremented once per weight whose half-float value is not finite (|w| > 65504, inf, NaN)
+__global__ void pack_weight_kind_kernel(uint4* __restrict__ dst, const uint16_t* __restrict__ src, int N, int K, int kind, int param,
+                                        int* __restrict__ bad) {
   const int KT = K >> 5;
   const size_t total = (size_t)(N >> 4) * KT * 64;
   for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
@@ -83,6 +85,12 @@ __global__ void pack_weight_kind_kernel(uint4* __restrict__ dst, const uint16_t*
     const uint16_t* p = src + (size_t)row * K + kt * 32 + (lane >> 4) * 8;
     const u32x4 h = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(p));
     dst[idx] = make_uint4(h[0], h[1], h[2], h[3]);
+    if (bad) {
+      int nb = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) nb += ((h[e] & 0x7c00u) == 0x7c00u) + ((h[e] & 0x7c000000u) == 0x7c000000u);   // exponent all ones
+      if (nb) atomicAdd(bad, nb);
+    }
   }
 }
 
@@ -1247,7 +1255,7 @@ __global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const f
   __syncthreads();
   if (threadIdx.x == 0) {
     for (int jj = 0; jj < b; ++jj) alpha[si * b + jj] = al[jj];
-    const int st = halt_decision(al, b, ha.t[si], ha.rule);
+    const int st = ha.force[si] >= 0 ? ha.force[si] : halt_decision(al, b, ha.t[si], ha.rule);
     stop[si] = st;
     host_stop[ha.seq[si]] = ha.ticket[si] * 2 + st;
   }

@@ -46,6 +46,13 @@ struct Seq {
   int last_n = -1, last_z = -1;
   int pv_ticket = 0;   // number of the last pre-verification call that covered this sequence (the kernel echoes it next to the stop flag)
   int acc_ticket = 0;  // number of the last accept call that covered it
+  int force = -1;      // stop flag forced on the next pre-verification call (test tap): -1 none, 0 go on, 1 stop
+  // the pending accept call, kept until its result is collected: what the bonus-row phase needs if every draft was accepted
+  int acc_mode = 0, acc_slot = 0;
+  float acc_beta = 0.f;
+  uint64_t acc_seed = 0, acc_ctr = 0;
+  const float* acc_logits = nullptr;
+  int *acc_n = nullptr, *acc_z = nullptr;
 };
 
 }  // namespace
@@ -78,6 +85,8 @@ struct pacer_ctx {
   int* host_res = nullptr;
   int* host_res_dev = nullptr;  // its device alias
   int pv_calls = 0, acc_calls = 0;
+  int64_t n_launches = 0;      // kernels enqueued so far
+  bool hip_failed = false;     // a HIP call failed since the hand-over counters were last cleared
   // profiling of the GEMM kernel
   bool prof = false;
   std::vector<hipEvent_t> ev;
@@ -98,10 +107,18 @@ int fail(pacer_ctx* c, int code, const char* fmt, ...) {
   return code;
 }
 
+// every kernel launch of a context goes through these: the context counts its launches (pacer_launch_count)
+#define PACER_LAUNCH(...) do { ++c->n_launches; hipLaunchKernelGGL(__VA_ARGS__); } while (0)
+#define PACER_LAUNCH_EXT(...) do { ++c->n_launches; hipExtLaunchKernelGGL(__VA_ARGS__); } while (0)
+
+// a HIP failure may have left a launch half done: its arrival counters are cleared again at the next step's start
 #define HIPCHK(c, call)                                                                    \
   do {                                                                                     \
     hipError_t e_ = (call);                                                                \
-    if (e_ != hipSuccess) return fail(c, PACER_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    if (e_ != hipSuccess) {                                                                \
+      if (c) (c)->hip_failed = true;                                                       \
+      return fail(c, PACER_EHIP, "%s: %s", #call, hipGetErrorString(e_));                  \
+    }                                                                                      \
   } while (0)
 
 size_t esize(int dtype) { return dtype == PACER_BF16 ? 2 : 4; }
@@ -221,7 +238,7 @@ template <int EPI, int TAG, int HL, int MT, int NT, int WAVES, int U, int X17 = 
 void launch_w16(pacer_ctx* c, GemmArgs ga, int n_tiles) {
   ga.sk_part = c->sk_part;
   ga.sk_cnt = c->sk_cnt;
-  hipExtLaunchKernelGGL((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17, HL, KSB>), dim3((n_tiles + NT - 1) / NT * KSB), dim3(WAVES * 64), 0, c->stream, c->pe0,
+  PACER_LAUNCH_EXT((gemm_w16_kernel<EPI, MT, NT, WAVES, U, TAG, X17, HL, KSB>), dim3((n_tiles + NT - 1) / NT * KSB), dim3(WAVES * 64), 0, c->stream, c->pe0,
                         c->pe1, 0, ga);
 }
 
@@ -265,7 +282,7 @@ void launch_wide_shape(pacer_ctx* c, const GemmArgs& ga, int n_tiles, int row_gr
   } else {
   const int n_groups = (n_tiles + 4 * NTW - 1) / (4 * NTW);
   const dim3 grid((unsigned)((n_groups + 7) / 8 * 8 * row_groups));
-  hipExtLaunchKernelGGL((gemm_wide_kernel<EPI, NTW, MTB, HL, TAG, KS>), grid, dim3(256 * KS), 0, c->stream, c->pe0, c->pe1, 0, ga, n_tiles, n_groups, row_groups);
+  PACER_LAUNCH_EXT((gemm_wide_kernel<EPI, NTW, MTB, HL, TAG, KS>), grid, dim3(256 * KS), 0, c->stream, c->pe0, c->pe1, 0, ga, n_tiles, n_groups, row_groups);
   }
 }
 // Shape of a wide launch: row tiles per block (MTB), output tiles per wave (NTW), K slices (KS).
@@ -311,7 +328,7 @@ constexpr int kWide8KC = 4;
 template <int EPI, int TAG, int HL, int NTW, int MTB, int KSB>
 void launch_wide8_shape(pacer_ctx* c, const GemmArgs& ga, int n_tiles, int n_groups) {
   const size_t lds = (size_t)2 * kWide8KC * MTB * HL * 1024;
-  hipExtLaunchKernelGGL((gemm_wide8_kernel<EPI, NTW, MTB, HL, TAG, kWide8KC, KSB>), dim3((unsigned)((n_groups + 7) / 8 * 8 * 2 * KSB)), dim3(512), lds,
+  PACER_LAUNCH_EXT((gemm_wide8_kernel<EPI, NTW, MTB, HL, TAG, kWide8KC, KSB>), dim3((unsigned)((n_groups + 7) / 8 * 8 * 2 * KSB)), dim3(512), lds,
                         c->stream, c->pe0, c->pe1, 0, ga, n_tiles, n_groups, 2);
 }
 template <int EPI, int TAG, int HL>
@@ -492,7 +509,7 @@ void gemm_w16(pacer_ctx* c, int tag, bool hilo, const GemmArgs& ga, int n_tiles,
 }
 
 void rope_table(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
-  hipLaunchKernelGGL(rope_table_kernel, dim3(R), dim3(m.cfg.head_dim / 2), 0, c->stream, sr, m.cfg.head_dim, m.cfg.rope_theta, c->rope);
+  PACER_LAUNCH(rope_table_kernel, dim3(R), dim3(m.cfg.head_dim / 2), 0, c->stream, sr, m.cfg.head_dim, m.cfg.rope_theta, c->rope);
 }
 
 // Decoder stack of a bf16 model on R rows.  On entry x holds the rows, xpA their f16 operand x*g of
@@ -562,7 +579,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       const int mrows = rt_split ? 16 : max_rows;
       const dim3 grid(rt_split ? 2 * S : S, H, sr.n_seqs);
       // LDS for the wave states: 8 waves x live rows x (hd + 4) floats
-#define PACER_ATT(HD_, MT_, QL_) hipLaunchKernelGGL((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), (size_t)8 * std::min(mrows, MT_ * 16) * (HD_ + 4) * 4, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total, rt_split ? 1 : 0, c->att_cnt)
+#define PACER_ATT(HD_, MT_, QL_) PACER_LAUNCH((attn_mfma_kernel<HD_, MT_, QL_>), grid, dim3(512), (size_t)8 * std::min(mrows, MT_ * 16) * (HD_ + 4) * 4, c->stream, c->qp, kv, l, L, g.max_seq, d, sr, kps, S, H, c->part, c->xpB, mt_total, rt_split ? 1 : 0, c->att_cnt)
       if (tag == 0) {
         if (hd == 128) { if (mrows > 16) PACER_ATT(128, 2, 2); else PACER_ATT(128, 1, 2); }
         else           { if (mrows > 16) PACER_ATT(64, 2, 2); else PACER_ATT(64, 1, 2); }
@@ -605,7 +622,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
 }
 
 void embed_w16(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
-  hipLaunchKernelGGL(embed_w16_kernel, dim3(R), dim3(256), 0, c->stream, static_cast<const uint16_t*>(m.embed), c->tokens, c->draft_tok, sr,
+  PACER_LAUNCH(embed_w16_kernel, dim3(R), dim3(256), 0, c->stream, static_cast<const uint16_t*>(m.embed), c->tokens, c->draft_tok, sr,
                      c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax, m.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq,
                      2 * m.cfg.n_layers + 1, c->rcap, c->rope, m.cfg.head_dim, m.cfg.rope_theta);
 }
@@ -636,12 +653,12 @@ void lm_head_w16(pacer_ctx* c, const Model& m, int tag, int R, float* out, const
 
 void gemm_f32(pacer_ctx* c, const void* W, const float* act, int lda, float* out, int ldo, int R, int N, int K, int acc,
               const SeqRows& sr, int rowmap) {
-  hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, static_cast<const float*>(W), act, lda, out, ldo, R, N,
+  PACER_LAUNCH(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, static_cast<const float*>(W), act, lda, out, ldo, R, N,
                      K, acc, sr, rowmap, c->G1);
 }
 
 void rmsnorm_f32(pacer_ctx* c, const Model& m, const float* g, int R, float* hid_out, const SeqRows& sr) {
-  hipLaunchKernelGGL(rmsnorm_pack_kernel, dim3(R), dim3(256), 0, c->stream, c->x, c->dmax, g, m.cfg.rms_eps, R, m.cfg.d_model, c->xn,
+  PACER_LAUNCH(rmsnorm_pack_kernel, dim3(R), dim3(256), 0, c->stream, c->x, c->dmax, g, m.cfg.rms_eps, R, m.cfg.d_model, c->xn,
                      c->kmax, hid_out, c->G1, sr);
 }
 
@@ -653,7 +670,7 @@ void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool
   for (int l = 0; l < g.n_layers; ++l) {
     rmsnorm_f32(c, m, m.attn_norm[l], R, nullptr, sr);
     gemm_f32(c, m.wqkv[l], c->xn, c->kmax, c->qkv, 3 * c->dmax, R, 3 * d, d, 0, none, ROWMAP_ID);
-    hipLaunchKernelGGL((rope_append_kernel<float>), dim3(R, H), dim3(hd / 2), 0, c->stream, c->qkv, 3 * c->dmax, c->rope, sr, d, hd,
+    PACER_LAUNCH((rope_append_kernel<float>), dim3(R, H), dim3(hd / 2), 0, c->stream, c->qkv, 3 * c->dmax, c->rope, sr, d, hd,
                        static_cast<float*>(m.kv), l, g.n_layers, g.max_seq, kv_only ? 1 : 0);
     if (kv_only) continue;
     int max_keys = 0;
@@ -662,13 +679,13 @@ void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool
     int chunks = std::min(std::min(n_tiles, kMaxChunks), std::max(1, 1024 / (H * sr.n_seqs)));
     const int tpc = (n_tiles + chunks - 1) / chunks;
     chunks = (n_tiles + tpc - 1) / tpc;
-    hipLaunchKernelGGL((attn_partial_kernel<float, 64>), dim3(chunks, H, sr.n_seqs), dim3(256), 0, c->stream, c->qkv, 3 * c->dmax,
+    PACER_LAUNCH((attn_partial_kernel<float, 64>), dim3(chunks, H, sr.n_seqs), dim3(256), 0, c->stream, c->qkv, 3 * c->dmax,
                        static_cast<const float*>(m.kv), l, g.n_layers, g.max_seq, d, sr, tpc, chunks, H, c->part);
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(R, H), dim3(hd), 0, c->stream, c->part, chunks, H, hd, c->ao, c->dmax);
+    PACER_LAUNCH(attn_combine_kernel, dim3(R, H), dim3(hd), 0, c->stream, c->part, chunks, H, hd, c->ao, c->dmax);
     gemm_f32(c, m.wo[l], c->ao, c->dmax, c->x, c->dmax, R, d, d, 1, none, ROWMAP_ID);
     rmsnorm_f32(c, m, m.ffn_norm[l], R, nullptr, sr);
     gemm_f32(c, m.wgu[l], c->xn, c->kmax, c->gu, 2 * c->fmax, R, 2 * F, d, 0, none, ROWMAP_ID);
-    hipLaunchKernelGGL(swiglu_pack_kernel, dim3((F / 8 + 255) / 256, R), dim3(256), 0, c->stream, c->gu, 2 * c->fmax, R, F, c->xn, c->kmax);
+    PACER_LAUNCH(swiglu_pack_kernel, dim3((F / 8 + 255) / 256, R), dim3(256), 0, c->stream, c->gu, 2 * c->fmax, R, F, c->xn, c->kmax);
     gemm_f32(c, m.wd[l], c->xn, c->kmax, c->x, c->dmax, R, d, F, 1, none, ROWMAP_ID);
   }
   if (!kv_only) rmsnorm_f32(c, m, m.final_norm, R, hid_out, sr);
@@ -682,7 +699,7 @@ void forward_lm(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows& sr)
     embed_w16(c, m, R, sr);
     run_layers_w16(c, m, tag, R, sr, false);
   } else {
-    hipLaunchKernelGGL((embed_rows_kernel<float>), dim3(R), dim3(256), 0, c->stream, static_cast<const float*>(m.embed), c->tokens,
+    PACER_LAUNCH((embed_rows_kernel<float>), dim3(R), dim3(256), 0, c->stream, static_cast<const float*>(m.embed), c->tokens,
                        c->draft_tok, sr, c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax);
     run_layers_f32(c, m, R, sr, false, nullptr);
   }
@@ -697,11 +714,11 @@ void lm_head(pacer_ctx* c, const Model& m, int tag, int R, float* out, const Seq
 void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr, const float* src, int lds, bool kv_only) {
   const Model& mb = c->m[PACER_PREVERIFY];
   if (is_w16(mb)) {
-    hipLaunchKernelGGL(mb_input_w16_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax,
+    PACER_LAUNCH(mb_input_w16_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax,
                        mb.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq, 3, c->rcap, c->rope, mb.cfg.head_dim, mb.cfg.rope_theta);
     run_layers_w16(c, mb, 1, R, sr, kv_only);
   } else {
-    hipLaunchKernelGGL(mb_input_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax);
+    PACER_LAUNCH(mb_input_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax);
     run_layers_f32(c, mb, R, sr, kv_only, nullptr);
   }
 }
@@ -710,10 +727,10 @@ void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr
 void preverify_head(pacer_ctx* c, int n, int b, const HaltArgs& ha, float* dev_alpha, int* dev_stop) {
   const Model& mb = c->m[PACER_PREVERIFY];
   if (is_w16(mb))
-    hipLaunchKernelGGL(mb_head_w16_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, mb.final_norm, slot(c, 2), c->rcap, 1.0f / mb.cfg.d_model,
+    PACER_LAUNCH(mb_head_w16_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, mb.final_norm, slot(c, 2), c->rcap, 1.0f / mb.cfg.d_model,
                        mb.cfg.rms_eps, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop, c->host_res_dev + 3 * PACER_MAX_BATCH);
   else
-    hipLaunchKernelGGL(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop,
+    PACER_LAUNCH(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop,
                        c->host_res_dev + 3 * PACER_MAX_BATCH);
 }
 
@@ -737,15 +754,15 @@ void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int m
     forward_lm(c, md, 1, n, sr);
     const PickCfg pick{1, mode, seed, (uint32_t)ctr};
     lm_head_w16(c, md, 1, n, c->ring, sr, ROWMAP_RING, &pick);
-    hipLaunchKernelGGL(draft_tail_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
+    PACER_LAUNCH(draft_tail_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
                        c->rcap, 1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->pick_val, c->pick_idx, md.cfg.vocab / 16,
                        c->draft_tok, pa, c->G1);
   } else {
-    hipLaunchKernelGGL((embed_rows_kernel<float>), dim3(n), dim3(256), 0, c->stream, static_cast<const float*>(md.embed), c->tokens,
+    PACER_LAUNCH((embed_rows_kernel<float>), dim3(n), dim3(256), 0, c->stream, static_cast<const float*>(md.embed), c->tokens,
                        c->draft_tok, sr, c->max_seq, c->G1, md.cfg.d_model, c->x, c->dmax);
     run_layers_f32(c, md, n, sr, false, c->hidden);
     lm_head(c, md, 1, n, c->ring, sr, ROWMAP_RING);
-    hipLaunchKernelGGL(pick_token_kernel, dim3(n), dim3(1024), 0, c->stream, c->ring, c->draft_tok, pa, c->G1, md.cfg.vocab, mode, seed,
+    PACER_LAUNCH(pick_token_kernel, dim3(n), dim3(1024), 0, c->stream, c->ring, c->draft_tok, pa, c->G1, md.cfg.vocab, mode, seed,
                        (uint32_t)ctr);
   }
 }
@@ -764,14 +781,90 @@ int wait_ticket(pacer_ctx* c, const int* p, int ticket, int shift) {
   return fail(c, PACER_EHIP, "a kernel's result did not reach host memory (ticket %d, found %d)", ticket, *v >> shift);
 }
 
+// M_B prefix rows (PosEmb row 0, K/V only) for positions no pre-verification call covered: the drafts beyond
+// the last pre-verified block (bonus = false) or the position of the extra draft forward (bonus = true)
+void mb_prefix_rows(pacer_ctx* c, const int* ids, int m, bool bonus) {
+  SeqRows sr{};
+  MbRows mr{};
+  int R = 0, k = 0;
+  for (int i = 0; i < m; ++i) {
+    const Seq& q = c->seq[ids[i]];
+    const int end = bonus ? q.verified + 1 : q.verified;       // draft positions [first, end)
+    const int first = bonus ? q.verified : std::min(q.mb_done, q.verified);
+    const int cnt = end - first;
+    if (cnt <= 0) continue;
+    sr.seq[k] = ids[i];
+    sr.row_off[k] = R;
+    sr.pos0[k] = q.len - 1 + first;
+    sr.len[k] = q.len;
+    mr.src_row0[k] = ids[i] * c->G1 + first;
+    mr.e0[k] = -1;
+    R += cnt;
+    ++k;
+  }
+  sr.n_seqs = k;
+  sr.row_off[k] = R;
+  if (R > 0) run_preverify_rows(c, R, sr, mr, c->hidden, c->m[PACER_PREVERIFY].cfg.d_model, true);
+}
+
+// the acceptance kernels over `rows` rows per sequence (phase 0: rows i < gamma; phase 1: the bonus row)
+void accept_launch(pacer_ctx* c, const AccArgs& aa, int rows, int phase, int mode, uint64_t seed, uint64_t ctr, const float* dev_logits,
+                   int* dev_n, int* dev_z) {
+  const int V = c->m[PACER_TARGET].cfg.vocab;
+  if (rows > 0) {
+    const dim3 grid(rows, aa.n_seqs, ACC_CHUNKS);
+    if (mode != PACER_GREEDY)
+      PACER_LAUNCH(accept_stats_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, aa, c->G1, V, phase, c->acc_part,
+                   (const int*)nullptr);
+    PACER_LAUNCH(accept_rows_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode, seed,
+                 (uint32_t)ctr, phase, c->acc_part, c->rej, (const int*)nullptr);
+  }
+  PACER_LAUNCH(accept_finalize_kernel, dim3(aa.n_seqs), dim3(64), 0, c->stream, c->acc_part, c->rej, c->draft_tok, aa, c->G1, mode,
+               phase, c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev, c->host_res_dev + 2 * PACER_MAX_BATCH, ++c->acc_calls, 0);
+  for (int i = 0; i < aa.n_seqs; ++i) c->seq[aa.seq[i]].acc_ticket = c->acc_calls;
+}
+
+// Collects the results of every pending accept call.  A sequence whose phase 0 reports (gamma, -1) accepted every
+// draft: its step still needs the draft forward on y_gamma (it completes the draft cache and yields the draft
+// logits of the bonus row), M_B's prefix row for that position and the bonus row's token.  That part is
+// enqueued here, once phase 0's result is known, for the sequences that need it, call by call.
 int fold(pacer_ctx* c, int s) {
-  Seq& q = c->seq[s];
-  if (!q.pending) return PACER_OK;
-  if (int rc = wait_ticket(c, c->host_res + 2 * PACER_MAX_BATCH + s, q.acc_ticket, 0)) return rc;
+  if (!c->seq[s].pending) return PACER_OK;
+  bool done[PACER_MAX_BATCH] = {false};
+  for (int i = 0; i < c->max_batch; ++i) {
+    Seq& o = c->seq[i];
+    if (!o.pending || done[i]) continue;
+    // the sequences of o's accept call carry the same ticket and were written by the same launch
+    AccArgs ab{};
+    int32_t sub[PACER_MAX_BATCH];
+    int jb[PACER_MAX_BATCH];
+    int m = 0;
+    const int ticket = o.acc_ticket;
+    for (int k = i; k < c->max_batch; ++k) {
+      Seq& q = c->seq[k];
+      if (!q.pending || q.acc_ticket != ticket) continue;
+      done[k] = true;
+      if (int rc = wait_ticket(c, c->host_res + 2 * PACER_MAX_BATCH + k, ticket, 0)) return rc;
+      if (c->host_res[2 * k + 1] >= 0) continue;
+      sub[m] = ab.seq[m] = ab.qslot[m] = k;
+      jb[m] = q.verified;
+      ab.slot[m] = q.acc_slot;
+      ab.gamma[m] = q.verified;
+      ab.len[m] = q.len;
+      ab.beta[m] = q.acc_beta;
+      ++m;
+    }
+    if (m > 0) {
+      ab.n_seqs = m;
+      draft_forward(c, sub, m, jb, PACER_GREEDY, 0, 0);
+      mb_prefix_rows(c, sub, m, true);
+      accept_launch(c, ab, 1, 1, o.acc_mode, o.acc_seed, o.acc_ctr, o.acc_logits, o.acc_n, o.acc_z);
+      HIPCHK(c, hipGetLastError());
+    }
+  }
   for (int i = 0; i < c->max_batch; ++i) {
     Seq& o = c->seq[i];
     if (!o.pending) continue;
-    // sequences of the same accept call carry the same ticket and were written by the same launch
     if (int rc = wait_ticket(c, c->host_res + 2 * PACER_MAX_BATCH + i, o.acc_ticket, 0)) return rc;
     o.last_n = c->host_res[2 * i];
     o.last_z = c->host_res[2 * i + 1];
@@ -891,7 +984,7 @@ void pacer_destroy(pacer_ctx* c) {
 const char* pacer_last_error(const pacer_ctx* c) { return c ? c->err : (g_err[0] ? g_err : "null context"); }
 
 int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int32_t n_in, int32_t tensor_id, int32_t head_dim,
-                          void* hip_stream) {
+                          int32_t* dev_not_finite, void* hip_stream) {
   if (!dev_dst || !dev_src || dev_dst == dev_src || n_out < 16 || n_in < 32 || n_out % 16 || n_in % 32) return PACER_EINVAL;
   int kind = PACK_PLAIN;
   if (tensor_id == PACER_T_WQKV) {
@@ -904,7 +997,7 @@ int32_t pacer_pack_weight(void* dev_dst, const void* dev_src, int32_t n_out, int
     return PACER_EINVAL;
   }
   hipLaunchKernelGGL(pack_weight_kind_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(hip_stream), static_cast<uint4*>(dev_dst),
-                     static_cast<const uint16_t*>(dev_src), n_out, n_in, kind, head_dim);
+                     static_cast<const uint16_t*>(dev_src), n_out, n_in, kind, head_dim, dev_not_finite);
   return hipGetLastError() == hipSuccess ? PACER_OK : PACER_EHIP;
 }
 
@@ -1019,7 +1112,7 @@ int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_
   Seq& q = c->seq[s];
   q = Seq();
   q.len = n;
-  hipLaunchKernelGGL(copy_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->tokens + (size_t)s * c->max_seq, dev_tokens, n);
+  PACER_LAUNCH(copy_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->tokens + (size_t)s * c->max_seq, dev_tokens, n);
   // up to 16 slots of 32 consecutive positions per pass: one trip through the weights per 512 prompt tokens
   for (int p0 = 0; p0 < n - 1; p0 += kPrefillRows) {
     const int R = std::min(kPrefillRows, n - 1 - p0);
@@ -1040,7 +1133,7 @@ int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_
     forward_lm(c, md, 1, R, sr);
     // the draft's hidden states (final-norm output) feed M_B's prefix rows; staged in ao
     if (is_w16(md))
-      hipLaunchKernelGGL(hidden_rows_kernel, dim3(R), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
+      PACER_LAUNCH(hidden_rows_kernel, dim3(R), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
                          c->rcap, 1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->ao, c->dmax);
     else
       (void)hipMemcpy2DAsync(c->ao, (size_t)c->dmax * 4, c->xn, (size_t)c->kmax * 4, (size_t)md.cfg.d_model * 4, R, hipMemcpyDeviceToDevice,
@@ -1071,6 +1164,12 @@ int32_t pacer_begin_step(pacer_ctx* c, int32_t s) {
   if (!c) return PACER_EINVAL;
   if (int rc = ready(c)) return rc;
   if (s < 0 || s >= c->max_batch) return fail(c, PACER_EINVAL, "begin_step: sequence id %d out of range", s);
+  if (c->hip_failed) {
+    // the cross-block hand-overs rely on their arrival counters being zero between launches
+    c->hip_failed = false;
+    HIPCHK(c, hipMemsetAsync(c->sk_cnt, 0, sizeof(unsigned) * kSplitGroups, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->att_cnt, 0, sizeof(unsigned) * PK_MAXB * c->hmax * 2, c->stream));
+  }
   if (int rc = fold(c, s)) return rc;
   Seq& q = c->seq[s];
   if (q.len < 1) return fail(c, PACER_ESTATE, "begin_step: sequence %d has no committed tokens (prefill first)", s);
@@ -1127,6 +1226,8 @@ int32_t pacer_preverify_block(pacer_ctx* c, const int32_t* seqs, int32_t n, floa
     ha.t[i] = q.t;
     ha.seq[i] = seqs[i];
     ha.ticket[i] = q.pv_ticket = c->pv_calls + 1;   // per context, never reused: a re-prefilled sequence cannot match a stale word
+    ha.force[i] = q.force;
+    q.force = -1;
   }
   ++c->pv_calls;
   sr.row_off[n] = n * b;
@@ -1139,6 +1240,14 @@ int32_t pacer_preverify_block(pacer_ctx* c, const int32_t* seqs, int32_t n, floa
     q.t = q.t * c->pv.rho;
   }
   HIPCHK(c, hipGetLastError());
+  return PACER_OK;
+}
+
+int32_t pacer_force_stop(pacer_ctx* c, int32_t s, int32_t flag) {
+  if (!c) return PACER_EINVAL;
+  if (s < 0 || s >= c->max_batch) return fail(c, PACER_EINVAL, "force_stop: sequence id %d out of range", s);
+  if (flag < -1 || flag > 1) return fail(c, PACER_EINVAL, "force_stop: flag must be -1, 0 or 1");
+  c->seq[s].force = flag;
   return PACER_OK;
 }
 
@@ -1199,49 +1308,13 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
   for (int i = 0; i < n; ++i)
     if (!c->seq[seqs[i]].in_step || c->seq[seqs[i]].verified < 0)
       return fail(c, PACER_ESTATE, "accept_rollback: sequence %d has not been verified", seqs[i]);
-  // Phase 0 takes rows i < gamma: M_B prefix rows for the drafts no pre-verification call covered, the accept
-  // tests and the token at the first rejection.  The draft forward on y_gamma (it completes the draft cache
-  // and yields the draft logits of the bonus row) is needed only by a sequence that accepted every draft;
-  // those sequences go through phase 1 once the host has seen phase 0's result.
-  const int V = c->m[PACER_TARGET].cfg.vocab;
-  auto mb_prefix = [&](const int* ids, int m, bool bonus) {
-    SeqRows sr{};
-    MbRows mr{};
-    int R = 0, k = 0;
-    for (int i = 0; i < m; ++i) {
-      const Seq& q = c->seq[ids[i]];
-      const int end = bonus ? q.verified + 1 : q.verified;       // draft positions [first, end)
-      const int first = bonus ? q.verified : std::min(q.mb_done, q.verified);
-      const int cnt = end - first;
-      if (cnt <= 0) continue;
-      sr.seq[k] = ids[i];
-      sr.row_off[k] = R;
-      sr.pos0[k] = q.len - 1 + first;
-      sr.len[k] = q.len;
-      mr.src_row0[k] = ids[i] * c->G1 + first;
-      mr.e0[k] = -1;
-      R += cnt;
-      ++k;
-    }
-    sr.n_seqs = k;
-    sr.row_off[k] = R;
-    if (R > 0) run_preverify_rows(c, R, sr, mr, c->hidden, c->m[PACER_PREVERIFY].cfg.d_model, true);
-  };
-  auto accept_rows = [&](const AccArgs& aa, int rows, int phase) {
-    if (rows > 0) {
-      const dim3 grid(rows, aa.n_seqs, ACC_CHUNKS);
-      if (mode != PACER_GREEDY)
-        hipLaunchKernelGGL(accept_stats_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, aa, c->G1, V, phase, c->acc_part,
-                           (const int*)nullptr);
-      hipLaunchKernelGGL(accept_rows_kernel, grid, dim3(256), 0, c->stream, dev_logits, c->ring, c->draft_tok, aa, c->G1, V, mode, seed,
-                         (uint32_t)ctr, phase, c->acc_part, c->rej, (const int*)nullptr);
-    }
-    hipLaunchKernelGGL(accept_finalize_kernel, dim3(aa.n_seqs), dim3(64), 0, c->stream, c->acc_part, c->rej, c->draft_tok, aa, c->G1,
-                       mode, phase, c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev, c->host_res_dev + 2 * PACER_MAX_BATCH,
-                       ++c->acc_calls, 0);
-    for (int i = 0; i < aa.n_seqs; ++i) c->seq[aa.seq[i]].acc_ticket = c->acc_calls;
-  };
-  mb_prefix(seqs, n, false);
+  // Rows i < gamma only: M_B prefix rows for the drafts no pre-verification call covered, the accept tests and
+  // the token at the first rejection.  The bonus row (needed only by a sequence that accepted every draft, and
+  // costing one more draft forward) is enqueued by whichever call collects the result (see fold), so this call
+  // returns without waiting for the verify pass.
+  for (int i = 0; i < n; ++i)
+    if (c->seq[seqs[i]].pending) return fail(c, PACER_ESTATE, "accept_rollback: sequence %d has an uncollected result", seqs[i]);
+  mb_prefix_rows(c, seqs, n, false);
   AccArgs aa{};
   aa.n_seqs = n;
   int gmax = 0;
@@ -1254,35 +1327,13 @@ int32_t pacer_accept_rollback(pacer_ctx* c, const int32_t* seqs, int32_t n, int3
     aa.beta[i] = beta[i];
     gmax = std::max(gmax, q.verified);
   }
-  accept_rows(aa, gmax, 0);
-  HIPCHK(c, hipGetLastError());
-  // the sequences whose drafts were all accepted: host_res holds (gamma, -1) for them
-  AccArgs ab{};
-  int32_t sub[PACER_MAX_BATCH];
-  int jb[PACER_MAX_BATCH];
-  int m = 0;
-  for (int i = 0; i < n; ++i) {
-    const Seq& q = c->seq[seqs[i]];
-    if (int rc = wait_ticket(c, c->host_res + 2 * PACER_MAX_BATCH + seqs[i], q.acc_ticket, 0)) return rc;
-    if (c->host_res[2 * seqs[i] + 1] >= 0) continue;
-    sub[m] = ab.seq[m] = ab.qslot[m] = seqs[i];
-    jb[m] = q.verified;
-    ab.slot[m] = i;
-    ab.gamma[m] = q.verified;
-    ab.len[m] = q.len;
-    ab.beta[m] = beta[i];
-    ++m;
-  }
-  if (m > 0) {
-    ab.n_seqs = m;
-    draft_forward(c, sub, m, jb, PACER_GREEDY, 0, 0);
-    mb_prefix(sub, m, true);
-    accept_rows(ab, 1, 1);
-  }
+  accept_launch(c, aa, gmax, 0, mode, seed, ctr, dev_logits, dev_n, dev_z);
   for (int i = 0; i < n; ++i) {
     Seq& q = c->seq[seqs[i]];
     q.pending = true;
     q.in_step = false;
+    q.acc_mode = mode; q.acc_slot = i; q.acc_beta = beta[i]; q.acc_seed = seed; q.acc_ctr = ctr;
+    q.acc_logits = dev_logits; q.acc_n = dev_n; q.acc_z = dev_z;
   }
   HIPCHK(c, hipGetLastError());
   return PACER_OK;
@@ -1369,6 +1420,21 @@ int32_t pacer_launch_plan(int32_t n_out, int32_t n_in, int32_t rows, int32_t ope
   const SplitShape sp = n_in / 32 >= 64 ? pick_split_shape(n_out / 16, n_in / 32, rows, operand_parts) : SplitShape{1, 1};
   *tiles_per_block = sp.nt;
   *k_slices = sp.ksb;
+  return PACER_OK;
+}
+
+int32_t pacer_launch_count(const pacer_ctx* c, int64_t* n_launches) {
+  if (!c || !n_launches) return PACER_EINVAL;
+  *n_launches = c->n_launches;
+  return PACER_OK;
+}
+
+int32_t pacer_stream_probe(const void* dev_src, uint64_t nbytes, void* dev_sink, void* hip_stream) {
+  if (!dev_src || !dev_sink || nbytes < 16 || reinterpret_cast<uintptr_t>(dev_src) % 16) return fail_noctx(PACER_EINVAL, "stream_probe: bad arguments");
+  hipLaunchKernelGGL(stream_probe_kernel, dim3(256 * 4), dim3(512), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const u32x4*>(dev_src), (size_t)(nbytes / 16), static_cast<uint32_t*>(dev_sink));
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_noctx(PACER_EHIP, "stream_probe: %s", hipGetErrorString(e));
   return PACER_OK;
 }
 

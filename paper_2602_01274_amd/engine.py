@@ -29,6 +29,7 @@ class Session:
         self.max_seq, self.max_batch = max_seq, max_batch
         self.stream = torch.cuda.current_stream().cuda_stream
         self.keep = []                      # tensors the library borrows
+        self.not_finite = torch.zeros(1, dtype=torch.int32, device="cuda")   # weights that do not fit a half float
         cfg_t = B.model_cfg(w["target"] | {"n_layers": len(target["layers"])}, max_seq, self.dtype)
         cfg_d = B.model_cfg(w["draft"], max_seq, self.dtype)
         pv = B.PvCfg(self.block, self.gamma_max, t0 if t0 is not None else w["t0"],
@@ -42,6 +43,9 @@ class Session:
         self._bind_f32(B.PREVERIFY, B.T_FINAL_NORM, 0, preverify["final_norm"])
         self._bind_f32(B.PREVERIFY, B.T_POSEMB, 0, preverify["posemb"])
         self._bind_f32(B.PREVERIFY, B.T_CLS, 0, preverify["cls"])
+        bad = int(self.not_finite.item())
+        if bad:
+            raise B.PacerError(B.EINVAL, f"{bad} weights are not finite as half floats (|w| > 65504, inf or NaN)")
         for which in (B.TARGET, B.DRAFT, B.PREVERIFY):
             kv = torch.empty(B.pacer_kv_bytes(self.ctx, which), dtype=torch.uint8, device="cuda")
             if kv_fill is not None:
@@ -60,6 +64,7 @@ class Session:
         self.step_idx = [0] * max_batch
         self.counts = dict(draft=0, target=0, preverify=0)
         self.timers = None                  # dict name -> [(start_event, stop_event)] when timing calls
+        self.launches = {}                  # dict name -> [kernels enqueued by the call] while timing calls
         torch.cuda.synchronize()
 
     # ---- weight upload -------------------------------------------------------------------
@@ -68,7 +73,7 @@ class Session:
         if self.dtype == "bf16":
             src = torch.cat([_dev(p, torch.bfloat16) for p in parts], dim=0).contiguous()
             dst = torch.empty_like(src)
-            B.pacer_pack_weight(dst, src, tid, head_dim, self.stream)
+            B.pacer_pack_weight(dst, src, tid, head_dim, self.not_finite, self.stream)
             torch.cuda.synchronize()
             del src
             return dst
@@ -133,15 +138,22 @@ class Session:
         if self.timers is None:
             return fn(*a)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n0 = B.pacer_launch_count(self.ctx)
         e0.record()
-        fn(*a)
+        out = fn(*a)
         e1.record()
         self.timers.setdefault(name, []).append((e0, e1))
+        self.launches.setdefault(name, []).append(B.pacer_launch_count(self.ctx) - n0)
+        return out
 
     def read_timers(self):
         torch.cuda.synchronize()
         out = {k: [a.elapsed_time(b) for a, b in v] for k, v in (self.timers or {}).items()}
         self.timers = {} if self.timers is not None else None
+        return out
+
+    def read_launches(self):
+        out, self.launches = self.launches, {}
         return out
 
     # ---- decoding --------------------------------------------------------------------------
@@ -172,13 +184,23 @@ class Session:
                     self._call("draft_step", B.pacer_draft_step, ctx, seqs, mode, seed, ctr)
                 gamma += self.block
                 self.counts["draft"] += self.block
+                forced = None
+                if force_stop is not None:
+                    # a pattern that does not look at alpha is forced inside the library (the kernel writes the
+                    # forced flag); one that does is applied here, after the read-back
+                    try:
+                        forced = force_stop(rnd, None)
+                    except TypeError:
+                        forced = None
+                    if forced is not None:
+                        B.pacer_force_stop(ctx, seq, 1 if forced else 0)
                 self._call("preverify_block", B.pacer_preverify_block, ctx, seqs, self.alpha, self.stop)
                 self.counts["preverify"] += 1
                 stop = bool(B.pacer_wait_stop(ctx, seqs)[0])       # the only read-back of the drafting loop
                 if record:
                     rec["alpha"] += self.alpha[0].tolist()
                     rec["stops"].append(stop)
-                if force_stop is not None:
+                if force_stop is not None and forced is None:
                     stop = bool(force_stop(rnd, self.alpha[0].tolist()))
                 rnd += 1
                 if stop or gamma + self.block > self.gamma_max:
@@ -187,7 +209,7 @@ class Session:
         self.counts["target"] += 1
         self._call("accept_rollback", B.pacer_accept_rollback, ctx, seqs, mode, [beta], seed, ctr, self.logits,
                    self.n_acc, self.next_tok)
-        st = B.pacer_get_state(ctx, seq)
+        st = self._call("collect_result", B.pacer_get_state, ctx, seq)   # the bonus-row part runs here when every draft was accepted
         self.step_idx[seq] += 1
         out = dict(gamma=gamma, n=st["n_accepted"], z=st["next_token"], len=st["len"])
         if record:

@@ -150,3 +150,16 @@ def test_accept_noalloc_validates_on_the_host(B):
         assert e.value.code == code, over
         if code == B.EOVERFLOW:
             assert "PACER_NOALLOC_MAX_GAMMA = 31" in str(e.value)
+
+
+def test_force_stop_and_launch_count_validate_arguments(B):
+    t, d = _cfgs(B)
+    ctx = B.pacer_create(t, d, B.PvCfg(2, 8, 0.5, 1.05, 0), 2, 0)
+    B.pacer_force_stop(ctx, 1, 1)
+    B.pacer_force_stop(ctx, 1, -1)
+    for seq, flag in ((2, 1), (-1, 0), (0, 2), (0, -2)):
+        with pytest.raises(B.PacerError) as e:
+            B.pacer_force_stop(ctx, seq, flag)
+        assert e.value.code == B.EINVAL
+    assert B.pacer_launch_count(ctx) == 0
+    B.pacer_destroy(ctx)

@@ -456,6 +456,78 @@ def test_wait_stop_and_get_state_match_the_device_buffers():
     s.close()
 
 
+def test_force_stop_overrides_the_device_flag_once():
+    """pacer_force_stop: the next pre-verification call of that sequence writes the forced flag (to the device buffer
+    and to the host-polled word) instead of its own decision, alpha is still computed, and the force is used up:
+    the call after it decides by the rule again (mean alpha <= t in f32, recomputed here from the kernel's alpha)."""
+    from paper_2602_01274_amd import binding as B
+    w = synth.workload("tiny")
+    tgt, drf, mb = synth.make_pair(w, seed=0)
+    s = _session(w, tgt, drf, mb, 256, max_batch=3)
+    seqs = [0, 1, 2]
+    for i in seqs:
+        s.prefill(synth.make_prompt(1024, 12 + 5 * i, 80 + i).tolist(), seq=i)
+        B.pacer_begin_step(s.ctx, i)
+
+    def natural(blk):
+        t = np.float32(w["t0"])
+        for _ in range(blk):
+            t = np.float32(t * np.float32(w["rho"]))
+        out = []
+        for a in s.alpha[:3].tolist():
+            acc = np.float32(0.0)
+            for v in a:
+                acc = np.float32(acc + np.float32(v))
+            out.append(int(np.float32(acc / np.float32(len(a))) <= t))
+        return out
+
+    for blk, forces in enumerate(([1, 0, -1], [-1, -1, -1], [0, 1, 1])):
+        for _ in range(w["block"]):
+            B.pacer_draft_step(s.ctx, seqs, B.GREEDY, 0, 0)
+        for i, f in zip(seqs, forces):
+            if f >= 0:
+                B.pacer_force_stop(s.ctx, i, f)
+        B.pacer_preverify_block(s.ctx, seqs, s.alpha, s.stop)
+        flags = B.pacer_wait_stop(s.ctx, seqs)
+        assert flags == s.stop[:3].tolist()
+        nat = natural(blk)
+        assert flags == [f if f >= 0 else n for f, n in zip(forces, nat)], (blk, flags, forces, nat)
+        assert all(0.0 < v < 1.0 for a in s.alpha[:3].tolist() for v in a)
+    with pytest.raises(B.PacerError) as e:
+        B.pacer_force_stop(s.ctx, 0, 2)
+    assert e.value.code == B.EINVAL
+    s.close()
+
+
+def test_pack_weight_counts_values_beyond_the_half_range():
+    """bf16 weights are held as half floats: a value beyond 65504 (or an inf / NaN in the source) cannot be represented,
+    and pacer_pack_weight reports how many there were instead of decoding garbage silently."""
+    from paper_2602_01274_amd import binding as B
+    src = (torch.randn(64, 128, device="cuda") * 0.02).to(torch.bfloat16)
+    dst = torch.empty_like(src)
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    B.pacer_pack_weight(dst, src, B.T_WO, 0, cnt, stream)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == 0
+    src[3, 5] = 1.0e6
+    src[40, 127] = float("inf")
+    src[17, 0] = -70000.0
+    src[9, 9] = 65000.0          # still a finite half
+    B.pacer_pack_weight(dst, src, B.T_WO, 0, cnt, stream)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == 3
+    B.pacer_pack_weight(dst, src, B.T_WO, 0, None, stream)      # the counter is optional
+    torch.cuda.synchronize()
+    # the engine refuses such a model
+    w = synth.workload("mid")
+    tgt, drf, mb = synth.make_pair(w, seed=0, n_layers_target=1)
+    tgt["layers"][0]["wo"][2, 2] = 3.0e5
+    with pytest.raises(B.PacerError) as e:
+        _session(w, tgt, drf, mb, 128)
+    assert e.value.code == B.EINVAL and "not finite" in str(e.value)
+
+
 def test_capacity_errors_are_reported_not_faulted():
     """KV capacity and window limits are host-checked: the calls fail with PACER_EOVERFLOW /
     PACER_ESTATE and leave the sequence usable."""
