@@ -196,6 +196,17 @@ int32_t pacer_force_stop(pacer_ctx* ctx, int32_t seq, int32_t flag);
  * has had no pre-verification call since its prefill. */
 int32_t pacer_wait_stop(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, int32_t* host_stop);
 
+/* The inner loop of Alg. 1 in one call, for sequences at the start of a step (after pacer_begin_step, no drafts
+ * yet): rounds of `block` draft steps (Eq. 6) and one pre-verification call (Eq. 7) for the sequences still
+ * drafting, until each has stopped (halting test, or a forced flag) or another block would exceed gamma_max.  It is
+ * the same sequence of pacer_draft_step / pacer_preverify_block / pacer_wait_stop calls a caller would issue (same
+ * kernels, same results); the loop runs inside the library so that between two rounds the host does nothing but
+ * read the kernel-written flag words and enqueue.  mode, rng_seed, rng_ctr as in pacer_draft_step.  dev_alpha
+ * [n_seqs][block] and dev_stop [n_seqs] are the outputs of the pre-verification calls (on return: of the last round,
+ * for the sequences that took part in it, in list order).  host_gamma[n_seqs] (host array) receives the windows. */
+int32_t pacer_draft_window(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, int32_t mode, uint64_t rng_seed,
+                           uint64_t rng_ctr, float* dev_alpha, int32_t* dev_stop, int32_t* host_gamma);
+
 /* Eq. 4: one target pass over [last committed token, y_1..y_gamma] of each listed sequence
  * against its KV cache (appending those rows).  gamma = number of drafts since
  * pacer_begin_step, or gamma_override[s] if gamma_override != NULL and >= 0 (host array; must

@@ -29,6 +29,7 @@ EXPORTS = [
     "pacer_preverify_block", "pacer_wait_stop", "pacer_verify", "pacer_accept_rollback", "pacer_get_state",
     "pacer_peek", "pacer_profile_enable", "pacer_profile_read", "pacer_launch_plan", "pacer_accept_noalloc",
     "pacer_force_stop", "pacer_launch_count", "pacer_stream_probe",
+    "pacer_draft_window",
 ]
 
 
@@ -79,6 +80,7 @@ def _load():
         "pacer_launch_plan": (i32, [i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]),
         "pacer_profile_read": (i32, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "pacer_stream_probe": (i32, [vp, u64, vp, vp]),
+        "pacer_draft_window": (i32, [vp, C.POINTER(i32), i32, i32, u64, u64, vp, vp, C.POINTER(i32)]),
         "pacer_force_stop": (i32, [vp, i32, i32]),
         "pacer_launch_count": (i32, [vp, C.POINTER(C.c_int64)]),
         "pacer_accept_noalloc": (i32, [vp, vp, vp, i32, i32, i32, i32, C.c_float, u64, u64, i32, vp, vp, vp]),
@@ -167,6 +169,12 @@ def pacer_begin_step(ctx, seq):
 
 def pacer_draft_step(ctx, seqs, mode, rng_seed, rng_ctr):
     _chk(ctx, _lib.pacer_draft_step(ctx, _i32s(seqs), len(seqs), mode, rng_seed, rng_ctr))
+
+
+def pacer_draft_window(ctx, seqs, mode, rng_seed, rng_ctr, dev_alpha, dev_stop):
+    out = (C.c_int32 * len(seqs))()
+    _chk(ctx, _lib.pacer_draft_window(ctx, _i32s(seqs), len(seqs), mode, rng_seed, rng_ctr, _ptr(dev_alpha), _ptr(dev_stop), out))
+    return list(out)
 
 
 def pacer_preverify_block(ctx, seqs, dev_alpha, dev_stop):

@@ -515,7 +515,9 @@ void rope_table(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
 // Decoder stack of a bf16 model on R rows.  On entry x holds the rows, xpA their f16 operand x*g of
 // the first norm and slot 0 their sums of squares.  On exit (not kv_only) x holds the final residual
 // rows, xpA = f16(x * g_final) and slot 2L their sums of squares.
-void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows& sr, bool kv_only) {
+// cache_only: the caller needs nothing but the KV cache rows (prompt ingestion of the target model), so the last
+// layer stops after its keys and values.
+void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows& sr, bool kv_only, bool cache_only = false) {
   const pacer_model_cfg& g = m.cfg;
   const int d = g.d_model, F = g.d_ffn, L = g.n_layers, H = g.n_heads, hd = g.head_dim;
   const int mt_total = (R + 15) / 16;
@@ -567,7 +569,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       ga.nt_begin = kv_only ? d / 16 : 0;
       gemm_w16<EPI_QKV>(c, tag, true, ga, (kv_only ? 2 : 3) * d / 16, d);
     }
-    if (kv_only) continue;
+    if (kv_only || (cache_only && l + 1 == L)) continue;
     {
       const _Float16* kv = static_cast<const _Float16*>(m.kv);
       // 17..32 rows per sequence: two row tiles.  With a short context and few (head, sequence) pairs the
@@ -662,7 +664,7 @@ void rmsnorm_f32(pacer_ctx* c, const Model& m, const float* g, int R, float* hid
                      c->kmax, hid_out, c->G1, sr);
 }
 
-void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool kv_only, float* hid_out) {
+void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool kv_only, float* hid_out, bool cache_only = false) {
   const pacer_model_cfg& g = m.cfg;
   const int d = g.d_model, F = g.d_ffn, H = g.n_heads, hd = g.head_dim;
   const SeqRows none{};
@@ -672,7 +674,7 @@ void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool
     gemm_f32(c, m.wqkv[l], c->xn, c->kmax, c->qkv, 3 * c->dmax, R, 3 * d, d, 0, none, ROWMAP_ID);
     PACER_LAUNCH((rope_append_kernel<float>), dim3(R, H), dim3(hd / 2), 0, c->stream, c->qkv, 3 * c->dmax, c->rope, sr, d, hd,
                        static_cast<float*>(m.kv), l, g.n_layers, g.max_seq, kv_only ? 1 : 0);
-    if (kv_only) continue;
+    if (kv_only || (cache_only && l + 1 == g.n_layers)) continue;
     int max_keys = 0;
     for (int i = 0; i < sr.n_seqs; ++i) max_keys = std::max(max_keys, sr.pos0[i] + sr.row_off[i + 1] - sr.row_off[i]);
     const int n_tiles = (max_keys + ATT_TILE - 1) / ATT_TILE;
@@ -688,20 +690,20 @@ void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool
     PACER_LAUNCH(swiglu_pack_kernel, dim3((F / 8 + 255) / 256, R), dim3(256), 0, c->stream, c->gu, 2 * c->fmax, R, F, c->xn, c->kmax);
     gemm_f32(c, m.wd[l], c->xn, c->kmax, c->x, c->dmax, R, d, F, 1, none, ROWMAP_ID);
   }
-  if (!kv_only) rmsnorm_f32(c, m, m.final_norm, R, hid_out, sr);
+  if (!kv_only && !cache_only) rmsnorm_f32(c, m, m.final_norm, R, hid_out, sr);
 }
 
 // ===== model-level steps, both paths ==========================================================
 
 // rows -> x (embedding gather) and the decoder stack; `tag` 0 = target model
-void forward_lm(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows& sr) {
+void forward_lm(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows& sr, bool cache_only = false) {
   if (is_w16(m)) {
     embed_w16(c, m, R, sr);
-    run_layers_w16(c, m, tag, R, sr, false);
+    run_layers_w16(c, m, tag, R, sr, false, cache_only);
   } else {
     PACER_LAUNCH((embed_rows_kernel<float>), dim3(R), dim3(256), 0, c->stream, static_cast<const float*>(m.embed), c->tokens,
                        c->draft_tok, sr, c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax);
-    run_layers_f32(c, m, R, sr, false, nullptr);
+    run_layers_f32(c, m, R, sr, false, nullptr, cache_only);
   }
 }
 
@@ -1128,7 +1130,7 @@ int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_
       mr.e0[i] = -1;
     }
     sr.row_off[sr.n_seqs] = R;
-    forward_lm(c, c->m[PACER_TARGET], 0, R, sr);
+    forward_lm(c, c->m[PACER_TARGET], 0, R, sr, true);       // the target's prompt pass leaves nothing but its cache rows
     const Model& md = c->m[PACER_DRAFT];
     forward_lm(c, md, 1, R, sr);
     // the draft's hidden states (final-norm output) feed M_B's prefix rows; staged in ao
@@ -1263,6 +1265,36 @@ int32_t pacer_wait_stop(pacer_ctx* c, const int32_t* seqs, int32_t n, int32_t* h
     if (int rc = wait_ticket(c, p, q.pv_ticket, 1)) return rc;
     host_stop[i] = *p & 1;
   }
+  return PACER_OK;
+}
+
+int32_t pacer_draft_window(pacer_ctx* c, const int32_t* seqs, int32_t n, int32_t mode, uint64_t seed, uint64_t ctr, float* dev_alpha,
+                           int32_t* dev_stop, int32_t* host_gamma) {
+  if (!c) return PACER_EINVAL;
+  if (int rc = ready(c)) return rc;
+  if (int rc = check_seqs(c, seqs, n)) return rc;
+  if (!dev_alpha || !dev_stop || !host_gamma) return fail(c, PACER_EINVAL, "draft_window: null output");
+  if (mode != PACER_GREEDY && mode != PACER_SAMPLE) return fail(c, PACER_EINVAL, "draft_window: bad mode %d", mode);
+  for (int i = 0; i < n; ++i) {
+    const Seq& q = c->seq[seqs[i]];
+    if (!q.in_step || q.verified >= 0 || q.gamma != 0) return fail(c, PACER_ESTATE, "draft_window: sequence %d is not at the start of a step", seqs[i]);
+  }
+  // the inner loop of Alg. 1: blocks of b draft steps and one pre-verification call for the sequences still drafting
+  int32_t active[PACER_MAX_BATCH], flags[PACER_MAX_BATCH];
+  int m = n;
+  for (int i = 0; i < n; ++i) active[i] = seqs[i];
+  const int b = c->pv.block;
+  while (m > 0) {
+    for (int k = 0; k < b; ++k)
+      if (int rc = pacer_draft_step(c, active, m, mode, seed, ctr)) return rc;
+    if (int rc = pacer_preverify_block(c, active, m, dev_alpha, dev_stop)) return rc;
+    if (int rc = pacer_wait_stop(c, active, m, flags)) return rc;
+    int keep = 0;
+    for (int i = 0; i < m; ++i)
+      if (!flags[i] && c->seq[active[i]].gamma + b <= c->pv.gamma_max) active[keep++] = active[i];
+    m = keep;
+  }
+  for (int i = 0; i < n; ++i) host_gamma[i] = c->seq[seqs[i]].gamma;
   return PACER_OK;
 }
 

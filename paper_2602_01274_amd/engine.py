@@ -178,6 +178,11 @@ class Session:
                 self._call("draft_step", B.pacer_draft_step, ctx, seqs, mode, seed, ctr)
             gamma = fixed_gamma
             self.counts["draft"] += gamma
+        elif not record and force_stop is None and self.timers is None:
+            # the whole inner loop of Alg. 1 in one library call (same kernels and flags as the loop below)
+            gamma = B.pacer_draft_window(ctx, seqs, mode, seed, ctr, self.alpha, self.stop)[0]
+            self.counts["draft"] += gamma
+            self.counts["preverify"] += gamma // self.block
         else:
             while True:
                 for _ in range(self.block):
@@ -237,6 +242,12 @@ class Session:
                 self._call("draft_step", B.pacer_draft_step, ctx, active, mode, seed, ctr)
             gamma = {s: fixed_gamma for s in seqs}
             self.counts["draft"] += fixed_gamma * len(seqs)
+            active = []
+        elif not record and self.timers is None:
+            gs = B.pacer_draft_window(ctx, active, mode, seed, ctr, self.alpha, self.stop)
+            gamma = dict(zip(seqs, gs))
+            self.counts["draft"] += sum(gs)
+            self.counts["preverify"] += sum(g // self.block for g in gs)
             active = []
         while active:
             for _ in range(self.block):

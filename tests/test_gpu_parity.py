@@ -123,6 +123,16 @@ def test_7b_width_long_context_4100_keys():
          w_over=dict(mode="greedy"), step_kw=dict(force_stop=lambda k, a: False))
 
 
+def test_prompt_ingestion_1500_tokens_first_alpha_and_first_verify():
+    """Prompt ingestion (three passes of up to 512 rows through the wide GEMMs, the last one ragged, 16 slots of 32
+    positions in the attention kernel; the target's last layer stops after its K/V) is checked by what is computed
+    from the caches it leaves: the pre-verification layer's first alpha values (its prefix rows), the draft logits
+    and every row of the first verify pass, against the oracle, with the halting test deciding the windows."""
+    ck, gammas, _ = _run("7b", 1500, 12, tol_logits=2e-2, tol_alpha=2e-2, n_layers_target=2, max_seq=1664,
+                         w_over=dict(mode="greedy"))
+    assert ck.max_err["alpha"] > 0.0 and ck.max_err["target_logits"] > 0.0      # both were really compared
+
+
 def test_7b_width_full_window_and_long_prompt():
     """gamma = gamma_max = 16 every step (17 verify rows: one full row tile + row 16), on a 2100-token
     prompt: the target's attention splits its keys over 8 blocks per head, the draft's and the
@@ -453,6 +463,40 @@ def test_wait_stop_and_get_state_match_the_device_buffers():
             for k, i in enumerate(seqs):
                 st = B.pacer_get_state(s.ctx, i)
                 assert st["n_accepted"] == int(s.n_acc[k].item()) and st["next_token"] == int(s.next_tok[k].item())
+    s.close()
+
+
+def test_draft_window_call_equals_the_call_by_call_loop():
+    """pacer_draft_window (the inner loop of Alg. 1 inside the library) against the same loop issued call by call:
+    same windows, same accept counts and same tokens, single sequence (both modes) and a ragged batch."""
+    for name, mode, n_prompt in (("tiny", po.GREEDY, 20), ("tiny", po.SAMPLE, 33), ("mid", po.GREEDY, 70)):
+        w = synth.workload(name)
+        tgt, drf, mb = synth.make_pair(w, seed=0, n_layers_target=2 if name == "mid" else None)
+        s = _session(w, tgt, drf, mb, 512)
+        prompt = synth.make_prompt(w["target"]["vocab"], n_prompt, 3).tolist()
+        runs = []
+        for record in (True, False):
+            s.prefill(prompt)
+            toks, recs = s.generate(40, mode=mode, seed=9, record=record)
+            runs.append((toks, [(r["gamma"], r["n"], r["z"]) for r in recs]))
+        assert runs[0] == runs[1]
+        assert len({g for g, _, _ in runs[0][1]}) > 1                 # windows of several lengths occurred
+        s.close()
+    w = synth.workload("tiny")
+    tgt, drf, mb = synth.make_pair(w, seed=0)
+    s = _session(w, tgt, drf, mb, 256, max_batch=4)
+    seqs, betas = [0, 1, 2, 3], [4.0, 1.0, 2.5, 3.0]
+    runs = []
+    for record in (True, False):
+        for i in seqs:
+            s.prefill(synth.make_prompt(1024, 7 + 9 * i, 40 + i).tolist(), seq=i)
+        s.step_idx = [0] * 4
+        out = []
+        for _ in range(8):
+            out.append([(r["gamma"], r["n"], r["z"]) for r in s.step_batch(seqs, betas=betas, record=record)])
+        runs.append((out, [s.tokens(i) for i in seqs]))
+    assert runs[0] == runs[1]
+    assert len({g for step in runs[0][0] for g, _, _ in step}) > 1
     s.close()
 
 
