@@ -79,10 +79,10 @@ def cpu_baseline(w, tgt, drf, mb, prompt, mode, budget_steps=2, threads=None):
                       f"BLAS threads = cores"}
 
 
-def stream_ceiling(torch, B):
+def stream_ceiling(torch, B, shape=None, n_layers=None):
     """What this GPU delivers to kernels that only move data: a streaming read (the library's probe kernel) and a
-    plain device-to-device copy of 1 GiB, in GB/s (the copy counts read + written bytes)."""
-    n = 1 << 30
+    plain device-to-device copy of 2 GiB, in GB/s (the copy counts read + written bytes)."""
+    n = 1 << 31
     src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
     dst = torch.empty_like(src)
     sink = torch.zeros(64, dtype=torch.int32, device="cuda")
@@ -100,10 +100,36 @@ def stream_ceiling(torch, B):
         return best
     read_ms = timed(lambda: B.pacer_stream_probe(src, sink, st))
     copy_ms = timed(lambda: dst.copy_(src))
+    # The same probe as ONE launch of the size of each of the target's matrices, in a chain of launches over
+    # consecutive cold regions (as the GEMMs of a verify pass follow each other): the time a kernel needs that
+    # does nothing but read those bytes, launch and ramp included.  Their sum over a pass is the floor of any
+    # design with one launch per matrix.
+    floors = None
+    if shape is not None:
+        d, f, v = shape["d_model"], shape["d_ffn"], shape["vocab"]
+        L = shape["n_layers"] if n_layers is None else n_layers
+        sizes = {"qkv": 3 * d * d * 2, "o": d * d * 2, "gate_up": 2 * f * d * 2, "down": d * f * 2, "lm_head": v * d * 2}
+        floors = {}
+        for name, nb in sizes.items():
+            nb = nb // 4096 * 4096
+            reps = max(2, min(24, n // nb))
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            best = 1e30
+            for _ in range(3):
+                torch.cuda.synchronize()
+                e0.record()
+                for r in range(reps):
+                    B.pacer_stream_probe(src[r * nb:(r + 1) * nb], sink, st)
+                e1.record()
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1) * 1e3 / reps)
+            floors[name] = {"MB": round(nb / 1e6, 1), "us": round(best, 2)}
+        per_layer = sum(floors[k]["us"] for k in ("qkv", "o", "gate_up", "down"))
+        floors["pass_ms_without_attention"] = round((L * per_layer + floors["lm_head"]["us"]) / 1e3, 4)
     del src, dst
     torch.cuda.empty_cache()
     return {"streaming_read_GBps": round(n / 1e6 / read_ms, 1), "device_copy_GBps": round(2 * n / 1e6 / copy_ms, 1),
-            "bytes": n, "note": "best of 5; the read kernel is the library's probe (16-byte loads, 1024 blocks of 8 waves)"}
+            "bytes": n, "per_launch_read_floor": floors, "note": "best of 5; the read kernel is the library's probe (16-byte loads, 256 blocks of 4 waves, 8 loads in flight per lane)"}
 
 
 def main():
@@ -236,7 +262,7 @@ def main():
         if a.cpu_one_thread:
             one = cpu_baseline(w, host[0], host[1], host[2], prompt, 1 if mode == B.SAMPLE else 0, threads=1)
             cpu["one_thread"] = {"value": one["value"], "cores": one["cores"], "sample": one["sample"]}
-    ceiling = stream_ceiling(torch, B)
+    ceiling = stream_ceiling(torch, B, w["target"] if w["dtype"] == "bf16" else None, L)
 
     if a.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()

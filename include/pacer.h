@@ -292,7 +292,7 @@ int32_t pacer_launch_plan(int32_t n_out, int32_t n_in, int32_t rows, int32_t ope
 /* Number of kernels the context has enqueued since it was created (benchmarks: launches per call). */
 int32_t pacer_launch_count(const pacer_ctx* ctx, int64_t* n_launches);
 
-/* Benchmark support, no context: one kernel that reads dev_src[0..nbytes) once (16-byte loads, 1024 blocks of 8
+/* Benchmark support, no context: one kernel that reads dev_src[0..nbytes) once (16-byte loads, 256 blocks of 4
  * waves) and folds it into dev_sink (256 bytes of device memory, caller-zeroed or not).  Timed by the caller, it
  * gives the streaming-read rate a kernel reaches on this GPU when it does nothing but load: the practical ceiling
  * beside which the weight-streaming GEMMs' rates are reported.  dev_src must be 16-byte aligned. */

@@ -1463,7 +1463,7 @@ int32_t pacer_launch_count(const pacer_ctx* c, int64_t* n_launches) {
 
 int32_t pacer_stream_probe(const void* dev_src, uint64_t nbytes, void* dev_sink, void* hip_stream) {
   if (!dev_src || !dev_sink || nbytes < 16 || reinterpret_cast<uintptr_t>(dev_src) % 16) return fail_noctx(PACER_EINVAL, "stream_probe: bad arguments");
-  hipLaunchKernelGGL(stream_probe_kernel, dim3(256 * 4), dim3(512), 0, static_cast<hipStream_t>(hip_stream),
+  hipLaunchKernelGGL(stream_probe_kernel, dim3(256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                      static_cast<const u32x4*>(dev_src), (size_t)(nbytes / 16), static_cast<uint32_t*>(dev_sink));
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_noctx(PACER_EHIP, "stream_probe: %s", hipGetErrorString(e));

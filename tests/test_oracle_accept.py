@@ -65,35 +65,66 @@ def _exact_ngram_law(w, tgt, drf, prompt, n):
     return law
 
 
+_STOP_RULES = {
+    "halting_test": None,                                   # the procedure's own decisions
+    "adversarial": lambda k, a: k == 0 and a[0] > 0.5,      # a stop rule that looks at the pre-verification output
+    "fixed3": "fixed3",                                     # vanilla speculative decoding, window 3
+}
+
+
+def _sample_ngrams(args):
+    """Worker: 3-gram counts of the sampled procedure for seeds [lo, hi) under one stop rule (one oracle, reset per sample)."""
+    rule, lo, hi, prompt = args
+    from threadpoolctl import threadpool_limits
+    threadpool_limits(1)                                    # 16-wide matrices: BLAS threads only get in each other's way
+    w, tgt, drf, mb = _tiny(beta=1.0)
+    fs = _STOP_RULES[rule]
+    cached = [helpers.to_oracle(m, cache=True) for m in (tgt, drf, mb)]
+    o = helpers.build_oracle(w, cached[0], cached[1], cached[2], mode=po.SAMPLE, seed=0, max_seq=32)
+    cnt, acc = {}, 0
+    for s in range(lo, hi):
+        o.tokens, o.step_idx, o.seed = [], 0, 1000 + s
+        for kv in (o.kvT, o.kvD, o.kvB):
+            kv.n = 0
+        o.prefill(prompt)
+        out, recs = o.generate(3, fixed_gamma=3) if fs == "fixed3" else o.generate(3, force_stop=fs)
+        cnt[tuple(out)] = cnt.get(tuple(out), 0) + 1
+        acc += recs[0]["n"]
+    return cnt, acc
+
+
 def test_sampled_pacer_output_follows_the_target_law():
     """Sec. 2.2 (last sentence): the output distribution equals that of autoregressive decoding
-    of the target.  3-gram law of the sampled procedure, with the real halting test and with an
-    adversarial stop rule that looks at the draft tokens, against exact enumeration."""
+    of the target.  3-gram law of the sampled procedure (30000 samples per stop rule, 125 cells: the smallest
+    expected cell count is above 5, so every cell takes part), with the real halting test, with an adversarial
+    stop rule that looks at the pre-verification output and with a fixed window, against exact enumeration."""
+    from concurrent.futures import ProcessPoolExecutor
+    import multiprocessing as mp
     w, tgt, drf, mb = _tiny(beta=1.0)
     prompt = [1, 4, 2]
     law = _exact_ngram_law(w, tgt, drf, prompt, 3)
     keys = sorted(law)
     exp = np.array([law[k] for k in keys])
     assert abs(exp.sum() - 1) < 1e-9 and exp.max() < 0.5
-    n = 2000
-    for fs in (None, lambda k, a: k == 0 and a[0] > 0.5, "fixed3"):
+    n, workers = 30000, 8
+    chunk = n // workers
+    jobs = [(rule, i * chunk, (i + 1) * chunk, prompt) for rule in _STOP_RULES for i in range(workers)]
+    with ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn")) as ex:
+        res = list(ex.map(_sample_ngrams, jobs))
+    for r, rule in enumerate(_STOP_RULES):
         cnt = dict.fromkeys(keys, 0)
-        acc = []
-        for s in range(n):
-            o = helpers.build_oracle(w, tgt, drf, mb, mode=po.SAMPLE, seed=1000 + s, max_seq=32)
-            o.prefill(prompt)
-            if fs == "fixed3":
-                out, recs = o.generate(3, fixed_gamma=3)
-            else:
-                out, recs = o.generate(3, force_stop=fs)
-            cnt[tuple(out)] += 1
-            acc.append(recs[0]["n"])
+        acc = 0
+        for c, a in res[r * workers:(r + 1) * workers]:
+            for k, v in c.items():
+                cnt[k] += v
+            acc += a
         obs = np.array([cnt[k] for k in keys], dtype=float)
+        assert obs.sum() == n
         big = exp * n >= 5
-        o2 = np.append(obs[big], obs[~big].sum())
-        e2 = np.append(exp[big], exp[~big].sum()) * n
-        assert stats.chisquare(o2, e2).pvalue > 1e-3
-        assert 0 < np.mean(acc) < 3          # both acceptances and rejections occurred
+        o2 = np.append(obs[big], obs[~big].sum()) if (~big).any() else obs
+        e2 = np.append(exp[big], exp[~big].sum()) * n if (~big).any() else exp * n
+        assert stats.chisquare(o2, e2).pvalue > 1e-3, rule
+        assert 0 < acc / n < 3, rule          # both acceptances and rejections occurred
 
 
 def test_sampled_first_token_is_not_the_draft_law():
