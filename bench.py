@@ -126,10 +126,21 @@ def stream_ceiling(torch, B, shape=None, n_layers=None):
             floors[name] = {"MB": round(nb / 1e6, 1), "us": round(best, 2)}
         per_layer = sum(floors[k]["us"] for k in ("qkv", "o", "gate_up", "down"))
         floors["pass_ms_without_attention"] = round((L * per_layer + floors["lm_head"]["us"]) / 1e3, 4)
+    # 1000 launches that read 4 KiB each, enqueued back to back by the library: what one more kernel in a sequence
+    # of launches costs when it does next to nothing (the floor under each of the 13 launches of a draft step)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tiny = 1e30
+    for _ in range(3):
+        torch.cuda.synchronize()
+        e0.record()
+        B.pacer_stream_probe(src[:4096], sink, st, repeat=1000)
+        e1.record()
+        torch.cuda.synchronize()
+        tiny = min(tiny, e0.elapsed_time(e1) * 1e3 / 1000)
     del src, dst
     torch.cuda.empty_cache()
     return {"streaming_read_GBps": round(n / 1e6 / read_ms, 1), "device_copy_GBps": round(2 * n / 1e6 / copy_ms, 1),
-            "bytes": n, "per_launch_read_floor": floors, "note": "best of 5; the read kernel is the library's probe (16-byte loads, 256 blocks of 4 waves, 8 loads in flight per lane)"}
+            "bytes": n, "per_launch_read_floor": floors, "empty_launch_us": round(tiny, 2), "note": "best of 5; the read kernel is the library's probe (16-byte loads, 256 blocks of 4 waves, 8 loads in flight per lane)"}
 
 
 def main():

@@ -295,8 +295,10 @@ int32_t pacer_launch_count(const pacer_ctx* ctx, int64_t* n_launches);
 /* Benchmark support, no context: one kernel that reads dev_src[0..nbytes) once (16-byte loads, 256 blocks of 4
  * waves) and folds it into dev_sink (256 bytes of device memory, caller-zeroed or not).  Timed by the caller, it
  * gives the streaming-read rate a kernel reaches on this GPU when it does nothing but load: the practical ceiling
- * beside which the weight-streaming GEMMs' rates are reported.  dev_src must be 16-byte aligned. */
-int32_t pacer_stream_probe(const void* dev_src, uint64_t nbytes, void* dev_sink, void* hip_stream);
+ * beside which the weight-streaming GEMMs' rates are reported.  dev_src must be 16-byte aligned.  repeat (1..100000)
+ * launches of the same read are enqueued back to back: with a few KiB this measures what one more kernel in a
+ * sequence of launches costs when it does next to nothing. */
+int32_t pacer_stream_probe(const void* dev_src, uint64_t nbytes, int32_t repeat, void* dev_sink, void* hip_stream);
 
 /* Kernel timing for benchmarks: while enabled, every launch of the target model's GEMM kernels
  * carries a pair of HIP events on the context's stream that receive the kernel's own begin and end

@@ -12,7 +12,8 @@ import os
 import torch  # imported first: the library resolves libamdhip64 to the runtime torch has loaded
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpacer.so")
+# PACER_LIB: another build of the same library (e.g. one compiled with -DPACER_FENCED_HANDOVER, to compare)
+LIB_PATH = os.environ.get("PACER_LIB") or os.path.join(_HERE, "libpacer.so")
 
 OK, EINVAL, ESTATE, EOVERFLOW, EHIP = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
@@ -79,7 +80,7 @@ def _load():
         "pacer_profile_enable": (i32, [vp, i32]),
         "pacer_launch_plan": (i32, [i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]),
         "pacer_profile_read": (i32, [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
-        "pacer_stream_probe": (i32, [vp, u64, vp, vp]),
+        "pacer_stream_probe": (i32, [vp, u64, i32, vp, vp]),
         "pacer_draft_window": (i32, [vp, C.POINTER(i32), i32, i32, u64, u64, vp, vp, C.POINTER(i32)]),
         "pacer_force_stop": (i32, [vp, i32, i32]),
         "pacer_launch_count": (i32, [vp, C.POINTER(C.c_int64)]),
@@ -181,8 +182,8 @@ def pacer_preverify_block(ctx, seqs, dev_alpha, dev_stop):
     _chk(ctx, _lib.pacer_preverify_block(ctx, _i32s(seqs), len(seqs), _ptr(dev_alpha), _ptr(dev_stop)))
 
 
-def pacer_stream_probe(src, sink, stream):
-    rc = _lib.pacer_stream_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink), C.c_void_p(stream))
+def pacer_stream_probe(src, sink, stream, repeat=1):
+    rc = _lib.pacer_stream_probe(_ptr(src), src.numel() * src.element_size(), repeat, _ptr(sink), C.c_void_p(stream))
     if rc != OK:
         raise PacerError(rc, _lib.pacer_last_error(None).decode())
 

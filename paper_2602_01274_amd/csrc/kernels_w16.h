@@ -29,6 +29,22 @@
 #pragma once
 #include "kernels.h"
 
+// The cross-block hand-overs below rest on gfx950 behaviour (see "KSB" at gemm_w16_kernel) and on the encoding of
+// s_waitcnt for that target: refuse to build device code for anything else.
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "kernels_w16.h is written for gfx950 (MI355X): the fence-free hand-over and the s_waitcnt immediates are specific to it"
+#endif
+// Memory order of the arrival-counter increment of those hand-overs.  Relaxed by default: ordering comes from the
+// write-through stores having completed (vmcnt 0) before the block's barrier, and from loads that do not hit in L2.
+// Building with -DPACER_FENCED_HANDOVER makes the increment an agent-scope acquire-release (L2 write-back before it,
+// invalidation after it, 4 to 15 us per launch): the variant to compare with if results ever differ between runs.
+#ifdef PACER_FENCED_HANDOVER
+#define PACER_HO_ORDER __ATOMIC_ACQ_REL
+#else
+#define PACER_HO_ORDER __ATOMIC_RELAXED
+#endif
+#define PACER_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0F70)   // gfx9 encoding: vmcnt = 0, expcnt and lgkmcnt at their maxima (no wait)
+
 #define PACK_PLAIN 0
 #define PACK_QKV 1
 #define PACK_GATEUP 2
@@ -535,9 +551,9 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 ? (NT >= 5 ? 2 : 4) : 1)) v
         __hip_atomic_store(dst + 1, __builtin_bit_cast(u64, hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's write-through stores have completed
+    PACER_WAIT_VMCNT0();   // this wave's write-through stores have completed
     __syncthreads();
-    if (threadIdx.x == 0) sk_arrived = __hip_atomic_fetch_add(ga.sk_cnt + grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) sk_arrived = __hip_atomic_fetch_add(ga.sk_cnt + grp, 1u, PACER_HO_ORDER, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (sk_arrived != KSB - 1) return;
     if (threadIdx.x == 0) __hip_atomic_store(ga.sk_cnt + grp, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -886,9 +902,9 @@ __global__ __launch_bounds__(512, 1) void gemm_wide8_kernel(const GemmArgs ga, i
         __hip_atomic_store(d, __builtin_bit_cast(u64, lo), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(d + 1, __builtin_bit_cast(u64, hi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's write-through stores have completed
+    PACER_WAIT_VMCNT0();   // this wave's write-through stores have completed
     __syncthreads();
-    if (threadIdx.x == 0) arrived = __hip_atomic_fetch_add(ga.sk_cnt + gidx, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) arrived = __hip_atomic_fetch_add(ga.sk_cnt + gidx, 1u, PACER_HO_ORDER, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (arrived != KSB - 1) return;
     if (threadIdx.x == 0) __hip_atomic_store(ga.sk_cnt + gidx, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1134,10 +1150,10 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
     }
   }
   if (n_split == 1) return;
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's write-through stores have completed
+  PACER_WAIT_VMCNT0();   // this wave's write-through stores have completed
   __syncthreads();
   unsigned* my_cnt = cnt + ((size_t)si * H + h) * 2 + rt;
-  if (threadIdx.x == 0) arrived = __hip_atomic_fetch_add(my_cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0) arrived = __hip_atomic_fetch_add(my_cnt, 1u, PACER_HO_ORDER, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   if (arrived != (unsigned)(n_split - 1)) return;
   if (threadIdx.x == 0) __hip_atomic_store(my_cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

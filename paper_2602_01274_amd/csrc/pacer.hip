@@ -1461,10 +1461,12 @@ int32_t pacer_launch_count(const pacer_ctx* c, int64_t* n_launches) {
   return PACER_OK;
 }
 
-int32_t pacer_stream_probe(const void* dev_src, uint64_t nbytes, void* dev_sink, void* hip_stream) {
-  if (!dev_src || !dev_sink || nbytes < 16 || reinterpret_cast<uintptr_t>(dev_src) % 16) return fail_noctx(PACER_EINVAL, "stream_probe: bad arguments");
-  hipLaunchKernelGGL(stream_probe_kernel, dim3(256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                     static_cast<const u32x4*>(dev_src), (size_t)(nbytes / 16), static_cast<uint32_t*>(dev_sink));
+int32_t pacer_stream_probe(const void* dev_src, uint64_t nbytes, int32_t repeat, void* dev_sink, void* hip_stream) {
+  if (!dev_src || !dev_sink || nbytes < 16 || repeat < 1 || repeat > 100000 || reinterpret_cast<uintptr_t>(dev_src) % 16)
+    return fail_noctx(PACER_EINVAL, "stream_probe: bad arguments");
+  for (int r = 0; r < repeat; ++r)
+    hipLaunchKernelGGL(stream_probe_kernel, dim3(256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const u32x4*>(dev_src), (size_t)(nbytes / 16), static_cast<uint32_t*>(dev_sink));
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_noctx(PACER_EHIP, "stream_probe: %s", hipGetErrorString(e));
   return PACER_OK;
