@@ -328,14 +328,20 @@ def test_7b_full_depth_headline_settings_against_oracle_and_losslessness(capsys)
     step at that context are compared with the oracle row by row (every logit of every verify row, every
     draft logit, alpha, every integer decision).  (ii) Property that holds at any size: greedy speculative
     decoding emits the tokens of target-only greedy decoding run through the same kernels; a mismatch must
-    sit at a near-tie of the GPU's own deciding logits."""
+    sit at a near-tie of the GPU's own deciding logits.  (iii) The long-context workload's length at full depth
+    (4096-token prompt, 32 layers), again by a property that holds at any size: row i of one 17-row verify pass
+    equals the i-th of 17 single-token target passes over the same tokens (the KV-cached parallel forward of
+    Eq. 4 against Eq. 1 step by step), here through different kernels (17-row form and split keys against the
+    one-row shapes)."""
+    from paper_2602_01274_amd import binding as B
+
     def say(msg):
         with capsys.disabled():
             print(f"[7b full depth] {msg}", flush=True)
     w = synth.workload("7b")
     assert w["mode"] == "sample" and w["prompt"] == 512
     tgt, drf, mb = synth.make_pair(w, seed=0, device="cuda")
-    s = _session(w, tgt, drf, mb, 1024)
+    s = _session(w, tgt, drf, mb, 4352)
     host = (_host_copy(tgt), _host_copy(drf), _host_copy(mb))
     del tgt, drf, mb
     torch.cuda.empty_cache()
@@ -369,6 +375,22 @@ def test_7b_full_depth_headline_settings_against_oracle_and_losslessness(capsys)
         say(f"speculative and autoregressive runs part at token {k}: top-2 gap {top[1] - top[0]:.2e}")
         assert top[1] - top[0] < 2e-2 * np.sqrt(np.mean(eff ** 2))
     assert any(r["n"] > 0 for r in recs) and any(r["n"] < r["gamma"] for r in recs)
+    # (iii) 4096-token prompt: one 17-row verify pass against 17 one-row passes over the same tokens
+    prompt = synth.make_prompt(32000, 4096, 4).tolist()
+    s.prefill(prompt)
+    one = s.step(fixed_gamma=16, record=True)
+    rows, y = one["target_logits"].double(), one["draft_tokens"]
+    s.prefill(prompt)
+    worst = 0.0
+    for i in range(17):
+        r = s.step(fixed_gamma=0, record=True)
+        single = r["target_logits"][0].double()
+        err = ((single - rows[i]).abs().max() / rows[i].pow(2).mean().sqrt()).item()
+        worst = max(worst, err)
+        if i < 16:      # teacher forcing: the committed token becomes the draft the 17-row pass verified
+            B.pacer_force_commit(s.ctx, 0, len(prompt) + i, [y[i]])
+    say(f"4096-token prompt: 17-row verify pass against 17 single-token passes, max err / RMS {worst:.2e}")
+    assert worst < 1e-2                # two f16 paths with different summation orders: half the tolerance against the oracle
     s.close()
 
 
