@@ -65,6 +65,19 @@ def test_tiny_forced_stop_patterns():
     _run("tiny", 20, 16, tol_logits=1e-4, tol_alpha=1e-4, step_kw=dict(force_stop=lambda k, a: True))
 
 
+def test_largest_windows_the_library_takes():
+    """gamma_max = 31 is the largest window a context accepts (32 verify rows = two full row tiles).  f32 pair with
+    block size 1 (31 draft steps and 31 one-row pre-verification calls per step), bf16 pair with gamma_max 28 and
+    b 4 (29 verify rows: two row tiles, not the 17-row form); every block is forced to pass so that each step uses
+    the whole window."""
+    ck, gammas, _ = _run("tiny", 11, 40, tol_logits=1e-4, tol_alpha=1e-4, w_over=dict(block=1, gamma_max=31),
+                         step_kw=dict(force_stop=lambda k, a: False), max_seq=256)
+    assert set(gammas) == {31}
+    ck, gammas, _ = _run("mid", 90, 24, tol_logits=2e-2, tol_alpha=2e-2, w_over=dict(gamma_max=28),
+                         step_kw=dict(force_stop=lambda k, a: False), max_seq=512)
+    assert set(gammas) == {28}
+
+
 def test_halting_variants_any_and_last():
     """Sec. 5.2's stricter criteria (any token / last token below t) next to the mean criterion."""
     g = {}

@@ -63,3 +63,91 @@ def test_accept_noalloc_matches_accept_rollback(mode):
         B.pacer_accept_noalloc(tl, dl, dt, 32, True, V, mode, 1.0, 0, 0, 0, out_n, out_z, stream)
     assert e.value.code == B.EOVERFLOW
     s.close()
+
+
+class _LogitsOracle:
+    """The oracle's own step (Alg. 1, verification part; Eq. 5) run on scripted logits: the draft and target
+    "models" return rows of given arrays, so the acceptance arithmetic of oracle/pacer_oracle.py is what decides."""
+
+    def __init__(self, tl, dl, beta, mode, seed, step_idx, seq):
+        from oracle import pacer_oracle as po
+
+        class Scripted(po.PacerOracle):
+            def __init__(s):
+                c = po.ModelCfg(1, 1, 1, 1, 1, tl.shape[1])
+                super().__init__(None, c, None, c, None, block=1, gamma_max=tl.shape[0], t0=0.5, rho=1.0, beta=beta,
+                                 mode=mode, seed=seed, seq=seq, max_seq=1)
+                s.k = 0
+
+                class NoCache:
+                    n = 10 ** 9
+                    def truncate(self, n): pass
+                s.kvT = s.kvD = s.kvB = NoCache()
+                s.tokens = [0]
+                s.step_idx = step_idx
+
+            def _draft_one(s, tok):
+                s.k += 1
+                return np.zeros(1), dl[s.k - 1]
+
+            def _target_rows(s, toks):
+                return tl[:len(toks)]
+
+        self.o = Scripted()
+
+    def step(self, gamma):
+        return self.o.step(fixed_gamma=gamma)
+
+
+@pytest.mark.parametrize("mode", [B.GREEDY, B.SAMPLE])
+def test_accept_noalloc_against_oracle_on_scripted_logits(mode):
+    """The acceptance kernels against the oracle's Eq. 5 arithmetic on logits that no model produced: the largest
+    window the entry point takes (gamma 31, vocabulary 32000: all 16 chunks), strong and weak coupling, identical
+    draft and target distributions (beta 0, equal logits: every draft is accepted with probability one and a rejection
+    would find no residual mass), and a window of one.  Integers must be equal unless the oracle's margin is a tie."""
+    import torch
+    from oracle import philox
+    from oracle import pacer_oracle as po
+    stream = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(17)
+    out_n = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out_z = torch.zeros(1, dtype=torch.int32, device="cuda")
+    cases = [(31, 32000, 3.0, 1.0, False), (31, 32000, 0.5, 1.0, False), (16, 32000, 0.0, 1.0, True), (1, 1024, 1.0, 2.0, False),
+             (8, 5000, 6.0, 0.5, False), (31, 1024, 12.0, 1.0, False), (5, 16, 1.0, 1.0, False)]
+    seen_bonus = False
+    for ci, (gamma, V, beta, scale, same) in enumerate(cases):
+        for rep in range(3):
+            dl = (rng.standard_normal((gamma + 1, V)) * scale).astype(np.float32).astype(np.float64)
+            tl = dl.copy() if same else (rng.standard_normal((gamma + 1, V)) * scale).astype(np.float32).astype(np.float64)
+            seed, step_idx, seq = 100 + ci, 7 + rep, (ci + rep) % 16
+            ro = _LogitsOracle(tl, dl, beta, mode, seed, step_idx, seq).step(gamma)
+            y = ro["draft_tokens"]
+            t_dev = torch.tensor(tl, dtype=torch.float32, device="cuda")
+            d_dev = torch.tensor(dl, dtype=torch.float32, device="cuda")
+            y_dev = torch.tensor(y, dtype=torch.int32, device="cuda")
+            B.pacer_accept_noalloc(t_dev, d_dev, y_dev, gamma, True, V, mode, beta, seed, step_idx, seq, out_n, out_z, stream)
+            torch.cuda.synchronize()
+            n, z = int(out_n.item()), int(out_z.item())
+            seen_bonus |= ro["n"] == gamma
+            if (n, z) != (ro["n"], ro["z"]):
+                # excused only as a tie of the oracle's own deciding quantity (float32 kernels against float64)
+                k = min(n, ro["n"])
+                eff = tl[k] + beta * dl[k]
+                if mode == B.GREEDY:
+                    top = np.sort(eff)[-2:]
+                    margin = top[1] - top[0]
+                elif n != ro["n"]:
+                    margin = abs(ro["r"][k] - ro["ratios"][k])
+                else:
+                    u = philox.vocab_uniforms(seed, seq, step_idx, k + 1, philox.PURPOSE_NEXT, V)
+                    if k == gamma:
+                        keys = eff + philox.gumbel(u)
+                    else:
+                        with np.errstate(divide="ignore"):
+                            keys = np.log(po.residual_dist(po.softmax(eff), po.softmax(dl[k]))) + philox.gumbel(u)
+                    top = np.sort(keys[np.isfinite(keys)])[-2:]
+                    margin = top[1] - top[0]
+                assert margin < 1e-3, (gamma, V, beta, same, (n, z), (ro["n"], ro["z"]), margin)
+            if same and mode == B.SAMPLE:
+                assert ro["n"] == gamma          # p == q: every ratio is 1
+    assert seen_bonus
