@@ -131,34 +131,31 @@ __device__ __forceinline__ void store_packed4(_Float16* __restrict__ xp, int MT_
 }
 
 // x = E[token]; operand = f16(x * g); ssq slot 0 = sum x^2; the row's accumulators of the other slots are cleared.
-// cos/sin of row r's absolute position for the model's rotation frequencies, evaluated in double
-__device__ __forceinline__ void rope_row(float* __restrict__ tab, int r, int pos, int hd, float theta) {
-  const int half = hd >> 1;
-  for (int j = threadIdx.x; j < half; j += blockDim.x) {
-    const double inv = pow((double)theta, -2.0 * (double)j / (double)hd);
-    double sn, cs;
-    sincos((double)pos * inv, &sn, &cs);
-    tab[((size_t)r * half + j) * 2] = (float)cs;
-    tab[((size_t)r * half + j) * 2 + 1] = (float)sn;
-  }
+// cos/sin of every absolute position for a model's rotation frequencies, evaluated in double and rounded once:
+// tab[pos][j] = (cos, sin)(pos * theta^(-2j/hd)).  Filled when the workspace is bound; the QKV epilogue reads the
+// row of a token's position.  grid = max_seq, block = hd/2
+__global__ void rope_positions_kernel(float* __restrict__ tab, int hd, float theta) {
+  const int pos = blockIdx.x, j = threadIdx.x, half = hd >> 1;
+  if (j >= half) return;
+  const double inv = pow((double)theta, -2.0 * (double)j / (double)hd);
+  double sn, cs;
+  sincos((double)pos * inv, &sn, &cs);
+  tab[((size_t)pos * half + j) * 2] = (float)cs;
+  tab[((size_t)pos * half + j) * 2 + 1] = (float)sn;
 }
 
 __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __restrict__ tokens, const int* __restrict__ draft_tok,
                                  SeqRows sr, int max_seq, int G1, int d, float* __restrict__ x, int ldx, const float* __restrict__ g,
-                                 _Float16* __restrict__ xp, int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride,
-                                 float* __restrict__ rope, int hd, float theta) {
+                                 _Float16* __restrict__ xp, int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   const int si = find_seq(sr, r);
   const int s = sr.seq[si];
   const int p = sr.pos0[si] + (r - sr.row_off[si]);
-  // the token id first: the rotation table's double-precision arithmetic then runs while that load (and the
-  // embedding row's, which depends on it) is in flight
   const int tok = p < sr.len[si] ? tokens[(size_t)s * max_seq + p] : draft_tok[s * G1 + (p - sr.len[si])];
   const uint16_t* e = E + (size_t)tok * d;
   uint2 w0 = {0u, 0u};
   if ((int)threadIdx.x * 4 < d) w0 = *reinterpret_cast<const uint2*>(e + threadIdx.x * 4);
-  rope_row(rope, r, p, hd, theta);
   float ss = 0.f;
   for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
     const uint2 w = k == (int)threadIdx.x * 4 ? w0 : *reinterpret_cast<const uint2*>(e + k);
@@ -175,17 +172,15 @@ __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __re
 // input rows of the pre-verification layer: x = hidden + PosEmb[e]; operand and ssq as above
 __global__ void mb_input_w16_kernel(const float* __restrict__ src, int lds, const float* __restrict__ posemb, SeqRows sr, MbRows mr,
                                     int d, float* __restrict__ x, int ldx, const float* __restrict__ g, _Float16* __restrict__ xp,
-                                    int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride, float* __restrict__ rope,
-                                    int hd, float theta) {
+                                    int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   const int si = find_seq(sr, r);
   const int rr = r - sr.row_off[si];
   const float* h = src + (size_t)(mr.src_row0[si] + rr) * lds;
   const float* e = posemb + (size_t)(mr.e0[si] < 0 ? 0 : mr.e0[si] + rr) * d;
-  float4 a0 = {0.f, 0.f, 0.f, 0.f}, b0 = a0;          // first chunk requested before the rotation table's arithmetic
+  float4 a0 = {0.f, 0.f, 0.f, 0.f}, b0 = a0;
   if ((int)threadIdx.x * 4 < d) { a0 = *reinterpret_cast<const float4*>(h + threadIdx.x * 4); b0 = *reinterpret_cast<const float4*>(e + threadIdx.x * 4); }
-  rope_row(rope, r, sr.pos0[si] + rr, hd, theta);
   float ss = 0.f;
   for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
     const bool first = k == (int)threadIdx.x * 4;
@@ -233,7 +228,7 @@ struct GemmArgs {
   u64* ssq_out;
   _Float16* qp;          // QKV: attention operand [slot][head][kt][2][lane][8]
   _Float16* kv;          // QKV: cache base of the model
-  const float* rope;     // QKV: [R][hd/2][2] cos, sin
+  const float* rope;     // QKV: the model's table [max_seq][hd/2][2] cos, sin by absolute position
   int d, hd, layer, n_layers, max_seq, H;
   // STORE of draft logits: per (row, output tile) candidate of the token choice
   float* pick_val;       // [rows][pick_tiles] best logit (+ Gumbel noise when sampling); null: off
@@ -340,7 +335,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& ga, int nt, int m,
           const int tph = hd >> 4;
           const int h = tq / tph, tt = tq % tph;
           const int j0 = 8 * tt + 4 * g4;                   // rotation pairs j0..j0+3
-          const float* tb = ga.rope + ((size_t)m * half + j0) * 2;
+          const float* tb = ga.rope + ((size_t)pos * half + j0) * 2;
           float va[4], vb[4];
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
@@ -1249,21 +1244,52 @@ __global__ void draft_tail_kernel(const float* __restrict__ x, int ldx, const fl
 }
 
 // pre-verification head on the un-normalised residual rows: z = (x*g*rs) . cls
+// One wave per row of the block; every input of the wave (the row, the gain, both head rows, the row's sums of
+// squares) is requested with 16-byte loads before the first is used: the kernel is one memory round trip, not a chain.
 __global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
                                    int ssq_stride, float inv_dim, float eps, const float* __restrict__ cls, int d, int b, HaltArgs ha,
                                    float* __restrict__ alpha, int* __restrict__ stop, int* __restrict__ host_stop) {
   __shared__ float al[32];
   const int si = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  constexpr int CH = 4;                                 // 16-byte chunks per lane held in registers: d <= 1024
+  const int n4 = d >> 2;
   for (int jj = wv; jj < b; jj += nw) {
     const int r = si * b + jj;
-    const float* xr = x + (size_t)r * ldx;
+    const float4* xr = reinterpret_cast<const float4*>(x + (size_t)r * ldx);
+    const float4* g4 = reinterpret_cast<const float4*>(g);
+    const float4* c0 = reinterpret_cast<const float4*>(cls);
+    const float4* c1 = reinterpret_cast<const float4*>(cls + d);
     float z0 = 0.f, z1 = 0.f;
-    for (int k = lane; k < d; k += 64) {
-      const float v = xr[k] * g[k];
-      z0 += v * cls[k];
-      z1 += v * cls[d + k];
+    u64 sq[SSQ_SUB];
+#pragma unroll
+    for (int i = 0; i < SSQ_SUB; ++i) sq[i] = ssq[(size_t)i * ssq_stride + r];
+    if (n4 <= CH * 64) {
+      float4 xv[CH], gv[CH], a0[CH], a1[CH];
+#pragma unroll
+      for (int u = 0; u < CH; ++u) {
+        const int k = min(lane + 64 * u, n4 - 1);        // a chunk past the end repeats the last one and is not added
+        xv[u] = xr[k]; gv[u] = g4[k]; a0[u] = c0[k]; a1[u] = c1[k];
+      }
+#pragma unroll
+      for (int u = 0; u < CH; ++u) {
+        if (lane + 64 * u < n4) {
+          const float v0 = xv[u].x * gv[u].x, v1 = xv[u].y * gv[u].y, v2 = xv[u].z * gv[u].z, v3 = xv[u].w * gv[u].w;
+          z0 += v0 * a0[u].x + v1 * a0[u].y + v2 * a0[u].z + v3 * a0[u].w;
+          z1 += v0 * a1[u].x + v1 * a1[u].y + v2 * a1[u].z + v3 * a1[u].w;
+        }
+      }
+    } else {
+      for (int k = lane; k < n4; k += 64) {
+        const float4 xv = xr[k], gv = g4[k], a0 = c0[k], a1 = c1[k];
+        const float v0 = xv.x * gv.x, v1 = xv.y * gv.y, v2 = xv.z * gv.z, v3 = xv.w * gv.w;
+        z0 += v0 * a0.x + v1 * a0.y + v2 * a0.z + v3 * a0.w;
+        z1 += v0 * a1.x + v1 * a1.y + v2 * a1.z + v3 * a1.w;
+      }
     }
-    const float rs = row_scale(ssq, ssq_stride, r, inv_dim, eps);
+    u64 t = 0;
+#pragma unroll
+    for (int i = 0; i < SSQ_SUB; ++i) t += sq[i];
+    const float rs = 1.0f / sqrtf((float)t * SSQ_INV_SCALE * inv_dim + eps);
     z0 = wave_sum(z0) * rs;
     z1 = wave_sum(z1) * rs;
     if (lane == 0) al[jj] = 1.0f / (1.0f + expf(z0 - z1));

@@ -71,6 +71,7 @@ struct pacer_ctx {
   float* acc_part = nullptr;   // acceptance: per (slot, row, vocabulary chunk) statistics and candidates
   float *ring = nullptr, *hidden = nullptr, *x = nullptr, *xn = nullptr, *qkv = nullptr, *ao = nullptr, *gu = nullptr,
         *rope = nullptr, *part = nullptr;
+  float* rope_pos[3] = {nullptr, nullptr, nullptr};            // bf16 path: per model, cos/sin of every position (filled at bind time)
   _Float16 *xpA = nullptr, *xpB = nullptr, *qp = nullptr;   // bf16 path: ping-pong f16 operands, attention Q operand
   u64* ssq = nullptr;                                         // bf16 path: row sums of squares, [2*Lmax+1][rcap]
   float* pick_val = nullptr;                                  // bf16 path: per (row, vocab tile) token candidates
@@ -168,6 +169,7 @@ size_t carve(pacer_ctx* c, void* base) {
   c->ao = k.take<float>((size_t)c->rcap * c->dmax);
   c->gu = k.take<float>((size_t)c->rcap * 2 * c->fmax);
   c->rope = k.take<float>((size_t)c->rcap * c->hdmax);
+  for (int w = 0; w < 3; ++w) c->rope_pos[w] = k.take<float>((size_t)c->max_seq * c->m[w].cfg.head_dim);
   c->part = k.take<float>((size_t)c->prows * c->hmax * kMaxChunks * (c->hdmax + 2));
   c->xpA = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);      // hi and lo tiles
   c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);
@@ -564,7 +566,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       ga.inv_dim = 1.0f / d;
       ga.qp = c->qp;
       ga.kv = static_cast<_Float16*>(m.kv);
-      ga.rope = c->rope;
+      ga.rope = c->rope_pos[&m - c->m];
       ga.layer = l;
       ga.nt_begin = kv_only ? d / 16 : 0;
       gemm_w16<EPI_QKV>(c, tag, true, ga, (kv_only ? 2 : 3) * d / 16, d);
@@ -626,7 +628,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
 void embed_w16(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
   PACER_LAUNCH(embed_w16_kernel, dim3(R), dim3(256), 0, c->stream, static_cast<const uint16_t*>(m.embed), c->tokens, c->draft_tok, sr,
                      c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax, m.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq,
-                     2 * m.cfg.n_layers + 1, c->rcap, c->rope, m.cfg.head_dim, m.cfg.rope_theta);
+                     2 * m.cfg.n_layers + 1, c->rcap);
 }
 
 struct PickCfg { int on, mode; uint64_t seed; uint32_t step; };
@@ -717,7 +719,7 @@ void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr
   const Model& mb = c->m[PACER_PREVERIFY];
   if (is_w16(mb)) {
     PACER_LAUNCH(mb_input_w16_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax,
-                       mb.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq, 3, c->rcap, c->rope, mb.cfg.head_dim, mb.cfg.rope_theta);
+                       mb.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq, 3, c->rcap);
     run_layers_w16(c, mb, 1, R, sr, kv_only);
   } else {
     PACER_LAUNCH(mb_input_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax);
@@ -1080,6 +1082,10 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
   carve(c, p);
   HIPCHK(c, hipMemsetAsync(c->sk_cnt, 0, sizeof(unsigned) * kSplitGroups, c->stream));
   HIPCHK(c, hipMemsetAsync(c->att_cnt, 0, sizeof(unsigned) * PK_MAXB * c->hmax * 2, c->stream));
+  for (int w = 0; w < 3; ++w)
+    if (is_w16(c->m[w]))
+      PACER_LAUNCH(rope_positions_kernel, dim3(c->max_seq), dim3(c->m[w].cfg.head_dim / 2), 0, c->stream, c->rope_pos[w], c->m[w].cfg.head_dim,
+                   c->m[w].cfg.rope_theta);
   void* hp = nullptr;
   HIPCHK(c, hipHostMalloc(&hp, sizeof(int) * 4 * PACER_MAX_BATCH, hipHostMallocMapped));
   c->host_res = static_cast<int*>(hp);
