@@ -144,16 +144,18 @@ __global__ void rope_positions_kernel(float* __restrict__ tab, int hd, float the
   tab[((size_t)pos * half + j) * 2 + 1] = (float)sn;
 }
 
-__global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __restrict__ tokens, const int* __restrict__ draft_tok,
-                                 SeqRows sr, int max_seq, int G1, int d, float* __restrict__ x, int ldx, const float* __restrict__ g,
-                                 _Float16* __restrict__ xp, int MT_total, u64* __restrict__ ssq, int n_slots, int slot_stride) {
-  __shared__ float red[16];
-  const int r = blockIdx.x;
-  const int si = find_seq(sr, r);
-  const int s = sr.seq[si];
-  const int p = sr.pos0[si] + (r - sr.row_off[si]);
-  const int tok = p < sr.len[si] ? tokens[(size_t)s * max_seq + p] : draft_tok[s * G1 + (p - sr.len[si])];
-  const uint16_t* e = E + (size_t)tok * d;
+// Row r of a forward's input from embedding row e: x, the first norm's operand f16(x * g) and the row's sums of
+// squares (slot 0 = sum x^2, the other slots cleared).  Called by all threads of a block.
+struct EmbedOut {
+  float* x;              // residual stream rows [.][ldx]
+  int ldx;
+  const float* g;        // gain of the first layer's attention norm
+  _Float16* xp;          // operand of the first GEMM
+  int MT_total;
+  u64* ssq;
+  int n_slots, slot_stride;
+};
+__device__ __forceinline__ void embed_row_w16(const uint16_t* __restrict__ e, int d, int r, const EmbedOut& o, float* red) {
   uint2 w0 = {0u, 0u};
   if ((int)threadIdx.x * 4 < d) w0 = *reinterpret_cast<const uint2*>(e + threadIdx.x * 4);
   float ss = 0.f;
@@ -161,12 +163,23 @@ __global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __re
     const uint2 w = k == (int)threadIdx.x * 4 ? w0 : *reinterpret_cast<const uint2*>(e + k);
     const float v0 = __uint_as_float(w.x << 16), v1 = __uint_as_float(w.x & 0xffff0000u);
     const float v2 = __uint_as_float(w.y << 16), v3 = __uint_as_float(w.y & 0xffff0000u);
-    *reinterpret_cast<float4*>(x + (size_t)r * ldx + k) = make_float4(v0, v1, v2, v3);
-    store_packed4(xp, MT_total, r, k, v0 * g[k], v1 * g[k + 1], v2 * g[k + 2], v3 * g[k + 3]);
+    *reinterpret_cast<float4*>(o.x + (size_t)r * o.ldx + k) = make_float4(v0, v1, v2, v3);
+    store_packed4(o.xp, o.MT_total, r, k, v0 * o.g[k], v1 * o.g[k + 1], v2 * o.g[k + 2], v3 * o.g[k + 3]);
     ss += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
   }
   ss = block_sum(ss, red);
-  ssq_init_row(ssq, n_slots, slot_stride, r, ss);
+  ssq_init_row(o.ssq, o.n_slots, o.slot_stride, r, ss);
+}
+
+__global__ void embed_w16_kernel(const uint16_t* __restrict__ E, const int* __restrict__ tokens, const int* __restrict__ draft_tok,
+                                 SeqRows sr, int max_seq, int G1, int d, EmbedOut out) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  const int si = find_seq(sr, r);
+  const int s = sr.seq[si];
+  const int p = sr.pos0[si] + (r - sr.row_off[si]);
+  const int tok = p < sr.len[si] ? tokens[(size_t)s * max_seq + p] : draft_tok[s * G1 + (p - sr.len[si])];
+  embed_row_w16(E + (size_t)tok * d, d, r, out, red);
 }
 
 // input rows of the pre-verification layer: x = hidden + PosEmb[e]; operand and ssq as above
@@ -1192,12 +1205,16 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
 
 // ------------------------------------------------------------------ tail of a draft forward
 // one block per listed sequence: hidden state h = x * g_final * row_scale into the ring, and the token
-// = best of the per-tile candidates the LM-head GEMM left
-__global__ void draft_tail_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
+// = best of the per-tile candidates the LM-head GEMM left.  With E != null the block goes on to what the next draft
+// step would start with, the embedding of the token it has just chosen (row si of next.x, operand, sums of
+// squares): a launch less per draft step.  The host skips its embedding launch only if that step really comes next.
+__global__ void draft_tail_kernel(const float* x, int ldx, const float* __restrict__ g, const u64* ssq,
                                   int ssq_stride, float inv_dim, float eps, int d, float* __restrict__ hidden, const float* __restrict__ pick_val,
-                                  const int* __restrict__ pick_idx, int pick_tiles, int* __restrict__ draft_tok, PickArgs pa, int G1) {
+                                  const int* __restrict__ pick_idx, int pick_tiles, int* __restrict__ draft_tok, PickArgs pa, int G1,
+                                  const uint16_t* __restrict__ E, EmbedOut next) {
   __shared__ float redv[16];
   __shared__ int redi[16];
+  __shared__ float red[16];
   const int si = blockIdx.x, s = pa.seq[si], j = pa.j[si];
   // every input is requested before anything is used: the kernel is a chain of memory round trips otherwise
   constexpr int XMAX = 8, CMAX = 16;                   // d <= 2048 and <= 4096 candidate tiles stay in registers
@@ -1239,17 +1256,20 @@ __global__ void draft_tail_kernel(const float* __restrict__ x, int ldx, const fl
       if (v > best || (v == best && i < bi)) { best = v; bi = i; }
     }
   }
-  block_argmax(best, bi, redv, redi);
+  block_argmax(best, bi, redv, redi);       // (its barriers also separate the reads of x and ssq above from the writes below)
   if (threadIdx.x == 0) draft_tok[s * G1 + j] = bi;
+  if (E) embed_row_w16(E + (size_t)bi * d, d, si, next, red);
 }
 
 // pre-verification head on the un-normalised residual rows: z = (x*g*rs) . cls
 // One wave per row of the block; every input of the wave (the row, the gain, both head rows, the row's sums of
 // squares) is requested with 16-byte loads before the first is used: the kernel is one memory round trip, not a chain.
-__global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const float* __restrict__ g, const u64* __restrict__ ssq,
+__global__ void mb_head_w16_kernel(const float* x, int ldx, const float* __restrict__ g, const u64* ssq,
                                    int ssq_stride, float inv_dim, float eps, const float* __restrict__ cls, int d, int b, HaltArgs ha,
-                                   float* __restrict__ alpha, int* __restrict__ stop, int* __restrict__ host_stop) {
+                                   float* __restrict__ alpha, int* __restrict__ stop, int* __restrict__ host_stop,
+                                   const uint16_t* __restrict__ E, const int* __restrict__ next_tok, EmbedOut next) {
   __shared__ float al[32];
+  __shared__ float red[16];
   const int si = blockIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
   constexpr int CH = 4;                                 // 16-byte chunks per lane held in registers: d <= 1024
   const int n4 = d >> 2;
@@ -1301,4 +1321,7 @@ __global__ void mb_head_w16_kernel(const float* __restrict__ x, int ldx, const f
     stop[si] = st;
     host_stop[ha.seq[si]] = ha.ticket[si] * 2 + st;
   }
+  // E != null (single-sequence launches only: row 0 of next.x is one of the rows this block has just read): the
+  // embedding of the newest draft token, which the next round's first draft step would start with if drafting goes on
+  if (E) embed_row_w16(E + (size_t)next_tok[0] * d, d, 0, next, red);
 }

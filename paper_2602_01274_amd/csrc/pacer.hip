@@ -87,6 +87,10 @@ struct pacer_ctx {
   int* host_res_dev = nullptr;  // its device alias
   int pv_calls = 0, acc_calls = 0;
   int64_t n_launches = 0;      // kernels enqueued so far
+  // bf16 path: the last kernel of a draft step (or of a single-sequence pre-verification call) has already
+  // written the embedding of the next draft step's input; valid only if exactly that step comes next
+  bool pre_valid = false;
+  int pre_n = 0, pre_seq[PACER_MAX_BATCH] = {0}, pre_j[PACER_MAX_BATCH] = {0};
   bool hip_failed = false;     // a HIP call failed since the hand-over counters were last cleared
   // profiling of the GEMM kernel
   bool prof = false;
@@ -625,10 +629,16 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
   }
 }
 
+// where a forward of model m on R rows expects its embedded input
+EmbedOut embed_out(pacer_ctx* c, const Model& m, int R) {
+  EmbedOut o{};
+  o.x = c->x; o.ldx = c->dmax; o.g = m.attn_norm[0]; o.xp = c->xpA; o.MT_total = (R + 15) / 16;
+  o.ssq = c->ssq; o.n_slots = 2 * m.cfg.n_layers + 1; o.slot_stride = c->rcap;
+  return o;
+}
 void embed_w16(pacer_ctx* c, const Model& m, int R, const SeqRows& sr) {
   PACER_LAUNCH(embed_w16_kernel, dim3(R), dim3(256), 0, c->stream, static_cast<const uint16_t*>(m.embed), c->tokens, c->draft_tok, sr,
-                     c->max_seq, c->G1, m.cfg.d_model, c->x, c->dmax, m.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq,
-                     2 * m.cfg.n_layers + 1, c->rcap);
+               c->max_seq, c->G1, m.cfg.d_model, embed_out(c, m, R));
 }
 
 struct PickCfg { int on, mode; uint64_t seed; uint32_t step; };
@@ -699,6 +709,7 @@ void run_layers_f32(pacer_ctx* c, const Model& m, int R, const SeqRows& sr, bool
 
 // rows -> x (embedding gather) and the decoder stack; `tag` 0 = target model
 void forward_lm(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows& sr, bool cache_only = false) {
+  c->pre_valid = false;      // x, the operand buffers and the sums of squares are about to be overwritten
   if (is_w16(m)) {
     embed_w16(c, m, R, sr);
     run_layers_w16(c, m, tag, R, sr, false, cache_only);
@@ -717,6 +728,7 @@ void lm_head(pacer_ctx* c, const Model& m, int tag, int R, float* out, const Seq
 // M_B over rows whose inputs are src rows + PosEmb; kv_only for prefix rows.
 void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr, const float* src, int lds, bool kv_only) {
   const Model& mb = c->m[PACER_PREVERIFY];
+  c->pre_valid = false;
   if (is_w16(mb)) {
     PACER_LAUNCH(mb_input_w16_kernel, dim3(R), dim3(256), 0, c->stream, src, lds, mb.posemb, sr, mr, mb.cfg.d_model, c->x, c->dmax,
                        mb.attn_norm[0], c->xpA, (R + 15) / 16, c->ssq, 3, c->rcap);
@@ -728,11 +740,15 @@ void run_preverify_rows(pacer_ctx* c, int R, const SeqRows& sr, const MbRows& mr
 }
 
 // the 2-class head, block mean and stop flag for n sequences of b rows each (after run_preverify_rows)
-void preverify_head(pacer_ctx* c, int n, int b, const HaltArgs& ha, float* dev_alpha, int* dev_stop) {
+// next_tok (device, may be null): the newest draft token of the call's single sequence; the head kernel then also
+// embeds it for the next round's first draft step
+void preverify_head(pacer_ctx* c, int n, int b, const HaltArgs& ha, float* dev_alpha, int* dev_stop, const int* next_tok) {
   const Model& mb = c->m[PACER_PREVERIFY];
+  const Model& md = c->m[PACER_DRAFT];
   if (is_w16(mb))
     PACER_LAUNCH(mb_head_w16_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, mb.final_norm, slot(c, 2), c->rcap, 1.0f / mb.cfg.d_model,
-                       mb.cfg.rms_eps, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop, c->host_res_dev + 3 * PACER_MAX_BATCH);
+                 mb.cfg.rms_eps, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop, c->host_res_dev + 3 * PACER_MAX_BATCH,
+                 next_tok ? static_cast<const uint16_t*>(md.embed) : nullptr, next_tok, embed_out(c, md, 1));
   else
     PACER_LAUNCH(mb_head_kernel, dim3(n), dim3(256), 0, c->stream, c->xn, c->kmax, mb.cls, mb.cfg.d_model, b, ha, dev_alpha, dev_stop,
                        c->host_res_dev + 3 * PACER_MAX_BATCH);
@@ -755,12 +771,20 @@ void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int m
   }
   sr.row_off[n] = n;
   if (is_w16(md)) {
-    forward_lm(c, md, 1, n, sr);
+    // the previous draft step's last kernel (or the pre-verification head) has embedded this step's input already
+    bool have = c->pre_valid && c->pre_n == n;
+    for (int i = 0; have && i < n; ++i) have = c->pre_seq[i] == seqs[i] && c->pre_j[i] == j[i];
+    c->pre_valid = false;
+    if (!have) embed_w16(c, md, n, sr);
+    run_layers_w16(c, md, 1, n, sr, false);
     const PickCfg pick{1, mode, seed, (uint32_t)ctr};
     lm_head_w16(c, md, 1, n, c->ring, sr, ROWMAP_RING, &pick);
     PACER_LAUNCH(draft_tail_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
-                       c->rcap, 1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->pick_val, c->pick_idx, md.cfg.vocab / 16,
-                       c->draft_tok, pa, c->G1);
+                 c->rcap, 1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->pick_val, c->pick_idx, md.cfg.vocab / 16,
+                 c->draft_tok, pa, c->G1, static_cast<const uint16_t*>(md.embed), embed_out(c, md, n));
+    c->pre_valid = true;
+    c->pre_n = n;
+    for (int i = 0; i < n; ++i) { c->pre_seq[i] = seqs[i]; c->pre_j[i] = j[i] + 1; }
   } else {
     PACER_LAUNCH((embed_rows_kernel<float>), dim3(n), dim3(256), 0, c->stream, static_cast<const float*>(md.embed), c->tokens,
                        c->draft_tok, sr, c->max_seq, c->G1, md.cfg.d_model, c->x, c->dmax);
@@ -1162,6 +1186,7 @@ int32_t pacer_force_commit(pacer_ctx* c, int32_t s, int32_t from, const int32_t*
   Seq& q = c->seq[s];
   q.pending = false;
   q.in_step = false;
+  c->pre_valid = false;
   q.len = from + n;
   q.gamma = q.mb_done = 0;
   q.verified = -1;
@@ -1186,6 +1211,7 @@ int32_t pacer_begin_step(pacer_ctx* c, int32_t s) {
   q.gamma = q.mb_done = 0;
   q.verified = -1;
   q.in_step = true;
+  c->pre_valid = false;
   return PACER_OK;
 }
 
@@ -1241,7 +1267,17 @@ int32_t pacer_preverify_block(pacer_ctx* c, const int32_t* seqs, int32_t n, floa
   sr.row_off[n] = n * b;
   const Model& mb = c->m[PACER_PREVERIFY];
   run_preverify_rows(c, n * b, sr, mr, c->hidden, mb.cfg.d_model, false);
-  preverify_head(c, n, b, ha, dev_alpha, dev_stop);
+  // one sequence, bf16 models: the head kernel goes on to embed the newest draft token, which is what the next
+  // round's first draft step starts with if drafting goes on (if it stops, the verify pass overwrites it)
+  const Seq& q0 = c->seq[seqs[0]];
+  const bool embed_next = n == 1 && is_w16(mb) && is_w16(c->m[PACER_DRAFT]) && q0.gamma < c->pv.gamma_max;
+  preverify_head(c, n, b, ha, dev_alpha, dev_stop, embed_next ? c->draft_tok + seqs[0] * c->G1 + (q0.gamma - 1) : nullptr);
+  if (embed_next) {
+    c->pre_valid = true;
+    c->pre_n = 1;
+    c->pre_seq[0] = seqs[0];
+    c->pre_j[0] = q0.gamma;
+  }
   for (int i = 0; i < n; ++i) {
     Seq& q = c->seq[seqs[i]];
     q.mb_done += b;
