@@ -293,6 +293,11 @@ def main():
                 traffic = float(line.split("=", 1)[1])
 
     achieved = gemm_bytes / 1e9 / (gemm_ms / 1e3) if gemm_ms > 0 else 0.0
+    # the same bytes at the rate of a kernel that only reads them, one cold launch per matrix (see stream_ceiling)
+    floor_gbps = None
+    fl = ceiling.get("per_launch_read_floor")
+    if fl:
+        floor_gbps = weight_bytes(w["target"], L) / 1e9 / (fl["pass_ms_without_attention"] / 1e3)
     out = {
         "metric": "decode tokens/s (7B-shape target, bs1) + verify-step achieved HBM GB/s",
         "value": round(main_run["tok_s"], 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -321,6 +326,8 @@ def main():
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "frac_of_streaming_read": round(achieved / ceiling["streaming_read_GBps"], 4),
+                     "read_floor_GBps": round(floor_gbps, 1) if floor_gbps else None,
+                     "frac_of_read_floor": round(achieved / floor_gbps, 4) if floor_gbps else None,
                      "launches": int(n_launch), "avg_launch_us": round(1e3 * gemm_ms / max(1, n_launch), 3),
                      "avg_launch_bytes": round(gemm_bytes / max(1, n_launch), 1)},
         "cpu_baseline": cpu,
