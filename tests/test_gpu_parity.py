@@ -100,6 +100,17 @@ def test_mid_bf16_greedy_steps_match_oracle():
     _run("mid", 150, 40, tol_logits=2e-2, tol_alpha=2e-2)
 
 
+def test_mid_config_as_named_full_length(capsys):
+    """Workload `mid` exactly as named: 12-layer d768 target, 2-layer draft, bf16, greedy, beta 3, 128-token prompt,
+    256 new tokens, gamma_max 12, b 4: about 200 teacher-forced steps and 3000 integer decisions against the oracle."""
+    w = synth.workload("mid")
+    assert (w["prompt"], w["new"], w["gamma_max"], w["block"], w["mode"]) == (128, 256, 12, 4, "greedy")
+    ck, gammas, ns = _run("mid", w["prompt"], w["new"], tol_logits=2e-2, tol_alpha=2e-2, gain_jitter=0.0, max_seq=640)
+    with capsys.disabled():
+        print(f"[mid as named] {ck.summary()}", flush=True)
+    assert ck.decisions > 1500
+
+
 def test_kv_buffers_full_of_nans_do_not_matter():
     """Attention reads whole 32-position groups of the cache, including slots past the sequence's end; the
     caller's buffers arrive here with every byte 0xFF (f16 and f32 NaNs) and the results must not change:
@@ -252,6 +263,13 @@ def test_13b_width_four_layers_batch_against_oracle():
     row tiles per block, K slices for the few-tile matrices)."""
     _run_batch("13b_batch", [18, 33, 47, 25, 60, 39, 21, 52, 30, 44, 27, 36],
                [1.0, 2.0, 3.0, 4.0, 5.0, 2.5, 3.5, 1.5, 4.5, 2.0, 3.0, 4.0], 2, 2e-2, 2e-2, max_seq=160, n_layers_target=4)
+
+
+def test_13b_width_ragged_prompts_in_the_named_range():
+    """The batched workload's prompt-length range (256 to 2048 tokens) at its width (d 5120, 40 heads) and a depth the
+    oracle can afford: three sequences of 300, 1100 and 2048 prompt tokens in one ragged verify launch (different
+    numbers of 512-row prompt passes, different key ranges per sequence in one attention launch), per-sequence beta."""
+    _run_batch("13b_batch", [300, 1100, 2048], [1.5, 3.0, 4.5], 2, 2e-2, 2e-2, max_seq=2176, n_layers_target=2)
 
 
 def test_13b_width_ten_full_windows_six_row_tiles_per_block():
