@@ -203,7 +203,8 @@ int32_t pacer_wait_stop(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, int
  * kernels, same results); the loop runs inside the library so that between two rounds the host does nothing but
  * read the kernel-written flag words and enqueue.  mode, rng_seed, rng_ctr as in pacer_draft_step.  dev_alpha
  * [n_seqs][block] and dev_stop [n_seqs] are the outputs of the pre-verification calls (on return: of the last round,
- * for the sequences that took part in it, in list order).  host_gamma[n_seqs] (host array) receives the windows. */
+ * for the sequences that took part in it, in list order).  host_gamma[n_seqs] (host array) receives the windows.
+ * If a call inside the loop fails, its status is returned and the sequences keep the drafts made so far. */
 int32_t pacer_draft_window(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, int32_t mode, uint64_t rng_seed,
                            uint64_t rng_ctr, float* dev_alpha, int32_t* dev_stop, int32_t* host_gamma);
 

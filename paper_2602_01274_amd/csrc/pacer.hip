@@ -71,7 +71,7 @@ struct pacer_ctx {
   float* acc_part = nullptr;   // acceptance: per (slot, row, vocabulary chunk) statistics and candidates
   float *ring = nullptr, *hidden = nullptr, *x = nullptr, *xn = nullptr, *qkv = nullptr, *ao = nullptr, *gu = nullptr,
         *rope = nullptr, *part = nullptr;
-  float* rope_pos[3] = {nullptr, nullptr, nullptr};            // bf16 path: per model, cos/sin of every position (filled at bind time)
+  float* rope_pos[2] = {nullptr, nullptr};   // bf16 path: cos/sin of every position, [0] target, [1] draft and M_B (same head size and theta); filled at bind time
   _Float16 *xpA = nullptr, *xpB = nullptr, *qp = nullptr;   // bf16 path: ping-pong f16 operands, attention Q operand
   u64* ssq = nullptr;                                         // bf16 path: row sums of squares, [2*Lmax+1][rcap]
   float* pick_val = nullptr;                                  // bf16 path: per (row, vocab tile) token candidates
@@ -173,7 +173,7 @@ size_t carve(pacer_ctx* c, void* base) {
   c->ao = k.take<float>((size_t)c->rcap * c->dmax);
   c->gu = k.take<float>((size_t)c->rcap * 2 * c->fmax);
   c->rope = k.take<float>((size_t)c->rcap * c->hdmax);
-  for (int w = 0; w < 3; ++w) c->rope_pos[w] = k.take<float>((size_t)c->max_seq * c->m[w].cfg.head_dim);
+  for (int w = 0; w < 2; ++w) c->rope_pos[w] = k.take<float>((size_t)c->max_seq * c->m[w].cfg.head_dim);
   c->part = k.take<float>((size_t)c->prows * c->hmax * kMaxChunks * (c->hdmax + 2));
   c->xpA = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);      // hi and lo tiles
   c->xpB = k.take<_Float16>((size_t)(c->kmax / 8 + 4) * mtcap * 16 * 8 * 2);
@@ -570,7 +570,7 @@ void run_layers_w16(pacer_ctx* c, const Model& m, int tag, int R, const SeqRows&
       ga.inv_dim = 1.0f / d;
       ga.qp = c->qp;
       ga.kv = static_cast<_Float16*>(m.kv);
-      ga.rope = c->rope_pos[&m - c->m];
+      ga.rope = c->rope_pos[tag == 0 ? PACER_TARGET : PACER_DRAFT];
       ga.layer = l;
       ga.nt_begin = kv_only ? d / 16 : 0;
       gemm_w16<EPI_QKV>(c, tag, true, ga, (kv_only ? 2 : 3) * d / 16, d);
@@ -1106,7 +1106,7 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
   carve(c, p);
   HIPCHK(c, hipMemsetAsync(c->sk_cnt, 0, sizeof(unsigned) * kSplitGroups, c->stream));
   HIPCHK(c, hipMemsetAsync(c->att_cnt, 0, sizeof(unsigned) * PK_MAXB * c->hmax * 2, c->stream));
-  for (int w = 0; w < 3; ++w)
+  for (int w = 0; w < 2; ++w)
     if (is_w16(c->m[w]))
       PACER_LAUNCH(rope_positions_kernel, dim3(c->max_seq), dim3(c->m[w].cfg.head_dim / 2), 0, c->stream, c->rope_pos[w], c->m[w].cfg.head_dim,
                    c->m[w].cfg.rope_theta);
