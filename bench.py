@@ -49,8 +49,8 @@ def run_steps(sess, n, mode, seed, batch=None, **kw):
                     accepted[i] += 1 if r["n"] > i else 0
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    return dict(tokens=toks, seconds=dt, tok_s=toks / dt, ms_per_step=1e3 * dt / n,
-                mean_gamma=gam / cnt, tau=acc / cnt, reached=reached, accepted=accepted)
+    return dict(tokens=toks, seconds=dt, tok_s=toks / dt, ms_per_step=1e3 * dt / max(n, 1),
+                mean_gamma=gam / max(cnt, 1), tau=acc / max(cnt, 1), reached=reached, accepted=accepted)
 
 
 def cpu_baseline(w, tgt, drf, mb, prompt, mode, budget_steps=2, threads=None):
