@@ -212,7 +212,10 @@ int32_t pacer_draft_window(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs, 
  * against its KV cache (appending those rows).  gamma = number of drafts since
  * pacer_begin_step, or gamma_override[s] if gamma_override != NULL and >= 0 (host array; must
  * not exceed the number of drafts made).  Writes f32 logits to
- * dev_logits[n_seqs][gamma_max+1][vocab] (rows beyond gamma+1 are left untouched). */
+ * dev_logits[n_seqs][gamma_max+1][vocab] (rows beyond gamma+1 are left untouched).
+ * The call only enqueues kernels on the context's stream (no allocation, no memset, no host
+ * wait) and writes the same cache and logits rows when repeated, so it may be recorded by a
+ * stream capture and replayed; positions and row counts are those of the recorded call. */
 int32_t pacer_verify(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seqs,
                      const int32_t* gamma_override, float* dev_logits);
 

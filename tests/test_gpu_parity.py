@@ -488,6 +488,47 @@ def test_verify_twice_gives_the_same_bits_batched_13b_width():
     s.close()
 
 
+def test_verify_can_be_captured_into_a_hip_graph():
+    """pacer_verify only enqueues kernels on the context's stream (no allocation, no memset, no host wait), so a
+    caller may capture it.  Captured on a side stream, the graph is replayed several times with eager passes and
+    synchronisations between the replays; every replay must reproduce the eager bits (a pass writes the same
+    cache rows and the same logits rows again).  A draft step is not replayed here: its last kernel already
+    embeds the token it chose into the buffer the step started from, so the same step cannot run twice."""
+    from paper_2602_01274_amd import binding as B
+    w = synth.workload("7b")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        tgt, drf, mb = synth.make_pair(w, seed=0, gain_jitter=0.1, n_layers_target=3)
+        s = _session(w, tgt, drf, mb, 768)
+        s.prefill(synth.make_prompt(w["target"]["vocab"], 600, 1).tolist())
+        for gamma in (12, 16):
+            B.pacer_begin_step(s.ctx, 0)
+            for _ in range(gamma):
+                B.pacer_draft_step(s.ctx, [0], B.GREEDY, 0, s.step_idx[0])
+            B.pacer_verify(s.ctx, [0], None, s.logits)
+            torch.cuda.synchronize()
+            first = s.logits[0, :gamma + 1].clone()
+            assert torch.isfinite(first).all()
+            gv = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gv, stream=side):
+                B.pacer_verify(s.ctx, [0], None, s.logits)
+            for rep in range(3):
+                s.logits.zero_()
+                gv.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(first, s.logits[0, :gamma + 1]), f"gamma {gamma}: graph replay {rep} differs from the eager pass"
+                s.logits.zero_()
+                B.pacer_verify(s.ctx, [0], None, s.logits)                # eager work between the replays
+                torch.cuda.synchronize()
+                assert torch.equal(first, s.logits[0, :gamma + 1])
+            del gv
+            B.pacer_accept_rollback(s.ctx, [0], B.GREEDY, [w["beta"]], 0, s.step_idx[0], s.logits, s.n_acc, s.next_tok)
+            st = B.pacer_get_state(s.ctx, 0)
+            assert 0 <= st["n_accepted"] <= gamma
+            s.step_idx[0] += 1
+        s.close()
+
+
 def test_wait_stop_and_get_state_match_the_device_buffers():
     """The host-polled words (stop flags, accept results) carry what the kernels wrote to the caller's
     device buffers, call after call, also across a re-prefill (tickets are never reused)."""
