@@ -41,6 +41,7 @@ extern "C" {
 #define PACER_ESTATE (-2)     /* call out of order, tensor / cache / workspace not bound          */
 #define PACER_EOVERFLOW (-3)  /* KV capacity (max_seq) or gamma_max would be exceeded             */
 #define PACER_EHIP (-4)       /* the HIP runtime reported an error                                */
+#define PACER_ENUMERIC (-5)   /* a token id outside the vocabulary was met on the device (pacer_prefill) */
 
 #define PACER_F32 0
 #define PACER_BF16 1
@@ -145,7 +146,15 @@ int32_t pacer_bind_workspace(pacer_ctx* ctx, void* dev_ptr, uint64_t nbytes);
 /* Prompt ingestion (support; Alg. 1 takes the prefix as given).  Resets sequence `seq` to the
  * committed tokens dev_tokens[0..n-1], n >= 1, and fills the three caches for positions
  * 0..n-2 (M_B with prefix rows), 512 positions per pass through the weights.  The workspace
- * is sized for such a pass whatever max_batch is. */
+ * is sized for such a pass whatever max_batch is.
+ * Token ids live on the device, so this call cannot refuse a bad one.  Instead no kernel ever
+ * uses an id outside [0, vocab) as an index: the copy of the prompt, and every kernel that
+ * chooses a token (an argmax over logits without a finite value has no winner), replaces such an
+ * id by the nearest valid one and sets a word for the sequence in pinned host memory.  The
+ * sequence's next pacer_wait_stop, pacer_get_state or pacer_begin_step then returns
+ * PACER_ENUMERIC and the sequence takes no further step until it is prefilled again.  (A used
+ * sequence's prefill waits for the stream first, so that no earlier kernel reports into the new
+ * prompt's word.) */
 int32_t pacer_prefill(pacer_ctx* ctx, int32_t seq, const int32_t* dev_tokens, int32_t n);
 
 /* Debug / teacher forcing: replace the committed tokens of `seq` from position `from` on with
@@ -253,7 +262,9 @@ int32_t pacer_accept_rollback(pacer_ctx* ctx, const int32_t* seqs, int32_t n_seq
  *   bonus_row         nonzero: if every draft is accepted the new token is taken from row gamma of both logits
  *                     buffers; zero: that case yields next token -1 and the caller evaluates the bonus row later
  *   beta, mode, rng_seed, rng_ctr, seq      as in pacer_accept_rollback (seq 0..PACER_MAX_BATCH-1 keys the random streams)
- *   dev_n_accepted[1], dev_next_token[1]    results (device memory, valid after the stream has passed the call)
+ *   dev_n_accepted[1], dev_next_token[1]    results (device memory, valid after the stream has passed the call);
+ *                     next token 0x7fffffff: the logits that decide it held no finite value.  A draft token id
+ *                     outside [0, vocab) is read as the nearest valid id (it never indexes past a logits row)
  * gamma may be 0..PACER_NOALLOC_MAX_GAMMA; a larger gamma is refused with PACER_EOVERFLOW.  Nothing but the two
  * results is written: no tokens are committed and no cache length changes.  The device that is current when the
  * call is made must be the one hip_stream belongs to; on the first call on a device the library looks up that

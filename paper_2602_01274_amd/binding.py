@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # PACER_LIB: another build of the same library (e.g. one compiled with -DPACER_FENCED_HANDOVER, to compare)
 LIB_PATH = os.environ.get("PACER_LIB") or os.path.join(_HERE, "libpacer.so")
 
-OK, EINVAL, ESTATE, EOVERFLOW, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, ESTATE, EOVERFLOW, EHIP, ENUMERIC = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 TARGET, DRAFT, PREVERIFY = 0, 1, 2
 GREEDY, SAMPLE = 0, 1

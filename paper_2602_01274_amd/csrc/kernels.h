@@ -135,6 +135,24 @@ __device__ __forceinline__ uint4 vocab_bits(uint64_t seed, int seq, uint32_t ste
   return philox4x32_10(make_uint4(blk, row, step, purpose | ((uint32_t)seq << 8)), (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
+// ------------------------------------------------------------------ token ids as table indices
+// A token id that is about to be stored, or used as an index, is checked against the vocabulary first.  An argmax
+// over logits that held no finite value leaves the sentinel 0x7fffffff, and a caller may hand in anything: such an
+// id is replaced by the nearest valid one, so that no later load leaves its table, and the sequence's word in
+// pinned host memory (host_bad, may be null) is set, which the host turns into an error at its next read-back.
+__device__ __forceinline__ int checked_token(int tok, int V, int* host_bad, int seq) {
+  if ((unsigned)tok < (unsigned)V) return tok;
+  if (host_bad) {
+    host_bad[seq] = 1;
+    __threadfence_system();
+  }
+  return tok < 0 ? 0 : V - 1;
+}
+// prompt tokens into the sequence's token buffer
+__global__ void copy_tokens_kernel(int* __restrict__ dst, const int* __restrict__ src, int n, int V, int* host_bad, int seq) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = checked_token(src[i], V, host_bad, seq);
+}
+
 // ------------------------------------------------------------------ embedding gather
 // token of (sequence, position): committed token below len, else the draft made at that position
 template <typename T>
@@ -471,7 +489,7 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int n_chunks
 // one block per listed sequence: y = argmax(logits) or Gumbel-max sample; row j of the ring
 struct PickArgs { int n_seqs; int seq[PK_MAXB]; int j[PK_MAXB]; };
 __global__ __launch_bounds__(1024) void pick_token_kernel(const float* __restrict__ ring, int* __restrict__ draft_tok, PickArgs pa,
-                                                          int G1, int V, int mode, uint64_t seed, uint32_t step) {
+                                                          int G1, int V, int mode, uint64_t seed, uint32_t step, int* host_bad) {
   __shared__ float redv[16];
   __shared__ int redi[16];
   const int si = blockIdx.x, s = pa.seq[si], j = pa.j[si];
@@ -494,7 +512,7 @@ __global__ __launch_bounds__(1024) void pick_token_kernel(const float* __restric
     }
   }
   block_argmax(best, bi, redv, redi);
-  if (threadIdx.x == 0) draft_tok[s * G1 + j] = bi;
+  if (threadIdx.x == 0) draft_tok[s * G1 + j] = checked_token(bi, V, host_bad, s);
 }
 
 // ------------------------------------------------------------------ pre-verification head + halting test
@@ -670,7 +688,8 @@ __global__ __launch_bounds__(256) void accept_rows_kernel(const float* __restric
     if (ch == 0) {
       int rj = 0;
       if (i < gamma) {
-        const float ratio = expf((t[y] + beta * q[y] - lsp) - (q[y] - lsq));
+        const int yc = min(max(y, 0), V - 1);          // a caller-held draft id outside the vocabulary must not index past the row
+        const float ratio = expf((t[yc] + beta * q[yc] - lsp) - (q[yc] - lsq));
         const uint4 b = vocab_bits(seed, s, step, (uint32_t)(i + 1), PURPOSE_ACCEPT, 0u);
         rj = (u01(b.x) > ratio) ? 1 : 0;
       }
@@ -688,7 +707,7 @@ __global__ __launch_bounds__(256) void accept_rows_kernel(const float* __restric
 __global__ void accept_finalize_kernel(const float* __restrict__ part, const int* __restrict__ rej, const int* __restrict__ draft_tok,
                                        AccArgs aa, int G1, int mode, int phase, int max_seq, int* __restrict__ tokens,
                                        int* __restrict__ out_n, int* __restrict__ out_z, int* __restrict__ host_res,
-                                       int* __restrict__ host_tick, int ticket, int skip_done) {
+                                       int* __restrict__ host_tick, int ticket, int skip_done, int V, int* host_bad) {
   const int si = blockIdx.x, s = aa.seq[si], sl = aa.slot[si], qs = aa.qslot[si];
   const int gamma = aa.gamma[si];
   if (phase && skip_done && out_z[sl] >= 0) return;
@@ -730,7 +749,7 @@ __global__ void accept_finalize_kernel(const float* __restrict__ part, const int
   if (!phase && tk)
     for (int k = threadIdx.x; k < n; k += blockDim.x) tk[k] = draft_tok[qs * G1 + k];
   if (threadIdx.x == 0) {
-    if (z >= 0 && tk) tk[n] = z;
+    if (z >= 0 && tk) tk[n] = checked_token(z, V, host_bad, s);   // out_z keeps the raw value: 0x7fffffff = no finite logit decided
     out_n[sl] = n;
     out_z[sl] = z;
     if (host_res) {

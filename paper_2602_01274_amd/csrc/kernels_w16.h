@@ -1211,7 +1211,7 @@ __global__ __launch_bounds__(512) void attn_mfma_kernel(const _Float16* __restri
 __global__ void draft_tail_kernel(const float* x, int ldx, const float* __restrict__ g, const u64* ssq,
                                   int ssq_stride, float inv_dim, float eps, int d, float* __restrict__ hidden, const float* __restrict__ pick_val,
                                   const int* __restrict__ pick_idx, int pick_tiles, int* __restrict__ draft_tok, PickArgs pa, int G1,
-                                  const uint16_t* __restrict__ E, EmbedOut next) {
+                                  const uint16_t* __restrict__ E, EmbedOut next, int V, int* host_bad) {
   __shared__ float redv[16];
   __shared__ int redi[16];
   __shared__ float red[16];
@@ -1257,6 +1257,7 @@ __global__ void draft_tail_kernel(const float* x, int ldx, const float* __restri
     }
   }
   block_argmax(best, bi, redv, redi);       // (its barriers also separate the reads of x and ssq above from the writes below)
+  bi = checked_token(bi, V, threadIdx.x == 0 ? host_bad : nullptr, s);   // candidates without a finite value leave the sentinel
   if (threadIdx.x == 0) draft_tok[s * G1 + j] = bi;
   if (E) embed_row_w16(E + (size_t)bi * d, d, si, next, red);
 }

@@ -43,6 +43,7 @@ struct Seq {
   float t = 0.f;      // current threshold
   bool pending = false;
   bool in_step = false;
+  bool broken = false;   // a token id outside the vocabulary was met on the device: closed until the next prefill
   int last_n = -1, last_z = -1;
   int pv_ticket = 0;   // number of the last pre-verification call that covered this sequence (the kernel echoes it next to the stop flag)
   int acc_ticket = 0;  // number of the last accept call that covered it
@@ -99,6 +100,11 @@ struct pacer_ctx {
   int n_ev = 0;
   double prof_bytes = 0.0;
 };
+
+namespace {
+// one word per sequence in pinned host memory (device alias): set by a kernel that met a token id outside the vocabulary
+inline int* host_bad_dev(pacer_ctx* c) { return c->host_res_dev + 4 * PACER_MAX_BATCH; }
+}  // namespace
 
 namespace {
 
@@ -781,7 +787,7 @@ void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int m
     lm_head_w16(c, md, 1, n, c->ring, sr, ROWMAP_RING, &pick);
     PACER_LAUNCH(draft_tail_kernel, dim3(n), dim3(256), 0, c->stream, c->x, c->dmax, md.final_norm, slot(c, 2 * md.cfg.n_layers),
                  c->rcap, 1.0f / md.cfg.d_model, md.cfg.rms_eps, md.cfg.d_model, c->hidden, c->pick_val, c->pick_idx, md.cfg.vocab / 16,
-                 c->draft_tok, pa, c->G1, static_cast<const uint16_t*>(md.embed), embed_out(c, md, n));
+                 c->draft_tok, pa, c->G1, static_cast<const uint16_t*>(md.embed), embed_out(c, md, n), md.cfg.vocab, host_bad_dev(c));
     c->pre_valid = true;
     c->pre_n = n;
     for (int i = 0; i < n; ++i) { c->pre_seq[i] = seqs[i]; c->pre_j[i] = j[i] + 1; }
@@ -791,7 +797,7 @@ void draft_forward(pacer_ctx* c, const int32_t* seqs, int n, const int* j, int m
     run_layers_f32(c, md, n, sr, false, c->hidden);
     lm_head(c, md, 1, n, c->ring, sr, ROWMAP_RING);
     PACER_LAUNCH(pick_token_kernel, dim3(n), dim3(1024), 0, c->stream, c->ring, c->draft_tok, pa, c->G1, md.cfg.vocab, mode, seed,
-                       (uint32_t)ctr);
+                       (uint32_t)ctr, host_bad_dev(c));
   }
 }
 
@@ -807,6 +813,19 @@ int wait_ticket(pacer_ctx* c, const int* p, int ticket, int shift) {
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if ((*v >> shift) == ticket) return PACER_OK;
   return fail(c, PACER_EHIP, "a kernel's result did not reach host memory (ticket %d, found %d)", ticket, *v >> shift);
+}
+
+// Has a kernel reported, for sequence s, a token id outside the vocabulary (a prompt token, or a token chosen from
+// logits without a finite value)?  The id was replaced by a valid one on the device, so nothing faulted, but the
+// sequence's state is meaningless from there on: the sequence is closed until its next pacer_prefill.
+int check_numeric(pacer_ctx* c, int s) {
+  Seq& q = c->seq[s];
+  if (!q.broken && !c->host_res[4 * PACER_MAX_BATCH + s]) return PACER_OK;
+  q.pending = false;
+  q.in_step = false;
+  q.broken = true;
+  return fail(c, PACER_ENUMERIC, "sequence %d: a token id outside the vocabulary was met (a prompt token out of range, or logits "
+              "without a finite value); prefill the sequence again", s);
 }
 
 // M_B prefix rows (PosEmb row 0, K/V only) for positions no pre-verification call covered: the drafts beyond
@@ -848,7 +867,8 @@ void accept_launch(pacer_ctx* c, const AccArgs& aa, int rows, int phase, int mod
                  (uint32_t)ctr, phase, c->acc_part, c->rej, (const int*)nullptr);
   }
   PACER_LAUNCH(accept_finalize_kernel, dim3(aa.n_seqs), dim3(64), 0, c->stream, c->acc_part, c->rej, c->draft_tok, aa, c->G1, mode,
-               phase, c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev, c->host_res_dev + 2 * PACER_MAX_BATCH, ++c->acc_calls, 0);
+               phase, c->max_seq, c->tokens, dev_n, dev_z, c->host_res_dev, c->host_res_dev + 2 * PACER_MAX_BATCH, ++c->acc_calls, 0, V,
+               host_bad_dev(c));
   for (int i = 0; i < aa.n_seqs; ++i) c->seq[aa.seq[i]].acc_ticket = c->acc_calls;
 }
 
@@ -898,8 +918,9 @@ int fold(pacer_ctx* c, int s) {
     o.last_z = c->host_res[2 * i + 1];
     o.len += o.last_n + 1;
     o.pending = false;
+    if (c->host_res[4 * PACER_MAX_BATCH + i]) o.broken = true;   // reported by the sequence's own next call
   }
-  return PACER_OK;
+  return check_numeric(c, s);
 }
 
 // ---- acceptance without a context and without any allocation ---------------------------------
@@ -1111,9 +1132,9 @@ int32_t pacer_bind_workspace(pacer_ctx* c, void* p, uint64_t nbytes) {
       PACER_LAUNCH(rope_positions_kernel, dim3(c->max_seq), dim3(c->m[w].cfg.head_dim / 2), 0, c->stream, c->rope_pos[w], c->m[w].cfg.head_dim,
                    c->m[w].cfg.rope_theta);
   void* hp = nullptr;
-  HIPCHK(c, hipHostMalloc(&hp, sizeof(int) * 4 * PACER_MAX_BATCH, hipHostMallocMapped));
+  HIPCHK(c, hipHostMalloc(&hp, sizeof(int) * 5 * PACER_MAX_BATCH, hipHostMallocMapped));
   c->host_res = static_cast<int*>(hp);
-  for (int i = 0; i < 4 * PACER_MAX_BATCH; ++i) c->host_res[i] = 0;
+  for (int i = 0; i < 5 * PACER_MAX_BATCH; ++i) c->host_res[i] = 0;
   void* dp = nullptr;
   HIPCHK(c, hipHostGetDevicePointer(&dp, hp, 0));
   c->host_res_dev = static_cast<int*>(dp);
@@ -1142,9 +1163,14 @@ int32_t pacer_prefill(pacer_ctx* c, int32_t s, const int32_t* dev_tokens, int32_
   if (s < 0 || s >= c->max_batch || !dev_tokens || n < 1) return fail(c, PACER_EINVAL, "prefill: bad arguments");
   if (n + c->G1 + 1 > c->max_seq) return fail(c, PACER_EOVERFLOW, "prefill: %d tokens leave no room for a step (max_seq %d)", n, c->max_seq);
   Seq& q = c->seq[s];
+  const bool q_was_used = q.len > 0;
   q = Seq();
   q.len = n;
-  PACER_LAUNCH(copy_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->tokens + (size_t)s * c->max_seq, dev_tokens, n);
+  // a sequence that was in use may still have kernels in flight that report into its word: let them finish, then clear it
+  if (q_was_used) HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->host_res[4 * PACER_MAX_BATCH + s] = 0;
+  PACER_LAUNCH(copy_tokens_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->tokens + (size_t)s * c->max_seq, dev_tokens, n,
+               c->m[PACER_TARGET].cfg.vocab, host_bad_dev(c), s);
   // up to 16 slots of 32 consecutive positions per pass: one trip through the weights per 512 prompt tokens
   for (int p0 = 0; p0 < n - 1; p0 += kPrefillRows) {
     const int R = std::min(kPrefillRows, n - 1 - p0);
@@ -1181,6 +1207,9 @@ int32_t pacer_force_commit(pacer_ctx* c, int32_t s, int32_t from, const int32_t*
   if (!c->ws_bound) return fail(c, PACER_ESTATE, "workspace not bound");
   if (s < 0 || s >= c->max_batch || !host_tokens || n < 1 || from < 0) return fail(c, PACER_EINVAL, "force_commit: bad arguments");
   if (from + n + c->G1 + 1 > c->max_seq) return fail(c, PACER_EOVERFLOW, "force_commit: beyond max_seq");
+  for (int i = 0; i < n; ++i)
+    if (host_tokens[i] < 0 || host_tokens[i] >= c->m[PACER_TARGET].cfg.vocab)
+      return fail(c, PACER_EINVAL, "force_commit: token %d (index %d) is outside the vocabulary", host_tokens[i], i);
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(c->tokens + (size_t)s * c->max_seq + from, host_tokens, sizeof(int) * n, hipMemcpyHostToDevice));
   Seq& q = c->seq[s];
@@ -1204,6 +1233,7 @@ int32_t pacer_begin_step(pacer_ctx* c, int32_t s) {
     HIPCHK(c, hipMemsetAsync(c->att_cnt, 0, sizeof(unsigned) * PK_MAXB * c->hmax * 2, c->stream));
   }
   if (int rc = fold(c, s)) return rc;
+  if (int rc = check_numeric(c, s)) return rc;
   Seq& q = c->seq[s];
   if (q.len < 1) return fail(c, PACER_ESTATE, "begin_step: sequence %d has no committed tokens (prefill first)", s);
   if (q.len + c->G1 + 1 > c->max_seq) return fail(c, PACER_EOVERFLOW, "begin_step: sequence %d is full", s);
@@ -1307,6 +1337,8 @@ int32_t pacer_wait_stop(pacer_ctx* c, const int32_t* seqs, int32_t n, int32_t* h
     if (int rc = wait_ticket(c, p, q.pv_ticket, 1)) return rc;
     host_stop[i] = *p & 1;
   }
+  for (int i = 0; i < n; ++i)
+    if (int rc = check_numeric(c, seqs[i])) return rc;
   return PACER_OK;
 }
 
@@ -1449,7 +1481,7 @@ int32_t pacer_accept_noalloc(const float* dev_target_logits, const float* dev_dr
                          seed, (uint32_t)ctr, phase, sc->part, sc->rej, done);
     }
     hipLaunchKernelGGL(accept_finalize_kernel, dim3(1), dim3(64), 0, st, sc->part, sc->rej, dev_draft_tokens, aa, G1, mode, phase, 0,
-                       (int*)nullptr, dev_n, dev_z, (int*)nullptr, (int*)nullptr, 0, 1);
+                       (int*)nullptr, dev_n, dev_z, (int*)nullptr, (int*)nullptr, 0, 1, vocab, (int*)nullptr);
   }
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_noctx(PACER_EHIP, "accept_noalloc: %s", hipGetErrorString(e));
@@ -1461,6 +1493,7 @@ int32_t pacer_get_state(pacer_ctx* c, int32_t s, int32_t* gamma, int32_t* len, f
   if (s < 0 || s >= c->max_batch) return fail(c, PACER_EINVAL, "get_state: sequence id %d out of range", s);
   if (c->ws_bound) {
     if (int rc = fold(c, s)) return rc;
+    if (int rc = check_numeric(c, s)) return rc;
   }
   const Seq& q = c->seq[s];
   if (gamma) *gamma = q.gamma;

@@ -701,3 +701,57 @@ def test_capacity_errors_are_reported_not_faulted():
             break
     assert B.pacer_get_state(s.ctx, 0)["len"] + w["gamma_max"] + 2 > 64
     s.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid"])
+def test_prompt_token_outside_the_vocabulary_is_reported_not_faulted(name):
+    """Token ids live on the device, so the library cannot refuse a bad prompt up front.  No kernel may use such
+    an id as an index: the prompt copy replaces it by a valid id and flags the sequence, the step's first
+    read-back returns PACER_ENUMERIC, the sequence takes no further step, and a new prefill reopens it
+    (f32 path: tiny, bf16 path: mid)."""
+    from paper_2602_01274_amd import binding as B
+    w = synth.workload(name)
+    tgt, drf, mb = synth.make_pair(w, seed=0)
+    V = w["target"]["vocab"]
+    s = _session(w, tgt, drf, mb, 256)
+    good = synth.make_prompt(V, 20, 1).tolist()
+    for bad_id in (V + 7, -3, 2**31 - 1):
+        bad = list(good)
+        bad[5] = bad_id
+        s.prefill(bad)
+        with pytest.raises(B.PacerError) as e:
+            s.step(mode=B.GREEDY)
+        assert e.value.code == B.ENUMERIC, str(e.value)
+        with pytest.raises(B.PacerError) as e:
+            B.pacer_begin_step(s.ctx, 0)
+        assert e.value.code == B.ENUMERIC
+    s.prefill(good)
+    r = s.step(mode=B.GREEDY)
+    assert r["n"] >= 0 and 0 <= r["z"] < V
+    s.close()
+
+
+def test_logits_without_a_finite_value_are_reported_not_faulted():
+    """A draft model whose final norm gain holds a NaN produces logits with no finite value: the token choice has
+    no winner.  The chosen id must still be a valid index (the same kernel embeds it at once), and the step ends
+    with PACER_ENUMERIC instead of tokens; the same for a target model with such a gain."""
+    from paper_2602_01274_amd import binding as B
+    w = synth.workload("mid")
+    V = w["target"]["vocab"]
+    prompt = synth.make_prompt(V, 20, 1).tolist()
+    for which in ("draft", "target"):
+        tgt, drf, mb = synth.make_pair(w, seed=0)
+        m = drf if which == "draft" else tgt
+        m["final_norm"] = m["final_norm"].clone()
+        m["final_norm"][:] = float("nan")
+        s = _session(w, tgt, drf, mb, 256)
+        s.prefill(prompt)
+        for mode in (B.GREEDY, B.SAMPLE):
+            with pytest.raises(B.PacerError) as e:
+                s.step(mode=mode)
+            assert e.value.code == B.ENUMERIC, (which, mode, str(e.value))
+            torch.cuda.synchronize()
+            toks = s.draft_tokens(0)[:w["block"]]          # the drafts of the first block were made in either case
+            assert int(toks.min()) >= 0 and int(toks.max()) < V
+            s.prefill(prompt)
+        s.close()
