@@ -151,3 +151,37 @@ def test_accept_noalloc_against_oracle_on_scripted_logits(mode):
             if same and mode == B.SAMPLE:
                 assert ro["n"] == gamma          # p == q: every ratio is 1
     assert seen_bonus
+
+
+@pytest.mark.parametrize("mode", [B.GREEDY, B.SAMPLE])
+def test_accept_noalloc_bad_values_do_not_index_out_of_range(mode):
+    """The caller's buffers may hold anything.  A draft id outside the vocabulary is read as the nearest valid id
+    (so p[y] and q[y] stay inside their rows); logits without a finite value leave the next token at 0x7fffffff.
+    Neither may fault, and a sound call afterwards gives the result it gave before."""
+    V, gamma = 1000, 6
+    g = torch.Generator(device="cpu").manual_seed(3)
+    tl = torch.randn(gamma + 1, V, generator=g).cuda()
+    dl = torch.randn(gamma + 1, V, generator=g).cuda()
+    dt = tl[:gamma].argmax(dim=1).to(torch.int32)
+    stream = torch.cuda.current_stream().cuda_stream
+    out_n = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    out_z = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+
+    def run(t, d, y):
+        B.pacer_accept_noalloc(t, d, y, gamma, True, V, mode, 0.0, 5, 0, 0, out_n, out_z, stream)
+        torch.cuda.synchronize()
+        return int(out_n.item()), int(out_z.item())
+
+    ref = run(tl, dl, dt)
+    assert 0 <= ref[0] <= gamma and 0 <= ref[1] < V
+    for bad in (V, V + 12345, -1, 2**31 - 1):
+        y = dt.clone()
+        y[2] = bad
+        n, z = run(tl, dl, y)
+        assert 0 <= n <= gamma and 0 <= z < V
+        if mode == B.GREEDY:
+            assert n <= 2                              # an id no argmax can equal is rejected at the latest there
+    nan = torch.full_like(tl, float("nan"))
+    n, z = run(nan, dl, dt)
+    assert z == 0x7FFFFFFF and 0 <= n <= gamma
+    assert run(tl, dl, dt) == ref
