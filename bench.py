@@ -53,30 +53,36 @@ def run_steps(sess, n, mode, seed, batch=None, **kw):
                 mean_gamma=gam / max(cnt, 1), tau=acc / max(cnt, 1), reached=reached, accepted=accepted)
 
 
-def cpu_baseline(w, tgt, drf, mb, prompt, mode, budget_steps=2, threads=None):
+def cpu_baseline(w, tgt, drf, mb, prompt, mode, budget_s=10.0, threads=None):
     """The CPU oracle as it stands, on the host cores, on a bounded sample of the same workload: the
-    workload's full prompt (untimed, as on the GPU), then `budget_steps` decoding steps (timed)."""
+    workload's full prompt (untimed, as on the GPU), then decoding steps (timed) until the workload's number of
+    new tokens is reached (the small workloads run in full) or `budget_s` seconds have passed, two steps at least."""
     import numpy as np
     import helpers
     from threadpoolctl import threadpool_info, threadpool_limits
     ctl = threadpool_limits(limits=threads) if threads else None
     cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=3, max_seq=len(prompt) + 64)
+    want = int(w["new"])
+    o = helpers.build_oracle(w, tgt, drf, mb, mode=mode, seed=3, max_seq=len(prompt) + want + w["gamma_max"] + 64)
     t0 = time.perf_counter()
     o.prefill(prompt)
     t_prompt = time.perf_counter() - t0
     t0 = time.perf_counter()
-    toks = 0
-    for _ in range(budget_steps):
+    toks = steps = 0
+    while True:
         r = o.step()
         toks += r["n"] + 1
-    dt = time.perf_counter() - t0
+        steps += 1
+        dt = time.perf_counter() - t0
+        if toks >= want or (steps >= 2 and dt >= budget_s):
+            break
     if ctl is not None:
         ctl.restore_original_limits()
+    full = "the workload's full decode" if toks >= want else "a bounded sample"
     return {"value": toks / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{budget_steps} Pacer decoding steps ({toks} tokens, {dt:.1f} s, timed) of the same pair after the "
+            "sample": f"{steps} Pacer decoding steps ({toks} tokens, {dt:.1f} s, timed; {full}) of the same pair after the "
                       f"workload's full {len(prompt)}-token prompt ({t_prompt:.1f} s, untimed); numpy float64 oracle, "
-                      f"BLAS threads = cores"}
+                      f"{int(cores)} BLAS thread{'s' if cores != 1 else ''}"}
 
 
 def stream_ceiling(torch, B, shape=None, n_layers=None):
